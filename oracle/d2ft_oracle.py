@@ -1,0 +1,333 @@
+"""CPU fp64 oracle for the head-selective ViT block and the bi-level knapsack.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+GPU library is checked against.  It shares no code with the HIP path, and only
+the tests, the smoke check and the benchmark's cpu_baseline leg may import it.
+
+What it follows:
+  * Operation set P = {p_f full, p_o forward-only, p_s shortcut} and the
+    residual route (Sec. II-A.2 "Operation selection").
+  * Partition of a block into per-head subnets (Sec. II-A.1).
+  * KnapsackScheduling and DPSearching (Alg. 1 and Alg. 2, Sec. II-C), the
+    bi-level problem they solve (Eq. 4 and Eq. 5).
+  * The LoRA extension: per-head adapters, base frozen (Sec. II-D).
+  * The analytic cost rules (Sec. IV-A "Analysis of computational and
+    communicational cost").
+
+Readings taken where the paper is silent or garbled (each also listed in the
+design notes of the repository):
+  * p_o is a stop-gradient on the head's output: no weight gradient and no
+    input gradient flows through a forward-only head (it costs only a forward
+    pass and sends no backward message, Sec. IV-A).
+  * p_s removes the head's term from the concatenation, i.e. its Q/K/V
+    columns and its output-projection columns are dropped.
+  * The output-projection bias is added iff at least one head is live, so an
+    all-shortcut block leaves the attention residual untouched.
+  * LayerNorm uses the biased variance; GELU is the exact erf form.
+  * The feed-forward network is not gated here: it always runs forward and
+    backward.
+  * In DPSearching the item weight tested and subtracted in the fill phase is
+    the operation's own weight (W_p), as the backtracking phase uses; the
+    backtracking index decrements by one.
+  * An item is taken only where it strictly changes the table value.
+  * The two DP calls use separate capacities, as Alg. 1's inputs state; an
+    item chosen by both is p_f.
+
+All arithmetic is float64.  Every function is written as the definition, with
+loops over heads; there is no blocking, fusion or reordering.
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+from scipy.special import erf as _erf
+
+OP_FULL, OP_FWD, OP_SKIP = 1, 2, 3   # codes of the scheduling table, Alg. 1
+
+
+# ----------------------------------------------------------------------------
+# head compaction
+# ----------------------------------------------------------------------------
+def compact_heads(ops: Sequence[int]) -> Tuple[List[int], int, int]:
+    """Live-head list of one block: full heads ascending, then forward-only heads ascending.
+
+    Returns (live, n_full, n_live).  Shortcut heads do not appear.
+    (Sec. II-A.2: p_f and p_o run the forward pass, p_s bypasses the subnet.)
+    """
+    full, fwd = [], []
+    for h, code in enumerate(ops):
+        code = int(code)
+        if code == OP_FULL:
+            full.append(h)
+        elif code == OP_FWD:
+            fwd.append(h)
+        elif code != OP_SKIP:
+            raise ValueError(f"bad op code {code} at head {h}")
+    return full + fwd, len(full), len(full) + len(fwd)
+
+
+# ----------------------------------------------------------------------------
+# elementary pieces
+# ----------------------------------------------------------------------------
+def layer_norm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray, eps: float):
+    """Per-row LayerNorm with biased variance.  Returns (y, xhat, rstd)."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = (x - mu) * rstd
+    return xhat * gamma + beta, xhat, rstd
+
+
+def layer_norm_bwd(d: np.ndarray, xhat: np.ndarray, rstd: np.ndarray, gamma: np.ndarray):
+    """Gradient of layer_norm.  Returns (dx, dgamma, dbeta)."""
+    dhat = d * gamma
+    m1 = dhat.mean(axis=-1, keepdims=True)
+    m2 = (dhat * xhat).mean(axis=-1, keepdims=True)
+    dx = rstd * (dhat - m1 - xhat * m2)
+    D = d.shape[-1]
+    return dx, (d * xhat).reshape(-1, D).sum(axis=0), d.reshape(-1, D).sum(axis=0)
+
+
+def gelu(z: np.ndarray) -> np.ndarray:
+    return 0.5 * z * (1.0 + _erf(z / math.sqrt(2.0)))
+
+
+def gelu_grad(z: np.ndarray) -> np.ndarray:
+    cdf = 0.5 * (1.0 + _erf(z / math.sqrt(2.0)))
+    pdf = np.exp(-0.5 * z * z) / math.sqrt(2.0 * math.pi)
+    return cdf + z * pdf
+
+
+def _f64(a):
+    return None if a is None else np.asarray(a, dtype=np.float64)
+
+
+# ----------------------------------------------------------------------------
+# block forward
+# ----------------------------------------------------------------------------
+def block_fwd(w: Dict[str, Optional[np.ndarray]], ops: Sequence[int], x: np.ndarray,
+              head_dim: int, ln_eps: float = 1e-6, lora_scale: float = 1.0,
+              attn_const: Optional[np.ndarray] = None):
+    """Forward of one pre-LN block whose heads carry op codes.
+
+    x: [B, T, D].  w: arrays named as in the library's weight struct
+    (w_qkv [3,H,dh,D], b_qkv [3,H,dh], w_o [D,H*dh], b_o [D] or None, w1 [Dm,D],
+    w2 [D,Dm], optional lora_a_q/v [H,r,D], lora_b_q/v [H,dh,r]).
+    attn_const, if given, is a [B, T, D] constant added to the attention
+    residual; a test uses it to hold a forward-only head's output fixed while
+    it perturbs parameters (the stop-gradient reading of p_o).
+    Returns (y, cache); cache holds what block_bwd needs.
+    """
+    w = {k: _f64(v) for k, v in w.items()}
+    x = _f64(x)
+    B, T, D = x.shape
+    dh = head_dim
+    live, n_full, n_live = compact_heads(ops)
+    has_lora = w.get("lora_a_q") is not None
+    cache = {"x": x, "ops": list(int(o) for o in ops), "live": live, "n_full": n_full,
+             "heads": {}}
+
+    attn = np.zeros_like(x)
+    if n_live > 0:
+        u, xhat1, rstd1 = layer_norm(x, w["ln1_g"], w["ln1_b"], ln_eps)
+        cache.update(u=u, xhat1=xhat1, rstd1=rstd1)
+        for h in live:
+            q = u @ w["w_qkv"][0, h].T + w["b_qkv"][0, h]
+            k = u @ w["w_qkv"][1, h].T + w["b_qkv"][1, h]
+            v = u @ w["w_qkv"][2, h].T + w["b_qkv"][2, h]
+            if has_lora:
+                q = q + lora_scale * ((u @ w["lora_a_q"][h].T) @ w["lora_b_q"][h].T)
+                v = v + lora_scale * ((u @ w["lora_a_v"][h].T) @ w["lora_b_v"][h].T)
+            s = (q @ np.swapaxes(k, -1, -2)) / math.sqrt(dh)
+            s = s - s.max(axis=-1, keepdims=True)
+            e = np.exp(s)
+            p = e / e.sum(axis=-1, keepdims=True)
+            o = p @ v
+            contrib = o @ w["w_o"][:, h * dh:(h + 1) * dh].T
+            attn = attn + contrib
+            cache["heads"][h] = dict(q=q, k=k, v=v, p=p, o=o, contrib=contrib)
+        if w.get("b_o") is not None:
+            attn = attn + w["b_o"]
+        x1 = x + attn
+    else:
+        x1 = x.copy()
+    if attn_const is not None:
+        x1 = x1 + _f64(attn_const)
+
+    vv, xhat2, rstd2 = layer_norm(x1, w["ln2_g"], w["ln2_b"], ln_eps)
+    z = vv @ w["w1"].T + w["b1"]
+    g = gelu(z)
+    y = x1 + g @ w["w2"].T
+    if w.get("b2") is not None:
+        y = y + w["b2"]
+    cache.update(x1=x1, v=vv, xhat2=xhat2, rstd2=rstd2, z=z, g=g, head_dim=dh,
+                 lora_scale=lora_scale, has_lora=has_lora)
+    return y, cache
+
+
+# ----------------------------------------------------------------------------
+# block backward
+# ----------------------------------------------------------------------------
+def block_bwd(w: Dict[str, Optional[np.ndarray]], cache: dict, dy: np.ndarray):
+    """Backward of block_fwd given dy.  Returns (dx, grads).
+
+    grads has one array per weight field, the same shape as the weight.  Slices
+    that belong to forward-only or shortcut heads are exactly zero: p_o keeps
+    the forward pass but skips backward propagation, p_s skips both
+    (Sec. II-A.2), and the gradient reaches earlier blocks by the residual
+    route alone.
+    """
+    w = {k: _f64(v) for k, v in w.items()}
+    dy = _f64(dy)
+    x = cache["x"]
+    B, T, D = x.shape
+    dh = cache["head_dim"]
+    s_l = cache["lora_scale"]
+    live, n_full = cache["live"], cache["n_full"]
+    full = live[:n_full]
+    rows = lambda a: a.reshape(-1, a.shape[-1])
+
+    g = {k: (None if v is None else np.zeros_like(v)) for k, v in w.items()}
+
+    # feed-forward network (never gated here)
+    g["w2"] = rows(dy).T @ rows(cache["g"])
+    if w.get("b2") is not None:
+        g["b2"] = rows(dy).sum(axis=0)
+    dg = dy @ w["w2"]
+    dz = dg * gelu_grad(cache["z"])
+    g["w1"] = rows(dz).T @ rows(cache["v"])
+    g["b1"] = rows(dz).sum(axis=0)
+    dv = dz @ w["w1"]
+    dln2, g["ln2_g"], g["ln2_b"] = layer_norm_bwd(dv, cache["xhat2"], cache["rstd2"], w["ln2_g"])
+    dx1 = dy + dln2
+
+    # attention side
+    if len(live) > 0 and w.get("b_o") is not None:
+        g["b_o"] = rows(dx1).sum(axis=0)
+    if n_full == 0:
+        return dx1, g
+
+    u = cache["u"]
+    du = np.zeros_like(u)
+    for h in full:
+        c = cache["heads"][h]
+        q, k, v, p, o = c["q"], c["k"], c["v"], c["p"], c["o"]
+        wo_h = w["w_o"][:, h * dh:(h + 1) * dh]            # [D, dh]
+        do = dx1 @ wo_h                                    # [B,T,dh]
+        g["w_o"][:, h * dh:(h + 1) * dh] = rows(dx1).T @ rows(o)
+        dvh = np.swapaxes(p, -1, -2) @ do
+        dp = do @ np.swapaxes(v, -1, -2)
+        ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
+        dq = (ds @ k) / math.sqrt(dh)
+        dk = (np.swapaxes(ds, -1, -2) @ q) / math.sqrt(dh)
+        for which, dproj in ((0, dq), (1, dk), (2, dvh)):
+            g["w_qkv"][which, h] = rows(dproj).T @ rows(u)
+            g["b_qkv"][which, h] = rows(dproj).sum(axis=0)
+            du = du + dproj @ w["w_qkv"][which, h]
+        if cache["has_lora"]:
+            for name, dproj in (("q", dq), ("v", dvh)):
+                a, b = w[f"lora_a_{name}"][h], w[f"lora_b_{name}"][h]   # [r,D], [dh,r]
+                t = u @ a.T                                              # [B,T,r]
+                g[f"lora_b_{name}"][h] = s_l * (rows(dproj).T @ rows(t))
+                dt = s_l * (dproj @ b)                                   # [B,T,r]
+                g[f"lora_a_{name}"][h] = rows(dt).T @ rows(u)
+                du = du + dt @ a
+    dln1, g["ln1_g"], g["ln1_b"] = layer_norm_bwd(du, cache["xhat1"], cache["rstd1"], w["ln1_g"])
+    return dx1 + dln1, g
+
+
+# ----------------------------------------------------------------------------
+# stack of blocks
+# ----------------------------------------------------------------------------
+def stack_fwd(weights: List[dict], ops: np.ndarray, x: np.ndarray, head_dim: int,
+              ln_eps: float = 1e-6, lora_scale: float = 1.0):
+    caches, h = [], _f64(x)
+    for l, w in enumerate(weights):
+        h, c = block_fwd(w, ops[l], h, head_dim, ln_eps, lora_scale)
+        caches.append(c)
+    return h, caches
+
+
+def stack_bwd(weights: List[dict], caches: List[dict], dy: np.ndarray):
+    grads, d = [None] * len(weights), _f64(dy)
+    for l in range(len(weights) - 1, -1, -1):
+        d, grads[l] = block_bwd(weights[l], caches[l], d)
+    return d, grads
+
+
+# ----------------------------------------------------------------------------
+# bi-level knapsack scheduling (Alg. 1 and Alg. 2)
+# ----------------------------------------------------------------------------
+def dp_searching(scores: Sequence[float], weight: int, capacity: int) -> List[int]:
+    """0/1 knapsack of one subnet with one common item weight (Alg. 2).
+
+    Fill phase: T[0][w] = 0; T[i][w] = max(T[i-1][w], T[i-1][w-c] + a[i-1]) where
+    w >= c, else T[i-1][w].  Backtracking phase: from i = n, w = capacity, while
+    both are positive, take item i-1 iff T[i][w] differs from T[i-1][w].
+    Returns the 0/1 selection list.
+    """
+    n, c, C = len(scores), int(weight), int(capacity)
+    sel = [0] * n
+    if C < 0:
+        return sel
+    T = np.zeros((n + 1, C + 1), dtype=np.float64)
+    for i in range(1, n + 1):
+        a = float(scores[i - 1])
+        for wcap in range(0, C + 1):
+            if wcap >= c:
+                T[i][wcap] = max(T[i - 1][wcap], T[i - 1][wcap - c] + a)
+            else:
+                T[i][wcap] = T[i - 1][wcap]
+    i, wcap = n, C
+    while i > 0 and wcap > 0:
+        if T[i][wcap] != T[i - 1][wcap]:
+            sel[i - 1] = 1
+            wcap -= c
+        i -= 1
+    return sel
+
+
+def knapsack_scheduling(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, cap_fwd) -> np.ndarray:
+    """Scheduling table of Alg. 1: uint8 [K, n] with 1 = p_f, 2 = p_o, 3 = p_s.
+
+    Per subnet k: the outer problem (Eq. 4) picks p_f items by backward scores
+    with weight c^f_k + c^b_k under cap_full[k]; the inner problem (Eq. 5) picks
+    p_o items by forward scores with weight c^f_k under cap_fwd[k]; an item in
+    both is p_f, an item in neither is p_s.
+    """
+    score_full = np.asarray(score_full, dtype=np.float64)
+    score_fwd = np.asarray(score_fwd, dtype=np.float64)
+    K, n = score_full.shape
+    table = np.zeros((K, n), dtype=np.uint8)
+    for k in range(K):
+        w_b = int(cost_fwd[k]) + int(cost_bwd[k])
+        w_f = int(cost_fwd[k])
+        t_pf = dp_searching(score_full[k], w_b, int(cap_full[k]))
+        t_po = dp_searching(score_fwd[k], w_f, int(cap_fwd[k]))
+        for i in range(n):
+            if t_pf[i] == 1 and t_po[i] == 0:
+                table[k][i] = OP_FULL
+            if t_pf[i] == 0 and t_po[i] == 1:
+                table[k][i] = OP_FWD
+            if t_pf[i] == 1 and t_po[i] == 1:
+                table[k][i] = OP_FULL
+            if t_pf[i] == 0 and t_po[i] == 0:
+                table[k][i] = OP_SKIP
+    return table
+
+
+# ----------------------------------------------------------------------------
+# analytic cost rules (Sec. IV-A)
+# ----------------------------------------------------------------------------
+def compute_cost_fraction(n_full: int, n_fwd: int, n_skip: int, fwd_share: float = 0.4) -> float:
+    """Compute cost relative to all-full: p_o costs fwd_share of p_f, p_s costs nothing."""
+    n = n_full + n_fwd + n_skip
+    return (n_full + fwd_share * n_fwd) / n
+
+
+def comm_cost_fraction(n_full: int, n_fwd: int, n_skip: int) -> float:
+    """Communication relative to all-full: p_o sends only the forward message (half), p_s none."""
+    n = n_full + n_fwd + n_skip
+    return (n_full + 0.5 * n_fwd) / n
