@@ -1,0 +1,191 @@
+/*
+ * d2ft.h - C ABI of the head-selective ViT block library for AMD MI355X (gfx950).
+ *
+ * The library runs the forward and backward pass of pre-LN ViT transformer
+ * blocks in which every attention head carries an operation code for the
+ * current step, as defined in Sec. II-A.2 "Operation selection" of the D2FT
+ * paper (arXiv 2504.12471):
+ *     p_f  full          forward and backward
+ *     p_o  forward-only  forward, no backward (no weight gradient, and no
+ *                        gradient flows through the head: the residual route
+ *                        carries the gradient past it)
+ *     p_s  shortcut      nothing; the residual route carries activations
+ *                        forward and gradients backward
+ * and it selects those codes with the bi-level knapsack of Alg. 1
+ * (KnapsackScheduling) and Alg. 2 (DPSearching).
+ *
+ * Conventions that hold for every entry point
+ *   - Plain C types only.  Every tensor pointer is a DEVICE pointer unless the
+ *     parameter comment says HOST.  Tensors are row-major and contiguous.
+ *   - The caller owns every buffer.  The library allocates no device memory
+ *     and keeps no state between calls.
+ *   - Block calls are asynchronous on the given HIP stream (a hipStream_t
+ *     passed as void*; NULL is the default stream).
+ *   - Errors are return codes.  Arguments are validated before anything is
+ *     launched, so a call that returns D2FT_EINVAL or D2FT_ESHAPE has had no
+ *     effect.  D2FT_EDEVICE reports a HIP error of a launch or copy.
+ *   - Storage type is fp32 or bf16 for all tensors of a call; accumulation is
+ *     fp32.  LayerNorm statistics and softmax log-sum-exp are kept in fp32.
+ */
+#ifndef D2FT_H
+#define D2FT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    D2FT_OK = 0,
+    D2FT_EINVAL = 1,  /* NULL pointer, bad enum value, op code outside {1,2,3}, non-finite score */
+    D2FT_ESHAPE = 2,  /* non-positive or unsupported dimension, workspace too small */
+    D2FT_EDEVICE = 3  /* a HIP launch, copy or synchronisation failed */
+} d2ft_status;
+
+/* Operation codes, with the values of the scheduling table T_opt of Alg. 1. */
+enum { D2FT_OP_FULL = 1, D2FT_OP_FWD = 2, D2FT_OP_SKIP = 3 };
+
+typedef enum { D2FT_F32 = 0, D2FT_BF16 = 1 } d2ft_dtype;
+
+/* flags of d2ft_block_desc */
+enum {
+    /* 0: gradients are overwritten, and the slices of heads that are not p_f are
+     *    written as +0.0.  1: gradients are added to what the buffers hold, and
+     *    the slices of heads that are not p_f are left untouched. */
+    D2FT_FLAG_ACCUM_GRADS = 1u,
+    /* bf16 only: run the vector-ALU kernels instead of the MFMA kernels (a cross-check
+     * of the two kernel families; fp32 always runs on the vector ALUs). */
+    D2FT_FLAG_NO_MFMA = 2u
+};
+
+#define D2FT_MAX_HEADS 64
+#define D2FT_HEAD_DIM 64      /* the only supported head dimension */
+#define D2FT_MAX_LORA_RANK 64
+
+/* Shape of one block as held by this device.  heads*head_dim need not equal
+ * width: a device may hold a share of the model's heads (Sec. II-A.1
+ * "Partitioning strategy") and a share of the MLP's hidden units. */
+typedef struct d2ft_block_desc {
+    int32_t batch;       /* B >= 1 */
+    int32_t tokens;      /* T in [1, 1024] */
+    int32_t width;       /* D >= 8, multiple of 8 */
+    int32_t heads;       /* H in [1, D2FT_MAX_HEADS]: heads held by this call */
+    int32_t head_dim;    /* must be D2FT_HEAD_DIM */
+    int32_t mlp_hidden;  /* Dm >= 8, multiple of 8 */
+    int32_t lora_rank;   /* 0: no LoRA; else r in [1, D2FT_MAX_LORA_RANK] (Sec. II-D) */
+    float ln_eps;        /* LayerNorm epsilon (> 0) */
+    float lora_scale;    /* s in W_eff = W + s * B * A */
+    int32_t dtype;       /* d2ft_dtype */
+    uint32_t flags;      /* D2FT_FLAG_* */
+} d2ft_block_desc;
+
+/* Weights of one block (device pointers, storage type desc.dtype).
+ * Linear layers compute y = x W^T + b with W stored [out, in].
+ * Head h owns rows [h*64, h*64+64) of each of the three w_qkv planes and
+ * columns [h*64, h*64+64) of w_o: that slice is the attention part of the
+ * paper's subnet k = (l, h).  b_o and b2 may be NULL (a device that does not
+ * own the bias of a sharded layer).  lora_* are read only if lora_rank > 0;
+ * adapters sit on the query and value projections of each head. */
+typedef struct d2ft_block_weights {
+    const void *ln1_g, *ln1_b;   /* [D] */
+    const void *w_qkv;           /* [3][H][64][D]  planes: 0 = query, 1 = key, 2 = value */
+    const void *b_qkv;           /* [3][H][64] */
+    const void *w_o;             /* [D][H*64] */
+    const void *b_o;             /* [D] or NULL; added iff at least one head is live */
+    const void *ln2_g, *ln2_b;   /* [D] */
+    const void *w1, *b1;         /* [Dm][D], [Dm] */
+    const void *w2, *b2;         /* [D][Dm], [D] or NULL */
+    const void *lora_a_q, *lora_a_v; /* [H][r][D] */
+    const void *lora_b_q, *lora_b_v; /* [H][64][r] */
+} d2ft_block_weights;
+
+/* Gradient outputs, same shapes and storage type as the weights.  A NULL field
+ * means that gradient is not computed (LayerNorm parameters are frozen in the
+ * paper's setup, Sec. III-A; base weights are frozen under LoRA, Sec. II-D). */
+typedef struct d2ft_block_grads {
+    void *ln1_g, *ln1_b;
+    void *w_qkv, *b_qkv;
+    void *w_o, *b_o;
+    void *ln2_g, *ln2_b;
+    void *w1, *b1;
+    void *w2, *b2;
+    void *lora_a_q, *lora_a_v;
+    void *lora_b_q, *lora_b_v;
+} d2ft_block_grads;
+
+/* Bytes of the `saved` buffer that d2ft_block_fwd fills for d2ft_block_bwd, and
+ * of the `scratch` buffer either call may use; worst case over all masks.
+ * Both buffers must be 256-byte aligned.  Return 0 if the descriptor is invalid. */
+size_t d2ft_block_saved_bytes(const d2ft_block_desc *desc);
+size_t d2ft_block_scratch_bytes(const d2ft_block_desc *desc);
+
+/* Head compaction (host only, no GPU work).  From the op codes of one block
+ * build the live-head list: heads with p_f in ascending order, then heads with
+ * p_o in ascending order; p_s heads do not appear (Sec. II-A.2).
+ *   ops     HOST [heads]  codes 1/2/3
+ *   live    HOST [heads]  out: first *n_live entries are valid
+ *   n_full  HOST          out: number of p_f heads (a prefix of live)
+ *   n_live  HOST          out: number of p_f + p_o heads
+ * D2FT_EINVAL on NULL or a code outside {1,2,3}; D2FT_ESHAPE if heads is not in
+ * [1, D2FT_MAX_HEADS]. */
+d2ft_status d2ft_compact_heads(const uint8_t *ops, int32_t heads, int32_t *live,
+                               int32_t *n_full, int32_t *n_live);
+
+/* Forward of one block (Sec. II-A.2; block structure of Sec. III-A "Model"):
+ *   u  = LN1(x)                                   (skipped if no head is live)
+ *   for live heads h: [Q K V]_h = u W_{qkv,h}^T + b (+ LoRA), O_h = softmax(Q K^T / 8) V
+ *   x1 = x + sum_{live h} O_h W_{o,h}^T (+ b_o if any head is live)
+ *   y  = x1 + W2 GELU(W1 LN2(x1) + b1) + b2       (erf GELU; the MLP is never gated)
+ *   ops      HOST [heads]
+ *   x        [B][T][D] input hidden states
+ *   y        [B][T][D] output; must not alias x
+ *   saved    d2ft_block_saved_bytes(desc) bytes; opaque, consumed by d2ft_block_bwd
+ *   scratch  d2ft_block_scratch_bytes(desc) bytes; contents undefined afterwards */
+d2ft_status d2ft_block_fwd(const d2ft_block_desc *desc, const d2ft_block_weights *weights,
+                           const uint8_t *ops, const void *x, void *y, void *saved,
+                           void *scratch, void *hip_stream);
+
+/* Backward of one block, for the same desc, weights, ops and x that the forward
+ * call saw, and the `saved` buffer it filled.  Attention-side backward work
+ * runs for p_f heads only (Sec. II-A.2: p_o keeps the forward pass and skips
+ * backward propagation; the gradient goes by the residual route).
+ *   dy     [B][T][D] upstream gradient
+ *   dx     [B][T][D] out; must not alias dy
+ *   grads  HOST struct of device pointers; NULL fields are skipped.  Slices of
+ *          heads that are not p_f follow D2FT_FLAG_ACCUM_GRADS (see above). */
+d2ft_status d2ft_block_bwd(const d2ft_block_desc *desc, const d2ft_block_weights *weights,
+                           const uint8_t *ops, const void *x, const void *dy, void *dx,
+                           const d2ft_block_grads *grads, const void *saved, void *scratch,
+                           void *hip_stream);
+
+/* Bi-level knapsack selection of operation codes: Alg. 1 (KnapsackScheduling)
+ * calling Alg. 2 (DPSearching) twice per knapsack - p_f items by backward
+ * scores with weight c^f_k + c^b_k under cap_full[k] (outer problem, Eq. 4),
+ * p_o items by forward scores with weight c^f_k under cap_fwd[k] (inner problem,
+ * Eq. 5); an item selected by both is p_f, by neither p_s.  The DP runs on the
+ * GPU in fp64, one add and one compare per cell in the order the algorithm
+ * writes them.  The call synchronises the stream before it returns.
+ *   score_full, score_fwd  HOST [n_knapsacks][n_items], finite
+ *   cost_fwd   HOST [n_knapsacks]  c^f_k >= 1
+ *   cost_bwd   HOST [n_knapsacks]  c^b_k >= 0
+ *   cap_full, cap_fwd  HOST [n_knapsacks]  >= 0
+ *   ops_out    HOST [n_knapsacks][n_items]  out: codes 1/2/3
+ *   workspace  DEVICE, at least d2ft_knapsack_workspace_bytes(...) bytes, 256-byte aligned */
+size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items,
+                                     const int32_t *cap_full, const int32_t *cap_fwd);
+d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items,
+                                 const double *score_full, const double *score_fwd,
+                                 const int32_t *cost_fwd, const int32_t *cost_bwd,
+                                 const int32_t *cap_full, const int32_t *cap_fwd,
+                                 uint8_t *ops_out, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+
+/* Static description of a status code. */
+const char *d2ft_status_string(d2ft_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* D2FT_H */

@@ -1,0 +1,12 @@
+"""MI355X-native head-selective ViT block forward/backward (D2FT hot path).
+
+The package is a thin layer over libd2ft.so (hand-written HIP for gfx950):
+`binding` mirrors the C ABI of include/d2ft.h one to one, `stack` is the
+caller-side loop over blocks.  Importing the package requires the built
+library; there is no CPU or PyTorch fallback.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, FLAG_ACCUM_GRADS, FLAG_NO_MFMA, OP_FULL, OP_FWD, OP_SKIP, WEIGHT_FIELDS, BlockDesc, D2ftError,
+    d2ft_block_bwd, d2ft_block_fwd, d2ft_block_saved_bytes, d2ft_block_scratch_bytes, d2ft_compact_heads,
+    d2ft_knapsack_workspace_bytes, d2ft_select_knapsack, d2ft_status_string)
+from .stack import BlockStack, make_desc, to_device, torch_dtype  # noqa: F401

@@ -1,0 +1,179 @@
+"""ctypes binding of libd2ft.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+include/d2ft.h) and does nothing but turn torch tensors into device pointers,
+fill the C structs and check the status code.  There is no fallback: if the
+shared library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libd2ft.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2504_12471_amd.build` "
+        "(there is no CPU or PyTorch fallback for the HIP path)")
+_lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ESHAPE, EDEVICE = 0, 1, 2, 3
+OP_FULL, OP_FWD, OP_SKIP = 1, 2, 3
+F32, BF16 = 0, 1
+FLAG_ACCUM_GRADS, FLAG_NO_MFMA = 1, 2
+MAX_HEADS = 64
+
+WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",
+                 "w1", "b1", "w2", "b2", "lora_a_q", "lora_a_v", "lora_b_q", "lora_b_v")
+
+
+class BlockDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("tokens", C.c_int32), ("width", C.c_int32), ("heads", C.c_int32),
+                ("head_dim", C.c_int32), ("mlp_hidden", C.c_int32), ("lora_rank", C.c_int32),
+                ("ln_eps", C.c_float), ("lora_scale", C.c_float), ("dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+class _Ptrs(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in WEIGHT_FIELDS]
+
+
+class D2ftError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {d2ft_status_string(status)} (status {status})")
+
+
+_lib.d2ft_status_string.restype = C.c_char_p
+_lib.d2ft_status_string.argtypes = [C.c_int]
+_lib.d2ft_block_saved_bytes.restype = C.c_size_t
+_lib.d2ft_block_saved_bytes.argtypes = [C.POINTER(BlockDesc)]
+_lib.d2ft_block_scratch_bytes.restype = C.c_size_t
+_lib.d2ft_block_scratch_bytes.argtypes = [C.POINTER(BlockDesc)]
+_lib.d2ft_compact_heads.restype = C.c_int
+_lib.d2ft_compact_heads.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+_lib.d2ft_block_fwd.restype = C.c_int
+_lib.d2ft_block_fwd.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.d2ft_block_bwd.restype = C.c_int
+_lib.d2ft_block_bwd.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.POINTER(_Ptrs), C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.d2ft_knapsack_workspace_bytes.restype = C.c_size_t
+_lib.d2ft_knapsack_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.d2ft_select_knapsack.restype = C.c_int
+_lib.d2ft_select_knapsack.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+
+
+def d2ft_status_string(status: int) -> str:
+    return _lib.d2ft_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise D2ftError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to libd2ft must be contiguous")
+    return t.data_ptr()
+
+
+def _ptr_struct(tensors: Dict[str, Optional[torch.Tensor]]) -> _Ptrs:
+    s = _Ptrs()
+    for name in WEIGHT_FIELDS:
+        setattr(s, name, _ptr(tensors.get(name)))
+    return s
+
+
+def _ops_array(ops: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(ops, dtype=np.uint8))
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def d2ft_block_saved_bytes(desc: BlockDesc) -> int:
+    return int(_lib.d2ft_block_saved_bytes(C.byref(desc)))
+
+
+def d2ft_block_scratch_bytes(desc: BlockDesc) -> int:
+    return int(_lib.d2ft_block_scratch_bytes(C.byref(desc)))
+
+
+def d2ft_compact_heads(ops: Sequence[int]):
+    """Returns (live list, n_full, n_live)."""
+    a = _ops_array(ops)
+    live = np.zeros(max(1, a.size), dtype=np.int32)
+    nf, nl = C.c_int32(0), C.c_int32(0)
+    st = _lib.d2ft_compact_heads(a.ctypes.data, int(a.size), live.ctypes.data, C.byref(nf), C.byref(nl))
+    _check(st, "d2ft_compact_heads")
+    return live[:nl.value].tolist(), nf.value, nl.value
+
+
+def d2ft_block_fwd(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], ops: Sequence[int],
+                   x: torch.Tensor, y: torch.Tensor, saved: torch.Tensor, scratch: torch.Tensor,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    a = _ops_array(ops)
+    w = _ptr_struct(weights)
+    st = _lib.d2ft_block_fwd(C.byref(desc), C.byref(w), a.ctypes.data, _ptr(x), _ptr(y), _ptr(saved), _ptr(scratch),
+                             _stream_ptr(stream))
+    _check(st, "d2ft_block_fwd")
+
+
+def d2ft_block_bwd(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], ops: Sequence[int],
+                   x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, grads: Dict[str, Optional[torch.Tensor]],
+                   saved: torch.Tensor, scratch: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    a = _ops_array(ops)
+    w = _ptr_struct(weights)
+    g = _ptr_struct(grads)
+    st = _lib.d2ft_block_bwd(C.byref(desc), C.byref(w), a.ctypes.data, _ptr(x), _ptr(dy), _ptr(dx), C.byref(g),
+                             _ptr(saved), _ptr(scratch), _stream_ptr(stream))
+    _check(st, "d2ft_block_bwd")
+
+
+def d2ft_knapsack_workspace_bytes(n_knapsacks: int, n_items: int, cap_full, cap_fwd) -> int:
+    cf = np.ascontiguousarray(cap_full, dtype=np.int32)
+    co = np.ascontiguousarray(cap_fwd, dtype=np.int32)
+    return int(_lib.d2ft_knapsack_workspace_bytes(n_knapsacks, n_items, cf.ctypes.data, co.ctypes.data))
+
+
+def d2ft_select_knapsack(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, cap_fwd,
+                         workspace: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> np.ndarray:
+    """Returns the uint8 [n_knapsacks, n_items] table of op codes (host array)."""
+    sf = np.ascontiguousarray(score_full, dtype=np.float64)
+    so = np.ascontiguousarray(score_fwd, dtype=np.float64)
+    if sf.ndim != 2 or sf.shape != so.shape:
+        raise ValueError("scores must be two [n_knapsacks, n_items] arrays")
+    K, n = sf.shape
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (cost_fwd, cost_bwd, cap_full, cap_fwd)]
+    if any(a.shape != (K,) for a in arrs):
+        raise ValueError("costs and capacities must have one entry per knapsack")
+    cf, cb, capf, capo = arrs
+    need = int(_lib.d2ft_knapsack_workspace_bytes(K, n, capf.ctypes.data, capo.ctypes.data))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    out = np.zeros((K, n), dtype=np.uint8)
+    st = _lib.d2ft_select_knapsack(K, n, sf.ctypes.data, so.ctypes.data, cf.ctypes.data, cb.ctypes.data,
+                                   capf.ctypes.data, capo.ctypes.data, out.ctypes.data, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "d2ft_select_knapsack")
+    return out
+
+
+def exported_symbols():
+    """Names this binding resolves in the shared library (used by the load test)."""
+    return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
+            "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack"]

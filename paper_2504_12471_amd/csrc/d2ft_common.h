@@ -1,0 +1,185 @@
+// Internal declarations shared by the HIP sources of libd2ft (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/d2ft.h"
+
+namespace d2ft {
+
+typedef __bf16 bf16;
+
+constexpr int kWave = 64;        // CDNA wavefront width
+constexpr int kHeadDim = 64;
+constexpr int kMaxBlocks64 = 3 * D2FT_MAX_HEADS;   // 64-row blocks of a compacted QKV weight
+
+// ---------------------------------------------------------------------------
+// element access: storage type T (float or bf16), arithmetic in float
+// ---------------------------------------------------------------------------
+template <typename T> __device__ __forceinline__ float ld(const T* p) { return static_cast<float>(*p); }
+template <typename T> __device__ __forceinline__ void st(T* p, float v) { *p = static_cast<T>(v); }
+
+// 8 consecutive elements; p must be aligned to 8 elements
+__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16* p, float (&o)[8]) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[2 * i] = __uint_as_float(w[i] << 16);
+        o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    bf16x2_t t;
+    t[0] = static_cast<__bf16>(lo);
+    t[1] = static_cast<__bf16>(hi);
+    return __builtin_bit_cast(uint32_t, t);
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
+    uint4 r;
+    r.x = pack_bf16x2(v[0], v[1]);
+    r.y = pack_bf16x2(v[2], v[3]);
+    r.z = pack_bf16x2(v[4], v[5]);
+    r.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4*>(p) = r;
+}
+
+// ---------------------------------------------------------------------------
+// wavefront reductions (all 64 lanes take part and receive the result)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+// exact (erf) GELU and its derivative
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+    const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+    const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+    return cdf + z * pdf;
+}
+
+// ---------------------------------------------------------------------------
+// 64-granular index remap: a compacted index i maps to tbl[i / 64] + i % 64.
+// It turns "column c of the compacted live-head layout" into a row or column
+// of the full weight tensor.
+// ---------------------------------------------------------------------------
+struct Remap64 {
+    int32_t start[kMaxBlocks64];
+    __host__ __device__ __forceinline__ int operator()(int i) const { return start[i >> 6] + (i & 63); }
+};
+
+// ---------------------------------------------------------------------------
+// GEMM problem: C[m][n] = epilogue( sum_k A(m,k) * B(k,n) )
+//   A(m,k) = A[m*a_rs + k*a_cs],  B(k,n) = B[k*b_rs + n*b_cs]   (element strides)
+// ---------------------------------------------------------------------------
+enum { REMAP_NONE = 0, REMAP_B_N = 1, REMAP_B_K = 2 };
+enum { ACT_NONE = 0, ACT_GELU = 1, ACT_DGELU = 2 };
+
+struct GemmArgs {
+    const void* A;
+    const void* B;
+    void* C;
+    long a_rs, a_cs, b_rs, b_cs, ldc;
+    int M, N, K;
+    int remap;            // REMAP_*: which index of B goes through tbl
+    int bias_remap;       // bias index n goes through tbl
+    const void* bias;     // [N] or null
+    const void* residual; // [M][ldr] or null, added in the epilogue
+    long ldr;
+    int act;              // ACT_GELU: Z <- pre-activation, C <- gelu; ACT_DGELU: C <- acc * gelu'(Z)
+    void* Z;
+    long ldz;
+    float* partial;       // non-null: split-K mode, raw fp32 sums go to partial[split][M][N]
+    int splits;
+    Remap64 tbl;
+};
+
+// launchers (defined in the kernel sources); each returns hipGetLastError()
+hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
+// bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
+bool gemm_mfma_supported(const GemmArgs& g);
+
+hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean,
+                         float* rstd, int rows, int width, float eps, hipStream_t s);
+// dx = LNbwd(d) + res
+hipError_t launch_ln_bwd(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, const void* res, void* dx, int rows, int width, hipStream_t s);
+// partial_g/partial_b: [chunks][width] fp32 sums of d*xhat and d over row chunks
+hipError_t launch_ln_param_grad(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
+                                float* partial_g, float* partial_b, int rows, int width, int chunks, hipStream_t s);
+// partial: [chunks][cols] fp32 column sums over row chunks of X[rows][ld]
+hipError_t launch_colsum(int dtype, const void* X, long ld, int rows, int cols, float* partial, int chunks,
+                         hipStream_t s);
+
+enum { RED_REMAP_NONE = 0, RED_REMAP_ROWS = 1, RED_REMAP_COLS = 2 };
+// out[r'][c'] (=|+=) scale * sum_s partial[s][r][c], (r',c') through the remap
+hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, long slice_stride, int rows, int cols,
+                                  void* out, long ldo, int remap, const Remap64& tbl, int accumulate,
+                                  hipStream_t s);
+
+struct HeadList {
+    int32_t n;
+    uint8_t h[D2FT_MAX_HEADS];
+};
+// write +0.0 to every gradient slice of the listed heads (null pointers are skipped)
+hipError_t launch_zero_head_slices(int dtype, const HeadList& heads, int H, int D, int r, void* g_wqkv, void* g_bqkv,
+                                   void* g_wo, void* g_la_q, void* g_la_v, void* g_lb_q, void* g_lb_v,
+                                   hipStream_t s);
+
+// W_eff rows for compacted heads: out[(j*3+p)*64 + d][:] = W[p][live[j]][d][:] (+ s * B A for p in {query, value})
+hipError_t launch_lora_merge(int dtype, const void* w_qkv, const void* la_q, const void* la_v, const void* lb_q,
+                             const void* lb_v, void* out, const HeadList& live, int n_heads_used, int H, int D, int r,
+                             float scale, hipStream_t s);
+// LoRA gradients from G = dW_eff (fp32, compacted rows as in launch_lora_merge, split-K slices summed here):
+//   dB[h] (=|+=) s * G_h A_h^T,  dA[h] (=|+=) s * B_h^T G_h   for the query and value planes
+hipError_t launch_lora_project(int dtype, const float* G, int splits, long slice_stride, const void* la_q,
+                               const void* la_v, const void* lb_q, const void* lb_v, void* g_la_q, void* g_la_v,
+                               void* g_lb_q, void* g_lb_v, const HeadList& full, int H, int D, int r, float scale,
+                               int accumulate, hipStream_t s);
+
+// attention over compacted heads.  qkv: [rows][ldq], head j at columns j*192 (+0 Q, +64 K, +128 V);
+// o: [rows][ldo], head j at columns j*64; lse: [n_full][rows] (written for j < n_full only)
+hipError_t launch_attn_fwd_simple(int dtype, const void* qkv, long ldq, void* o, long ldo, float* lse, int batch,
+                                  int tokens, int n_live, int n_full, hipStream_t s);
+// d_o: [rows][ld_do] head j at j*64; dqkv: [rows][ld_dqkv] head j at j*192; delta: [n_full][rows] scratch
+hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, long ldq, const void* o, long ldo, const float* lse,
+                                  const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, int batch,
+                                  int tokens, int n_full, hipStream_t s);
+
+// bi-level knapsack (Alg. 1 + Alg. 2); all pointers are device pointers into the caller's workspace
+struct KnapsackArgs {
+    int n_knapsacks, n_items;
+    const double* score_full;   // [K][n]
+    const double* score_fwd;    // [K][n]
+    const int* cost_fwd;        // [K]
+    const int* cost_bwd;        // [K]
+    const int* cap_full;        // [K]
+    const int* cap_fwd;         // [K]
+    double* rows;               // [K*2 problems][2][stride]   two rows of the DP value table
+    uint8_t* changed;           // [K*2 problems][n][stride]   T[i][w] != T[i-1][w]
+    uint8_t* selected;          // [K*2 problems][n]           0/1 tables of the two stages
+    long stride;                // max capacity + 1, rounded up
+};
+hipError_t launch_knapsack(const KnapsackArgs& a, uint8_t* ops_dev, hipStream_t s);
+
+}  // namespace d2ft

@@ -1,0 +1,578 @@
+// C ABI entry points of libd2ft: argument validation, head compaction, buffer layout and the
+// launch sequence of one block's forward and backward pass.  All device work is in the
+// kernels_*.hip files; nothing here allocates device memory or keeps state between calls.
+#include <math.h>
+#include <string.h>
+
+#include "d2ft_common.h"
+
+namespace d2ft {
+
+namespace {
+
+constexpr int kMaxSplits = 8;
+constexpr int kColChunks = 32;
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline size_t elem_size(int dtype) { return dtype == D2FT_F32 ? 4 : 2; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Dims {
+    int B, T, D, H, Dm, r;
+    long M;
+    int dtype;
+    size_t es;
+};
+
+bool desc_ok(const d2ft_block_desc* d, d2ft_status* why) {
+    if (!d) { *why = D2FT_EINVAL; return false; }
+    if (d->dtype != D2FT_F32 && d->dtype != D2FT_BF16) { *why = D2FT_EINVAL; return false; }
+    if (!(d->ln_eps > 0.0f) || !isfinite(d->ln_eps) || !isfinite(d->lora_scale)) { *why = D2FT_EINVAL; return false; }
+    *why = D2FT_ESHAPE;
+    if (d->batch < 1 || d->tokens < 1 || d->tokens > 1024) return false;
+    if (d->width < 8 || d->width % 8) return false;
+    if (d->mlp_hidden < 8 || d->mlp_hidden % 8) return false;
+    if (d->heads < 1 || d->heads > D2FT_MAX_HEADS) return false;
+    if (d->head_dim != D2FT_HEAD_DIM) return false;
+    if (d->lora_rank < 0 || d->lora_rank > D2FT_MAX_LORA_RANK) return false;
+    if ((long)d->batch * d->tokens > (1L << 24)) return false;
+    *why = D2FT_OK;
+    return true;
+}
+
+Dims dims_of(const d2ft_block_desc* d) {
+    Dims s;
+    s.B = d->batch; s.T = d->tokens; s.D = d->width; s.H = d->heads; s.Dm = d->mlp_hidden; s.r = d->lora_rank;
+    s.M = (long)d->batch * d->tokens;
+    s.dtype = d->dtype;
+    s.es = elem_size(d->dtype);
+    return s;
+}
+
+// ---- layout of the saved buffer (forward -> backward) ----
+struct SavedLayout {
+    size_t mean1, rstd1, u, qkv, o, lse, x1, mean2, rstd2, v, z, g, total;
+};
+SavedLayout saved_layout(const Dims& s) {
+    SavedLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
+    L.mean1 = take(s.M * 4);
+    L.rstd1 = take(s.M * 4);
+    L.u = take(s.M * s.D * s.es);
+    L.qkv = take(s.M * s.H * 192 * s.es);
+    L.o = take(s.M * s.H * 64 * s.es);
+    L.lse = take((size_t)s.H * s.M * 4);
+    L.x1 = take(s.M * s.D * s.es);
+    L.mean2 = take(s.M * 4);
+    L.rstd2 = take(s.M * 4);
+    L.v = take(s.M * s.D * s.es);
+    L.z = take(s.M * s.Dm * s.es);
+    L.g = take(s.M * s.Dm * s.es);
+    L.total = off;
+    return L;
+}
+
+// ---- layout of the scratch buffer ----
+struct ScratchLayout {
+    size_t part, colpart, dz, dv, dx1, d_o, dqkv, du, delta, weff, total;
+    size_t part_floats;
+};
+ScratchLayout scratch_layout(const Dims& s) {
+    ScratchLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
+    size_t mat = (size_t)s.Dm * s.D;
+    if ((size_t)192 * s.H * s.D > mat) mat = (size_t)192 * s.H * s.D;
+    size_t cols = s.Dm;
+    if ((size_t)192 * s.H > cols) cols = 192 * s.H;
+    if ((size_t)s.D > cols) cols = s.D;
+    L.part_floats = mat * kMaxSplits;
+    L.part = take(L.part_floats * 4);
+    L.colpart = take(2 * kColChunks * cols * 4);
+    L.dz = take(s.M * s.Dm * s.es);
+    L.dv = take(s.M * s.D * s.es);
+    L.dx1 = take(s.M * s.D * s.es);
+    L.d_o = take(s.M * s.H * 64 * s.es);
+    L.dqkv = take(s.M * s.H * 192 * s.es);
+    L.du = take(s.M * s.D * s.es);
+    L.delta = take((size_t)s.H * s.M * 4);
+    L.weff = take(s.r > 0 ? (size_t)192 * s.H * s.D * s.es : 0);
+    L.total = off;
+    return L;
+}
+
+d2ft_status compact(const uint8_t* ops, int heads, int32_t* live, int32_t* n_full, int32_t* n_live) {
+    if (!ops || !live || !n_full || !n_live) return D2FT_EINVAL;
+    if (heads < 1 || heads > D2FT_MAX_HEADS) return D2FT_ESHAPE;
+    int nf = 0, nl = 0;
+    for (int h = 0; h < heads; ++h) {
+        if (ops[h] != D2FT_OP_FULL && ops[h] != D2FT_OP_FWD && ops[h] != D2FT_OP_SKIP) return D2FT_EINVAL;
+    }
+    for (int h = 0; h < heads; ++h)
+        if (ops[h] == D2FT_OP_FULL) live[nl++] = h;
+    nf = nl;
+    for (int h = 0; h < heads; ++h)
+        if (ops[h] == D2FT_OP_FWD) live[nl++] = h;
+    *n_full = nf;
+    *n_live = nl;
+    return D2FT_OK;
+}
+
+bool weights_ok(const d2ft_block_desc* d, const d2ft_block_weights* w) {
+    if (!w) return false;
+    const void* req[] = {w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o, w->ln2_g, w->ln2_b, w->w1, w->b1, w->w2};
+    for (const void* p : req)
+        if (!p || !aligned16(p)) return false;
+    if ((w->b_o && !aligned16(w->b_o)) || (w->b2 && !aligned16(w->b2))) return false;
+    if (d->lora_rank > 0) {
+        const void* lo[] = {w->lora_a_q, w->lora_a_v, w->lora_b_q, w->lora_b_v};
+        for (const void* p : lo)
+            if (!p || !aligned16(p)) return false;
+    }
+    return true;
+}
+
+// compacted-QKV remap: 64-row block j*3+p of the compacted weight is plane p, head live[j]
+void fill_qkv_table(Remap64& t, const int32_t* live, int n, int H) {
+    for (int j = 0; j < n; ++j)
+        for (int p = 0; p < 3; ++p) t.start[j * 3 + p] = (p * H + live[j]) * 64;
+}
+void fill_head_table(Remap64& t, const int32_t* live, int n) {
+    for (int j = 0; j < n; ++j) t.start[j] = live[j] * 64;
+}
+
+#define D2FT_TRY(expr)                          \
+    do {                                        \
+        hipError_t e__ = (expr);                \
+        if (e__ != hipSuccess) return D2FT_EDEVICE; \
+    } while (0)
+
+hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) {
+    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
+    return launch_gemm_simple(g, d->dtype, s);
+}
+
+GemmArgs gemm_base() {
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.splits = 1;
+    return g;
+}
+
+int pick_splits(long out_rows, long out_cols, long K) {
+    const long tiles = ((out_rows + 127) / 128) * ((out_cols + 127) / 128);
+    int s = 1;
+    while (s < kMaxSplits && tiles * s < 512 && K / (s * 2) >= 512) s *= 2;
+    return s;
+}
+
+int pick_chunks(long rows) {
+    long c = rows / 128;
+    if (c < 1) c = 1;
+    if (c > kColChunks) c = kColChunks;
+    return (int)c;
+}
+
+// weight gradient dW[out_rows][out_cols] = Aop^T Bop over the token rows, reduced through fp32 partials
+//   Aop: [M][lda] columns a_col0.. (out_rows of them), Bop: [M][ldb] columns (out_cols of them)
+d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop, long lda, const void* Bop, long ldb,
+                        int out_rows, int out_cols, float* part, void* out, long ldo, int red_remap,
+                        const Remap64& tbl, hipStream_t st, int* splits_out = nullptr, bool reduce = true) {
+    GemmArgs g = gemm_base();
+    g.A = Aop; g.a_rs = 1; g.a_cs = lda;      // A(m = out row, k = token) = Aop[token][m]
+    g.B = Bop; g.b_rs = ldb; g.b_cs = 1;      // B(k = token, n = out col) = Bop[token][n]
+    g.M = out_rows; g.N = out_cols; g.K = (int)s.M;
+    g.partial = part;
+    g.splits = pick_splits(out_rows, out_cols, s.M);
+    if (splits_out) *splits_out = g.splits;
+    D2FT_TRY(run_gemm(g, d, st));
+    if (reduce)
+        D2FT_TRY(launch_reduce_partials(s.dtype, part, g.splits, (long)out_rows * out_cols, out_rows, out_cols, out,
+                                        ldo, red_remap, tbl, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+    return D2FT_OK;
+}
+
+d2ft_status bias_grad(const d2ft_block_desc* d, const Dims& s, const void* X, long ldx, int cols, float* colpart,
+                      void* out, int red_remap, const Remap64& tbl, hipStream_t st) {
+    const int chunks = pick_chunks(s.M);
+    D2FT_TRY(launch_colsum(s.dtype, X, ldx, (int)s.M, cols, colpart, chunks, st));
+    D2FT_TRY(launch_reduce_partials(s.dtype, colpart, chunks, cols, 1, cols, out, cols, red_remap, tbl,
+                                    (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+    return D2FT_OK;
+}
+
+}  // namespace
+}  // namespace d2ft
+
+using namespace d2ft;
+
+extern "C" {
+
+const char* d2ft_status_string(d2ft_status status) {
+    switch (status) {
+        case D2FT_OK: return "ok";
+        case D2FT_EINVAL: return "invalid argument (null or misaligned pointer, bad enum, op code or score)";
+        case D2FT_ESHAPE: return "unsupported shape or workspace too small";
+        case D2FT_EDEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+size_t d2ft_block_saved_bytes(const d2ft_block_desc* desc) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    return saved_layout(dims_of(desc)).total;
+}
+
+size_t d2ft_block_scratch_bytes(const d2ft_block_desc* desc) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    return scratch_layout(dims_of(desc)).total;
+}
+
+d2ft_status d2ft_compact_heads(const uint8_t* ops, int32_t heads, int32_t* live, int32_t* n_full, int32_t* n_live) {
+    return compact(ops, heads, live, n_full, n_live);
+}
+
+d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
+                           const void* x, void* y, void* saved, void* scratch, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!weights_ok(desc, w) || !ops || !x || !y || !saved || !scratch || x == y) return D2FT_EINVAL;
+    if (!aligned16(x) || !aligned16(y) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
+    int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
+    d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
+    if (cs != D2FT_OK) return cs;
+
+    const Dims s = dims_of(desc);
+    const SavedLayout SL = saved_layout(s);
+    const ScratchLayout WL = scratch_layout(s);
+    char* sv = static_cast<char*>(saved);
+    char* ws = static_cast<char*>(scratch);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int M = (int)s.M;
+
+    const void* x1 = x;   // all heads shortcut: the attention residual is x itself
+    if (nl > 0) {
+        void* u = sv + SL.u;
+        D2FT_TRY(launch_ln_fwd(s.dtype, x, w->ln1_g, w->ln1_b, u, (float*)(sv + SL.mean1), (float*)(sv + SL.rstd1), M,
+                               s.D, desc->ln_eps, st));
+        // Q, K, V of the live heads only
+        GemmArgs g = gemm_base();
+        fill_qkv_table(g.tbl, live, nl, s.H);
+        g.A = u; g.a_rs = s.D; g.a_cs = 1;
+        g.M = M; g.N = nl * 192; g.K = s.D;
+        g.C = sv + SL.qkv; g.ldc = nl * 192;
+        g.bias = w->b_qkv; g.bias_remap = 1;
+        if (s.r > 0) {
+            HeadList hl; hl.n = nl;
+            for (int j = 0; j < nl; ++j) hl.h[j] = (uint8_t)live[j];
+            D2FT_TRY(launch_lora_merge(s.dtype, w->w_qkv, w->lora_a_q, w->lora_a_v, w->lora_b_q, w->lora_b_v,
+                                       ws + WL.weff, hl, nl, s.H, s.D, s.r, desc->lora_scale, st));
+            g.B = ws + WL.weff; g.b_rs = 1; g.b_cs = s.D; g.remap = REMAP_NONE;
+        } else {
+            g.B = w->w_qkv; g.b_rs = 1; g.b_cs = s.D; g.remap = REMAP_B_N;
+        }
+        D2FT_TRY(run_gemm(g, desc, st));
+        // softmax attention per (image, live head); log-sum-exp kept for p_f heads only
+        D2FT_TRY(launch_attn_fwd_simple(s.dtype, sv + SL.qkv, nl * 192, sv + SL.o, nl * 64, (float*)(sv + SL.lse), s.B,
+                                        s.T, nl, nf, st));
+        // x1 = x + O Wo_live^T + b_o
+        GemmArgs p = gemm_base();
+        fill_head_table(p.tbl, live, nl);
+        p.A = sv + SL.o; p.a_rs = nl * 64; p.a_cs = 1;
+        p.B = w->w_o; p.b_rs = 1; p.b_cs = (long)s.H * 64; p.remap = REMAP_B_K;
+        p.M = M; p.N = s.D; p.K = nl * 64;
+        p.C = sv + SL.x1; p.ldc = s.D;
+        p.bias = w->b_o;
+        p.residual = x; p.ldr = s.D;
+        D2FT_TRY(run_gemm(p, desc, st));
+        x1 = sv + SL.x1;
+    }
+    void* v = sv + SL.v;
+    D2FT_TRY(launch_ln_fwd(s.dtype, x1, w->ln2_g, w->ln2_b, v, (float*)(sv + SL.mean2), (float*)(sv + SL.rstd2), M, s.D,
+                           desc->ln_eps, st));
+    {   // z = v W1^T + b1, g = GELU(z)
+        GemmArgs g = gemm_base();
+        g.A = v; g.a_rs = s.D; g.a_cs = 1;
+        g.B = w->w1; g.b_rs = 1; g.b_cs = s.D;
+        g.M = M; g.N = s.Dm; g.K = s.D;
+        g.C = sv + SL.g; g.ldc = s.Dm;
+        g.bias = w->b1;
+        g.act = ACT_GELU; g.Z = sv + SL.z; g.ldz = s.Dm;
+        D2FT_TRY(run_gemm(g, desc, st));
+    }
+    {   // y = x1 + g W2^T + b2
+        GemmArgs g = gemm_base();
+        g.A = sv + SL.g; g.a_rs = s.Dm; g.a_cs = 1;
+        g.B = w->w2; g.b_rs = 1; g.b_cs = s.Dm;
+        g.M = M; g.N = s.D; g.K = s.Dm;
+        g.C = y; g.ldc = s.D;
+        g.bias = w->b2;
+        g.residual = x1; g.ldr = s.D;
+        D2FT_TRY(run_gemm(g, desc, st));
+    }
+    return D2FT_OK;
+}
+
+d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
+                           const void* x, const void* dy, void* dx, const d2ft_block_grads* grads, const void* saved,
+                           void* scratch, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!weights_ok(desc, w) || !ops || !x || !dy || !dx || !grads || !saved || !scratch || dy == dx)
+        return D2FT_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255))
+        return D2FT_EINVAL;
+    {
+        const void* gp[] = {grads->ln1_g, grads->ln1_b, grads->w_qkv, grads->b_qkv, grads->w_o, grads->b_o,
+                            grads->ln2_g, grads->ln2_b, grads->w1, grads->b1, grads->w2, grads->b2,
+                            grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v};
+        for (const void* p : gp)
+            if (p && !aligned16(p)) return D2FT_EINVAL;
+    }
+    int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
+    d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
+    if (cs != D2FT_OK) return cs;
+
+    const Dims s = dims_of(desc);
+    const SavedLayout SL = saved_layout(s);
+    const ScratchLayout WL = scratch_layout(s);
+    const char* sv = static_cast<const char*>(saved);
+    char* ws = static_cast<char*>(scratch);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int M = (int)s.M;
+    const int accum = (desc->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
+    float* part = (float*)(ws + WL.part);
+    float* colpart = (float*)(ws + WL.colpart);
+    Remap64 none;
+    memset(&none, 0, sizeof(none));
+    const void* x1 = nl > 0 ? (const void*)(sv + SL.x1) : x;
+    d2ft_status rc;
+
+    // ---- MLP (never gated) ----
+    if (grads->w2) {   // dW2 = dy^T g
+        rc = weight_grad(desc, s, dy, s.D, sv + SL.g, s.Dm, s.D, s.Dm, part, grads->w2, s.Dm, RED_REMAP_NONE, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    if (grads->b2 && w->b2) {
+        rc = bias_grad(desc, s, dy, s.D, s.D, colpart, grads->b2, RED_REMAP_NONE, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    {   // dz = (dy W2) * GELU'(z)
+        GemmArgs g = gemm_base();
+        g.A = dy; g.a_rs = s.D; g.a_cs = 1;
+        g.B = w->w2; g.b_rs = s.Dm; g.b_cs = 1;   // B(k = width index, n = hidden index) = W2[k][n]
+        g.M = M; g.N = s.Dm; g.K = s.D;
+        g.C = ws + WL.dz; g.ldc = s.Dm;
+        g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = s.Dm;
+        D2FT_TRY(run_gemm(g, desc, st));
+    }
+    if (grads->w1) {   // dW1 = dz^T v
+        rc = weight_grad(desc, s, ws + WL.dz, s.Dm, sv + SL.v, s.D, s.Dm, s.D, part, grads->w1, s.D, RED_REMAP_NONE, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    if (grads->b1) {
+        rc = bias_grad(desc, s, ws + WL.dz, s.Dm, s.Dm, colpart, grads->b1, RED_REMAP_NONE, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    {   // dv = dz W1
+        GemmArgs g = gemm_base();
+        g.A = ws + WL.dz; g.a_rs = s.Dm; g.a_cs = 1;
+        g.B = w->w1; g.b_rs = s.D; g.b_cs = 1;
+        g.M = M; g.N = s.D; g.K = s.Dm;
+        g.C = ws + WL.dv; g.ldc = s.D;
+        D2FT_TRY(run_gemm(g, desc, st));
+    }
+    if (grads->ln2_g || grads->ln2_b) {
+        const int chunks = pick_chunks(s.M);
+        float* pg = colpart;
+        float* pb = colpart + (size_t)kColChunks * s.D;
+        D2FT_TRY(launch_ln_param_grad(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2),
+                                      (const float*)(sv + SL.rstd2), pg, pb, M, s.D, chunks, st));
+        if (grads->ln2_g)
+            D2FT_TRY(launch_reduce_partials(s.dtype, pg, chunks, s.D, 1, s.D, grads->ln2_g, s.D, RED_REMAP_NONE, none, accum, st));
+        if (grads->ln2_b)
+            D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, accum, st));
+    }
+    // dx1 = dy + LN2bwd(dv); with no p_f head this already is dx (residual route only)
+    void* dx1 = (nf > 0) ? (void*)(ws + WL.dx1) : dx;
+    D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2), (const float*)(sv + SL.rstd2),
+                           w->ln2_g, dy, dx1, M, s.D, st));
+
+    // ---- attention side ----
+    if (grads->b_o && w->b_o && nl > 0) {
+        rc = bias_grad(desc, s, dx1, s.D, s.D, colpart, grads->b_o, RED_REMAP_NONE, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    // heads that are not p_f: gradient slices are +0.0 in overwrite mode, untouched in accumulate mode
+    if (!accum) {
+        HeadList nonfull; nonfull.n = 0;
+        for (int h = 0; h < s.H; ++h)
+            if (ops[h] != D2FT_OP_FULL) nonfull.h[nonfull.n++] = (uint8_t)h;
+        D2FT_TRY(launch_zero_head_slices(s.dtype, nonfull, s.H, s.D, s.r, grads->w_qkv, grads->b_qkv, grads->w_o,
+                                         grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v, st));
+        if (nl == 0 && grads->b_o && w->b_o) {   // bias was not applied: its gradient is zero
+            // a [1][D] "partial" of zero splits writes +0.0
+            D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->b_o, s.D, RED_REMAP_NONE, none, 0, st));
+        }
+        if (nf == 0) {
+            if (grads->ln1_g) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln1_g, s.D, RED_REMAP_NONE, none, 0, st));
+            if (grads->ln1_b) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, 0, st));
+        }
+    }
+    if (nf == 0) return D2FT_OK;
+
+    const long ldq = (long)nl * 192, ldo = (long)nl * 64;
+    const long ld_do = (long)nf * 64, ld_dq = (long)nf * 192;
+    Remap64 head_tbl, qkv_tbl;
+    memset(&head_tbl, 0, sizeof(head_tbl));
+    memset(&qkv_tbl, 0, sizeof(qkv_tbl));
+    fill_head_table(head_tbl, live, nf);
+    fill_qkv_table(qkv_tbl, live, nf, s.H);
+    {   // dO = dx1 Wo[:, p_f heads]
+        GemmArgs g = gemm_base();
+        g.tbl = head_tbl;
+        g.A = dx1; g.a_rs = s.D; g.a_cs = 1;
+        g.B = w->w_o; g.b_rs = (long)s.H * 64; g.b_cs = 1; g.remap = REMAP_B_N;
+        g.M = M; g.N = nf * 64; g.K = s.D;
+        g.C = ws + WL.d_o; g.ldc = ld_do;
+        D2FT_TRY(run_gemm(g, desc, st));
+    }
+    if (grads->w_o) {   // dWo[:, head cols] = dx1^T O_h
+        rc = weight_grad(desc, s, dx1, s.D, sv + SL.o, ldo, s.D, nf * 64, part, grads->w_o, (long)s.H * 64, RED_REMAP_COLS,
+                         head_tbl, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    D2FT_TRY(launch_attn_bwd_simple(s.dtype, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o,
+                                    ld_do, ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), s.B, s.T, nf, st));
+    const void* u = sv + SL.u;
+    const bool want_lora = s.r > 0 && (grads->lora_a_q || grads->lora_a_v || grads->lora_b_q || grads->lora_b_v);
+    if (grads->w_qkv || want_lora) {   // G = dQKV^T u, rows in compacted order
+        int splits = 1;
+        rc = weight_grad(desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D, RED_REMAP_ROWS, qkv_tbl,
+                         st, &splits, grads->w_qkv != nullptr);
+        if (rc != D2FT_OK) return rc;
+        if (want_lora) {
+            HeadList fl; fl.n = nf;
+            for (int j = 0; j < nf; ++j) fl.h[j] = (uint8_t)live[j];
+            D2FT_TRY(launch_lora_project(s.dtype, part, splits, (long)nf * 192 * s.D, w->lora_a_q, w->lora_a_v, w->lora_b_q,
+                                         w->lora_b_v, grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v,
+                                         fl, s.H, s.D, s.r, desc->lora_scale, accum, st));
+        }
+    }
+    if (grads->b_qkv) {
+        rc = bias_grad(desc, s, ws + WL.dqkv, ld_dq, nf * 192, colpart, grads->b_qkv, RED_REMAP_COLS, qkv_tbl, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    {   // du = dQKV W_eff (rows of the p_f heads)
+        GemmArgs g = gemm_base();
+        g.tbl = qkv_tbl;
+        g.A = ws + WL.dqkv; g.a_rs = ld_dq; g.a_cs = 1;
+        if (s.r > 0) {
+            HeadList fl; fl.n = nf;
+            for (int j = 0; j < nf; ++j) fl.h[j] = (uint8_t)live[j];
+            D2FT_TRY(launch_lora_merge(s.dtype, w->w_qkv, w->lora_a_q, w->lora_a_v, w->lora_b_q, w->lora_b_v,
+                                       ws + WL.weff, fl, nf, s.H, s.D, s.r, desc->lora_scale, st));
+            g.B = ws + WL.weff; g.remap = REMAP_NONE;
+        } else {
+            g.B = w->w_qkv; g.remap = REMAP_B_K;
+        }
+        g.b_rs = s.D; g.b_cs = 1;
+        g.M = M; g.N = s.D; g.K = nf * 192;
+        g.C = ws + WL.du; g.ldc = s.D;
+        D2FT_TRY(run_gemm(g, desc, st));
+    }
+    if (grads->ln1_g || grads->ln1_b) {
+        const int chunks = pick_chunks(s.M);
+        float* pg = colpart;
+        float* pb = colpart + (size_t)kColChunks * s.D;
+        D2FT_TRY(launch_ln_param_grad(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1),
+                                      (const float*)(sv + SL.rstd1), pg, pb, M, s.D, chunks, st));
+        if (grads->ln1_g)
+            D2FT_TRY(launch_reduce_partials(s.dtype, pg, chunks, s.D, 1, s.D, grads->ln1_g, s.D, RED_REMAP_NONE, none, accum, st));
+        if (grads->ln1_b)
+            D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, accum, st));
+    }
+    // dx = dx1 + LN1bwd(du)
+    D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1), (const float*)(sv + SL.rstd1), w->ln1_g,
+                           dx1, dx, M, s.D, st));
+    return D2FT_OK;
+}
+
+size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const int32_t* cap_full,
+                                     const int32_t* cap_fwd) {
+    if (n_knapsacks < 1 || n_items < 1 || !cap_full || !cap_fwd) return 0;
+    long cmax = 0;
+    for (int k = 0; k < n_knapsacks; ++k) {
+        if (cap_full[k] < 0 || cap_fwd[k] < 0) return 0;
+        if (cap_full[k] > cmax) cmax = cap_full[k];
+        if (cap_fwd[k] > cmax) cmax = cap_fwd[k];
+    }
+    const size_t stride = align256((size_t)cmax + 1);
+    const size_t probs = (size_t)n_knapsacks * 2;
+    size_t total = 0;
+    total += align256((size_t)n_knapsacks * n_items * 8) * 2;   // scores
+    total += align256((size_t)n_knapsacks * 4) * 4;             // costs, capacities
+    total += align256(probs * 2 * stride * 8);                  // two table rows per problem
+    total += align256(probs * n_items * stride);                // change flags
+    total += align256(probs * n_items);                         // 0/1 selections
+    total += align256((size_t)n_knapsacks * n_items);           // merged codes
+    return total;
+}
+
+d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items, const double* score_full,
+                                 const double* score_fwd, const int32_t* cost_fwd, const int32_t* cost_bwd,
+                                 const int32_t* cap_full, const int32_t* cap_fwd, uint8_t* ops_out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+    if (!score_full || !score_fwd || !cost_fwd || !cost_bwd || !cap_full || !cap_fwd || !ops_out || !workspace)
+        return D2FT_EINVAL;
+    if (n_knapsacks < 1 || n_items < 1) return D2FT_ESHAPE;
+    if ((uintptr_t)workspace & 255) return D2FT_EINVAL;
+    long cmax = 0;
+    for (int k = 0; k < n_knapsacks; ++k) {
+        if (cost_fwd[k] < 1 || cost_bwd[k] < 0 || cap_full[k] < 0 || cap_fwd[k] < 0) return D2FT_EINVAL;
+        if ((long)cost_fwd[k] + cost_bwd[k] > 0x3fffffff) return D2FT_EINVAL;
+        if (cap_full[k] > cmax) cmax = cap_full[k];
+        if (cap_fwd[k] > cmax) cmax = cap_fwd[k];
+    }
+    const size_t nsc = (size_t)n_knapsacks * n_items;
+    for (size_t i = 0; i < nsc; ++i)
+        if (!isfinite(score_full[i]) || !isfinite(score_fwd[i])) return D2FT_EINVAL;
+    const size_t need = d2ft_knapsack_workspace_bytes(n_knapsacks, n_items, cap_full, cap_fwd);
+    if (need == 0 || workspace_bytes < need) return D2FT_ESHAPE;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* at = ws + off; off += align256(bytes); return at; };
+    const size_t stride = align256((size_t)cmax + 1);
+    const size_t probs = (size_t)n_knapsacks * 2;
+    KnapsackArgs a;
+    a.n_knapsacks = n_knapsacks; a.n_items = n_items; a.stride = (long)stride;
+    double* d_sf = (double*)take(nsc * 8);
+    double* d_so = (double*)take(nsc * 8);
+    int* d_cf = (int*)take((size_t)n_knapsacks * 4);
+    int* d_cb = (int*)take((size_t)n_knapsacks * 4);
+    int* d_capf = (int*)take((size_t)n_knapsacks * 4);
+    int* d_capo = (int*)take((size_t)n_knapsacks * 4);
+    a.rows = (double*)take(probs * 2 * stride * 8);
+    a.changed = (uint8_t*)take(probs * n_items * stride);
+    a.selected = (uint8_t*)take(probs * n_items);
+    uint8_t* d_ops = (uint8_t*)take(nsc);
+    a.score_full = d_sf; a.score_fwd = d_so; a.cost_fwd = d_cf; a.cost_bwd = d_cb; a.cap_full = d_capf; a.cap_fwd = d_capo;
+
+    D2FT_TRY(hipMemcpyAsync(d_sf, score_full, nsc * 8, hipMemcpyHostToDevice, st));
+    D2FT_TRY(hipMemcpyAsync(d_so, score_fwd, nsc * 8, hipMemcpyHostToDevice, st));
+    D2FT_TRY(hipMemcpyAsync(d_cf, cost_fwd, (size_t)n_knapsacks * 4, hipMemcpyHostToDevice, st));
+    D2FT_TRY(hipMemcpyAsync(d_cb, cost_bwd, (size_t)n_knapsacks * 4, hipMemcpyHostToDevice, st));
+    D2FT_TRY(hipMemcpyAsync(d_capf, cap_full, (size_t)n_knapsacks * 4, hipMemcpyHostToDevice, st));
+    D2FT_TRY(hipMemcpyAsync(d_capo, cap_fwd, (size_t)n_knapsacks * 4, hipMemcpyHostToDevice, st));
+    D2FT_TRY(launch_knapsack(a, d_ops, st));
+    D2FT_TRY(hipMemcpyAsync(ops_out, d_ops, nsc, hipMemcpyDeviceToHost, st));
+    D2FT_TRY(hipStreamSynchronize(st));
+    return D2FT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,365 @@
+// LayerNorm forward/backward, column sums, split reductions, gradient-slice fills and the
+// small LoRA helpers.  All of these are bandwidth-bound: one wavefront owns one row and
+// reduces with cross-lane shuffles; column reductions write fp32 partials per row chunk and
+// a second kernel sums the partials in a fixed order, so results do not depend on timing.
+#include "d2ft_common.h"
+
+namespace d2ft {
+
+// ---------------------------------------------------------------------------
+// LayerNorm forward: y = (x - mean) * rstd * gamma + beta, biased variance
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ y,
+                                                     float* __restrict__ mean, float* __restrict__ rstd, int rows,
+                                                     int width, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const T* xr = x + (long)row * width;
+    float v[8];
+    float s = 0.f;
+    for (int c = lane * 8; c < width; c += 512) {
+        load8(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += v[i];
+    }
+    const float mu = wave_sum(s) / (float)width;
+    float q = 0.f;
+    for (int c = lane * 8; c < width; c += 512) {
+        load8(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float d = v[i] - mu;
+            q += d * d;
+        }
+    }
+    const float rs = 1.0f / sqrtf(wave_sum(q) / (float)width + eps);
+    T* yr = y + (long)row * width;
+    float g[8], b[8], o[8];
+    for (int c = lane * 8; c < width; c += 512) {
+        load8(xr + c, v);
+        load8(gamma + c, g);
+        load8(beta + c, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = (v[i] - mu) * rs * g[i] + b[i];
+        store8(yr + c, o);
+    }
+    if (lane == 0) {
+        mean[row] = mu;
+        rstd[row] = rs;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm backward wrt the input, plus a residual: dx = rstd*(dh - mean(dh) - xh*mean(dh*xh)) + res
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ d, const T* __restrict__ x,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     const T* __restrict__ gamma, const T* __restrict__ res,
+                                                     T* __restrict__ dx, int rows, int width) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const long off = (long)row * width;
+    const float mu = mean[row], rs = rstd[row];
+    float dv[8], xv[8], g[8];
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = lane * 8; c < width; c += 512) {
+        load8(d + off + c, dv);
+        load8(x + off + c, xv);
+        load8(gamma + c, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float dh = dv[i] * g[i];
+            s1 += dh;
+            s2 += dh * ((xv[i] - mu) * rs);
+        }
+    }
+    const float m1 = wave_sum(s1) / (float)width;
+    const float m2 = wave_sum(s2) / (float)width;
+    float r[8], o[8];
+    for (int c = lane * 8; c < width; c += 512) {
+        load8(d + off + c, dv);
+        load8(x + off + c, xv);
+        load8(gamma + c, g);
+        if (res) {
+            load8(res + off + c, r);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float xh = (xv[i] - mu) * rs;
+            o[i] = rs * (dv[i] * g[i] - m1 - xh * m2) + r[i];
+        }
+        store8(dx + off + c, o);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// column sums over a chunk of rows: block = 64 columns x 4 row lanes
+// ---------------------------------------------------------------------------
+template <typename T, bool LN>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, long ldx, const T* __restrict__ x,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     int rows, int cols, float* __restrict__ partial,
+                                                     float* __restrict__ partial2, int chunks) {
+    __shared__ float red[2][4][64];
+    const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + cl;
+    const int per = (rows + chunks - 1) / chunks;
+    const int r0 = blockIdx.y * per;
+    const int r1 = min(rows, r0 + per);
+    float a = 0.f, b = 0.f;
+    if (col < cols) {
+        for (int r = r0 + rg; r < r1; r += 4) {
+            const float dv = ld<T>(X + (long)r * ldx + col);
+            if (LN) {
+                const float xh = (ld<T>(x + (long)r * ldx + col) - mean[r]) * rstd[r];
+                a += dv * xh;
+                b += dv;
+            } else {
+                a += dv;
+            }
+        }
+    }
+    red[0][rg][cl] = a;
+    red[1][rg][cl] = b;
+    __syncthreads();
+    if (rg == 0 && col < cols) {
+        partial[(long)blockIdx.y * cols + col] = (red[0][0][cl] + red[0][1][cl]) + (red[0][2][cl] + red[0][3][cl]);
+        if (LN)
+            partial2[(long)blockIdx.y * cols + col] =
+                (red[1][0][cl] + red[1][1][cl]) + (red[1][2][cl] + red[1][3][cl]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// sum split partials in order and write (or add to) the output, with an optional remap
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int splits,
+                                                              long slice_stride, int rows, int cols,
+                                                              T* __restrict__ out, long ldo, int remap,
+                                                              int accumulate, Remap64 tbl) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)rows * cols) return;
+    const int r = (int)(idx / cols), c = (int)(idx % cols);
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += partial[k * slice_stride + idx];
+    const int ro = (remap == RED_REMAP_ROWS) ? tbl(r) : r;
+    const int co = (remap == RED_REMAP_COLS) ? tbl(c) : c;
+    T* o = out + (long)ro * ldo + co;
+    if (accumulate) s += ld<T>(o);
+    st<T>(o, s);
+}
+
+// ---------------------------------------------------------------------------
+// +0.0 into every gradient slice of the listed heads
+// ---------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void zero_span(T* base, long count, int tid, int nth) {
+    if (!base) return;
+    for (long i = tid; i < count; i += nth) base[i] = static_cast<T>(0.0f);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void zero_head_slices_kernel(HeadList heads, int H, int D, int r, T* g_wqkv,
+                                                               T* g_bqkv, T* g_wo, T* g_la_q, T* g_la_v, T* g_lb_q,
+                                                               T* g_lb_v) {
+    const int h = heads.h[blockIdx.y];
+    const int tid = blockIdx.x * 256 + threadIdx.x, nth = gridDim.x * 256;
+    for (int p = 0; p < 3; ++p) {
+        if (g_wqkv) zero_span(g_wqkv + ((long)(p * H + h) * 64) * D, (long)64 * D, tid, nth);
+        if (g_bqkv) zero_span(g_bqkv + (long)(p * H + h) * 64, 64, tid, nth);
+    }
+    if (g_wo) {
+        const long hd = (long)H * 64;
+        for (long i = tid; i < (long)D * 64; i += nth) g_wo[(i >> 6) * hd + h * 64 + (i & 63)] = static_cast<T>(0.0f);
+    }
+    if (r > 0) {
+        if (g_la_q) zero_span(g_la_q + (long)h * r * D, (long)r * D, tid, nth);
+        if (g_la_v) zero_span(g_la_v + (long)h * r * D, (long)r * D, tid, nth);
+        if (g_lb_q) zero_span(g_lb_q + (long)h * 64 * r, (long)64 * r, tid, nth);
+        if (g_lb_v) zero_span(g_lb_v + (long)h * 64 * r, (long)64 * r, tid, nth);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// LoRA: effective weights of the compacted heads (Sec. II-D: adapters on query and value)
+//   out[(j*3+p)*64 + d][k] = W[p][h][d][k] + scale * sum_i B_p[h][d][i] * A_p[h][i][k],  h = live[j]
+// one block per output row
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void lora_merge_kernel(const T* __restrict__ w_qkv, const T* __restrict__ la_q,
+                                                         const T* __restrict__ la_v, const T* __restrict__ lb_q,
+                                                         const T* __restrict__ lb_v, T* __restrict__ out,
+                                                         HeadList live, int H, int D, int r, float scale) {
+    const int row = blockIdx.x;
+    const int j = row / 192, p = (row % 192) / 64, d = row % 64;
+    const int h = live.h[j];
+    const T* wrow = w_qkv + ((long)(p * H + h) * 64 + d) * D;
+    const T* A = (p == 0) ? la_q : (p == 2 ? la_v : nullptr);
+    const T* B = (p == 0) ? lb_q : (p == 2 ? lb_v : nullptr);
+    T* orow = out + (long)row * D;
+    for (int k = threadIdx.x; k < D; k += 256) {
+        float v = ld<T>(wrow + k);
+        if (A) {
+            float acc = 0.f;
+            for (int i = 0; i < r; ++i) acc += ld<T>(B + ((long)h * 64 + d) * r + i) * ld<T>(A + ((long)h * r + i) * D + k);
+            v += scale * acc;
+        }
+        st<T>(orow + k, v);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// LoRA gradients from G = gradient of the effective weight (fp32 split partials):
+//   dB[h][d][i] = scale * sum_k G_h[d][k] A[h][i][k]
+//   dA[h][i][k] = scale * sum_d B[h][d][i] G_h[d][k]
+// grid (n_full, 2 planes); G rows of head j, plane p start at (j*3+p)*64
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void lora_project_kernel(const float* __restrict__ G, int splits, long slice_stride,
+                                                           const T* __restrict__ la_q, const T* __restrict__ la_v,
+                                                           const T* __restrict__ lb_q, const T* __restrict__ lb_v,
+                                                           T* g_la_q, T* g_la_v, T* g_lb_q, T* g_lb_v, HeadList full,
+                                                           int H, int D, int r, float scale, int accumulate) {
+    const int j = blockIdx.x, plane = blockIdx.y;   // plane 0: query, 1: value
+    const int p = plane == 0 ? 0 : 2;
+    const int h = full.h[j];
+    const T* A = (plane == 0 ? la_q : la_v) + (long)h * r * D;
+    const T* B = (plane == 0 ? lb_q : lb_v) + (long)h * 64 * r;
+    T* gA = plane == 0 ? g_la_q : g_la_v;
+    T* gB = plane == 0 ? g_lb_q : g_lb_v;
+    const float* Gh = G + ((long)(j * 3 + p) * 64) * D;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (gB) {
+        gB += (long)h * 64 * r;
+        for (int pair = wave; pair < 64 * r; pair += 4) {
+            const int d = pair / r, i = pair % r;
+            float acc = 0.f;
+            for (int k = lane; k < D; k += 64) {
+                float gsum = 0.f;
+                for (int s = 0; s < splits; ++s) gsum += Gh[s * slice_stride + (long)d * D + k];
+                acc += gsum * ld<T>(A + (long)i * D + k);
+            }
+            acc = wave_sum(acc) * scale;
+            if (lane == 0) {
+                if (accumulate) acc += ld<T>(gB + d * r + i);
+                st<T>(gB + d * r + i, acc);
+            }
+        }
+    }
+    if (gA) {
+        gA += (long)h * r * D;
+        for (int e = threadIdx.x; e < r * D; e += 256) {
+            const int i = e / D, k = e % D;
+            float acc = 0.f;
+            for (int d = 0; d < 64; ++d) {
+                float gsum = 0.f;
+                for (int s = 0; s < splits; ++s) gsum += Gh[s * slice_stride + (long)d * D + k];
+                acc += ld<T>(B + d * r + i) * gsum;
+            }
+            acc *= scale;
+            if (accumulate) acc += ld<T>(gA + e);
+            st<T>(gA + e, acc);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+#define D2FT_DISPATCH(dtype, ...)                  \
+    if ((dtype) == D2FT_F32) {                     \
+        typedef float T;                           \
+        __VA_ARGS__                                \
+    } else {                                       \
+        typedef bf16 T;                            \
+        __VA_ARGS__                                \
+    }
+
+hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean,
+                         float* rstd, int rows, int width, float eps, hipStream_t s) {
+    const dim3 grid((rows + 3) / 4), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(ln_fwd_kernel<T>, grid, block, 0, s, (const T*)x, (const T*)gamma,
+                                            (const T*)beta, (T*)y, mean, rstd, rows, width, eps);)
+    return hipGetLastError();
+}
+
+hipError_t launch_ln_bwd(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, const void* res, void* dx, int rows, int width, hipStream_t s) {
+    const dim3 grid((rows + 3) / 4), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(ln_bwd_kernel<T>, grid, block, 0, s, (const T*)d, (const T*)x, mean, rstd,
+                                            (const T*)gamma, (const T*)res, (T*)dx, rows, width);)
+    return hipGetLastError();
+}
+
+hipError_t launch_ln_param_grad(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
+                                float* partial_g, float* partial_b, int rows, int width, int chunks, hipStream_t s) {
+    const dim3 grid((width + 63) / 64, chunks), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL((colsum_kernel<T, true>), grid, block, 0, s, (const T*)d, (long)width,
+                                            (const T*)x, mean, rstd, rows, width, partial_g, partial_b, chunks);)
+    return hipGetLastError();
+}
+
+hipError_t launch_colsum(int dtype, const void* X, long ld, int rows, int cols, float* partial, int chunks,
+                         hipStream_t s) {
+    const dim3 grid((cols + 63) / 64, chunks), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL((colsum_kernel<T, false>), grid, block, 0, s, (const T*)X, ld,
+                                            (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, rows,
+                                            cols, partial, (float*)nullptr, chunks);)
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, long slice_stride, int rows, int cols,
+                                  void* out, long ldo, int remap, const Remap64& tbl, int accumulate,
+                                  hipStream_t s) {
+    const long total = (long)rows * cols;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(reduce_partials_kernel<T>, grid, block, 0, s, partial, splits,
+                                            slice_stride, rows, cols, (T*)out, ldo, remap, accumulate, tbl);)
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_head_slices(int dtype, const HeadList& heads, int H, int D, int r, void* g_wqkv, void* g_bqkv,
+                                   void* g_wo, void* g_la_q, void* g_la_v, void* g_lb_q, void* g_lb_v,
+                                   hipStream_t s) {
+    if (heads.n <= 0) return hipSuccess;
+    const dim3 grid(32, heads.n), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(zero_head_slices_kernel<T>, grid, block, 0, s, heads, H, D, r,
+                                            (T*)g_wqkv, (T*)g_bqkv, (T*)g_wo, (T*)g_la_q, (T*)g_la_v, (T*)g_lb_q,
+                                            (T*)g_lb_v);)
+    return hipGetLastError();
+}
+
+hipError_t launch_lora_merge(int dtype, const void* w_qkv, const void* la_q, const void* la_v, const void* lb_q,
+                             const void* lb_v, void* out, const HeadList& live, int n_heads_used, int H, int D, int r,
+                             float scale, hipStream_t s) {
+    if (n_heads_used <= 0) return hipSuccess;
+    const dim3 grid(n_heads_used * 192), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(lora_merge_kernel<T>, grid, block, 0, s, (const T*)w_qkv, (const T*)la_q,
+                                            (const T*)la_v, (const T*)lb_q, (const T*)lb_v, (T*)out, live, H, D, r,
+                                            scale);)
+    return hipGetLastError();
+}
+
+hipError_t launch_lora_project(int dtype, const float* G, int splits, long slice_stride, const void* la_q,
+                               const void* la_v, const void* lb_q, const void* lb_v, void* g_la_q, void* g_la_v,
+                               void* g_lb_q, void* g_lb_v, const HeadList& full, int H, int D, int r, float scale,
+                               int accumulate, hipStream_t s) {
+    if (full.n <= 0) return hipSuccess;
+    const dim3 grid(full.n, 2), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(lora_project_kernel<T>, grid, block, 0, s, G, splits, slice_stride,
+                                            (const T*)la_q, (const T*)la_v, (const T*)lb_q, (const T*)lb_v,
+                                            (T*)g_la_q, (T*)g_la_v, (T*)g_lb_q, (T*)g_lb_v, full, H, D, r, scale,
+                                            accumulate);)
+    return hipGetLastError();
+}
+
+}  // namespace d2ft

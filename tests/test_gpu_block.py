@@ -1,0 +1,171 @@
+"""GPU parity: libd2ft (through its C ABI) against the CPU fp64 oracle, element by element.
+
+Bar: bit-exact for op-code work (compaction, knapsack, zero gradient slices); per tensor
+max|gpu - oracle| / max|oracle| <= 1e-4 (fp32) or 2e-2 (bf16 storage, fp32 accumulate).
+For bf16 workloads the oracle consumes the bf16-rounded inputs promoted to fp64.
+"""
+import numpy as np
+import pytest
+
+import d2ft_inputs as di
+from helpers import TOL, compare_block, gpu_block, oracle_block, rel_inf
+
+pytestmark = pytest.mark.gpu
+
+FULL, FWD, SKIP = di.OP_FULL, di.OP_FWD, di.OP_SKIP
+
+
+def draw_block(w, seed):
+    rng = np.random.default_rng(seed)
+    x = di.draw_hidden(rng, w)
+    wt = di.draw_block_weights(rng, w)
+    dy = di.draw_hidden(rng, w)
+    return x, wt, dy
+
+
+def run_case(w, ops, seed=0, flags=0, grad_fields=None, tol=None):
+    x, wt, dy = draw_block(w, seed)
+    fields = di.WEIGHT_FIELDS if grad_fields is None else grad_fields
+    got = gpu_block(w, wt, ops, x, dy, fields, flags)
+    ref = oracle_block(w, wt, ops, x, dy)
+    rep = {}
+    compare_block(w, ops, got, ref, TOL[w.dtype] if tol is None else tol, fields, rep)
+    print(f"[{w.name} ops={list(ops)} flags={flags}] " + " ".join(f"{k}={v:.2e}" for k, v in rep.items()), flush=True)
+    return got, ref
+
+
+# ---------------------------------------------------------------------------
+# configuration 1: ViT-Tiny-shaped fp32 block, mask [full, fwd-only, skip]
+# ---------------------------------------------------------------------------
+def test_vit_tiny_fp32_block():
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    run_case(w, [FULL, FWD, SKIP])
+
+
+@pytest.mark.parametrize("ops", [(FULL, FULL, FULL), (SKIP, SKIP, SKIP), (FWD, FWD, FWD), (SKIP, FWD, FULL),
+                                 (FWD, SKIP, SKIP), (SKIP, FULL, SKIP)])
+def test_fp32_masks(ops):
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    run_case(w, list(ops), seed=1)
+
+
+def test_fp32_all_skip_is_residual_plus_mlp_bitwise():
+    """All-shortcut block: x1 is x itself, so y equals the all-skip run of a block with different attention weights."""
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    x, wt, dy = draw_block(w, 2)
+    y1, dx1, _ = gpu_block(w, wt, [SKIP] * 3, x, dy)
+    wt2 = dict(wt)
+    rng = np.random.default_rng(99)
+    for k in ("w_qkv", "b_qkv", "w_o", "b_o", "ln1_g", "ln1_b"):
+        wt2[k] = (rng.standard_normal(wt[k].shape) * 0.5).astype(np.float32)
+    y2, dx2, _ = gpu_block(w, wt2, [SKIP] * 3, x, dy)
+    assert np.array_equal(y1, y2) and np.array_equal(dx1, dx2)
+
+
+# ragged shapes: token count and widths that are not multiples of the tile sizes
+RAGGED = di.Workload("ragged_f32", 3, 37, 72, 5, 64, 136, 1, "f32")
+
+
+@pytest.mark.parametrize("ops", [(FULL, SKIP, FWD, FULL, FWD), (FWD, FULL, SKIP, SKIP, SKIP), (FULL,) * 5])
+def test_fp32_ragged(ops):
+    run_case(RAGGED, list(ops), seed=3)
+
+
+def test_single_token_single_head():
+    w = di.Workload("one", 1, 1, 64, 1, 64, 8, 1, "f32")
+    run_case(w, [FULL], seed=4)
+
+
+def test_null_bias_and_frozen_fields():
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    x, wt, dy = draw_block(w, 5)
+    wt["b_o"] = None
+    wt["b2"] = None
+    fields = ("w_qkv", "w_o", "w1", "b1")
+    ops = [FULL, FWD, FULL]
+    got = gpu_block(w, wt, ops, x, dy, fields)
+    ref = oracle_block(w, wt, ops, x, dy)
+    compare_block(w, ops, got, ref, TOL["f32"], fields)
+    assert got[2]["b_qkv"] is None and got[2]["w2"] is None
+
+
+def test_accumulate_mode_adds_and_leaves_non_full_slices():
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    x, wt, dy = draw_block(w, 6)
+    ops = [FULL, FWD, SKIP]
+    rng = np.random.default_rng(7)
+    init = {k: (rng.standard_normal(v.shape) * 0.1).astype(np.float32) for k, v in wt.items() if v is not None}
+    _, _, g = gpu_block(w, wt, ops, x, dy, di.WEIGHT_FIELDS, flags=1, grads_init=init)
+    _, _, rg, _ = oracle_block(w, wt, ops, x, dy)
+    for k, v in g.items():
+        if v is None:
+            continue
+        assert rel_inf(v, init[k] + rg[k]) < 1e-4, k
+    dh = w.head_dim
+    for h in (1, 2):   # not p_f: untouched, bit for bit
+        assert np.array_equal(g["w_qkv"][:, h], init["w_qkv"][:, h])
+        assert np.array_equal(g["b_qkv"][:, h], init["b_qkv"][:, h])
+        assert np.array_equal(g["w_o"][:, h * dh:(h + 1) * dh], init["w_o"][:, h * dh:(h + 1) * dh])
+
+
+# ---------------------------------------------------------------------------
+# LoRA (Sec. II-D)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_lora_block(dtype):
+    w = di.Workload("lora_" + dtype, 2, 33, 128, 4, 64, 256, 1, dtype, lora_rank=8, lora_scale=1.5,
+                    lora_b_zero=False)
+    run_case(w, [FULL, SKIP, FWD, FULL], seed=8)
+
+
+def test_lora_zero_b_and_frozen_base():
+    w = di.Workload("lora_frozen", 2, 33, 128, 4, 64, 256, 1, "f32", lora_rank=8, lora_b_zero=True)
+    fields = ("lora_a_q", "lora_a_v", "lora_b_q", "lora_b_v")
+    got, ref = run_case(w, [FULL, FULL, SKIP, FWD], seed=9, grad_fields=fields)
+    assert np.all(got[2]["lora_a_q"] == 0.0) and np.all(got[2]["lora_a_v"] == 0.0)
+
+
+# ---------------------------------------------------------------------------
+# bf16: both kernel families
+# ---------------------------------------------------------------------------
+SMALL_BF16 = di.Workload("small_bf16", 3, 70, 256, 4, 64, 512, 1, "bf16")
+MID_BF16 = di.Workload("mid_bf16", 5, 197, 384, 6, 64, 1536, 1, "bf16")   # ViT-Small block: several tiles + ragged tails
+
+
+@pytest.mark.parametrize("flags", [0, 2])
+@pytest.mark.parametrize("ops", [(FULL, FWD, SKIP, FULL), (FULL,) * 4, (SKIP,) * 4, (FWD, FWD, SKIP, FWD)])
+def test_bf16_small(ops, flags):
+    run_case(SMALL_BF16, list(ops), seed=10, flags=flags)
+
+
+@pytest.mark.parametrize("flags", [0, 2])
+def test_bf16_vit_small_block(flags):
+    run_case(MID_BF16, [FULL, FWD, SKIP, FULL, FULL, FWD], seed=11, flags=flags)
+
+
+def test_bf16_ragged_widths():
+    w = di.Workload("ragged_bf16", 2, 50, 200, 3, 64, 328, 1, "bf16")
+    run_case(w, [FWD, FULL, FULL], seed=12)
+
+
+# ---------------------------------------------------------------------------
+# stack of blocks
+# ---------------------------------------------------------------------------
+def test_small_stack_against_oracle():
+    import torch
+    import paper_2504_12471_amd as P
+    from oracle import d2ft_oracle as orc
+    w = di.Workload("stack_bf16", 4, 50, 256, 4, 64, 512, 3, "bf16", mask=("counts", 0.5, 0.25, 0.25))
+    s = di.draw_stack(w, seed=13)
+    desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype)
+    dws = [{k: P.to_device(v, w.dtype) for k, v in bw.items()} for bw in s.weights]
+    st = P.BlockStack(desc, dws, w.dtype)
+    y, dx = st.step(P.to_device(s.x, w.dtype), P.to_device(s.dy, w.dtype), s.ops)
+    torch.cuda.synchronize()
+    ry, caches = orc.stack_fwd(s.weights, s.ops, s.x, w.head_dim)
+    rdx, rgrads = orc.stack_bwd(s.weights, caches, s.dy)
+    assert rel_inf(y.float().cpu().numpy(), ry) < 2e-2
+    assert rel_inf(dx.float().cpu().numpy(), rdx) < 2e-2
+    for l in range(w.blocks):
+        for k in ("w_qkv", "w_o", "w1", "w2", "b1"):
+            assert rel_inf(st.grads[l][k].float().cpu().numpy(), rgrads[l][k]) < 2e-2, (l, k)
