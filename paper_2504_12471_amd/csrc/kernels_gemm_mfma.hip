@@ -1,5 +1,423 @@
+// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//
+//   C[m][n] = epilogue( sum_k A(m,k) * B(k,n) )
+//
+// One 256-thread workgroup (4 wavefronts, 2 x 2) owns a BM x BN tile of C; each wavefront owns
+// (BM/2) x (BN/2) of it as a grid of 32x32 MFMA tiles.  K is consumed BK at a time: the next
+// slab is fetched from global memory into registers while the current one is multiplied out of
+// LDS, then written to the other LDS buffer (one barrier per slab).
+//
+// Either operand may be stored with K contiguous ("row" form: A[m][k], B[n][k]) or with its
+// other index contiguous ("col" form: A[k][m], B[k][n]).  The MFMA wants 8 consecutive k per
+// lane.  Row-form slabs are stored in LDS as [index][k] and read with one 128-bit load per
+// fragment; col-form slabs are stored as [k][index] and read with two transposing LDS loads
+// (ds_read_b64_tr_b16), so no operand is ever transposed in global memory.
+//
+// B's n or k index may go through a 64-granular remap table: that is how the compacted
+// live-head list selects rows / columns of the full weight tensors without copying them.
 #include "d2ft_common.h"
+
 namespace d2ft {
-bool gemm_mfma_supported(const GemmArgs&) { return false; }
-hipError_t launch_gemm_mfma(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// LDS row strides (in bf16 elements), chosen so that the fragment reads are bank-conflict free
+template <int BK> constexpr int row_form_stride() { return BK + 8; }          // [index][k]: +16 bytes
+template <int BI> constexpr int col_form_stride() { return BI + 32; }         // [k][index]: +64 bytes
+
+template <int BI, int BK, bool COL> constexpr int slab_elems() {
+    return COL ? BK * col_form_stride<BI>() : BI * row_form_stride<BK>();
+}
+
+// ---- global -> registers: one slab of an operand, 16-byte chunks, zero fill outside the matrix ----
+// ROW form: element (i, k) at base + i*s_i + k          (k contiguous, s_k == 1)
+// COL form: element (i, k) at base + k*s_k + i          (i contiguous, s_i == 1)
+// Loads are raw buffer loads: a chunk outside the matrix gets an offset beyond the buffer's
+// declared size, for which the hardware returns zeros without touching memory, so there is no
+// branch and no select in the loop.  The part of the address that does not change from slab to
+// slab (the index part) is computed once.
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+constexpr uint32_t kBufBytes = 0x80000000u;   // declared buffer size; operands are checked to be smaller
+constexpr uint32_t kOutside = 0x80000000u;    // any offset >= kBufBytes reads as zero
+
+template <int BI, int BK, bool COL>
+struct SlabLoader {
+    static constexpr int kChunks = BI * BK / 8;
+    static constexpr int kPerThread = kChunks / kThreads;
+    static_assert(kChunks % kThreads == 0, "slab must divide over the workgroup");
+    static_assert(BK == 64, "the k remap is resolved once per slab, which needs 64-aligned slabs");
+    u32x4 v[kPerThread];
+    uint32_t base[kPerThread];   // byte offset of the chunk within slab 0, kOutside if its index is outside
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t sk_bytes;
+
+    static __device__ __forceinline__ int k_local(int c) {
+        const int id = threadIdx.x + c * kThreads;
+        return COL ? id / (BI / 8) : (id % (BK / 8)) * 8;
+    }
+
+    template <bool REMAP_I>
+    __device__ __forceinline__ void init(const bf16* p, long s_i, long s_k, int i0, int I, const Remap64& tbl) {
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(p), 0, kBufBytes, 0x00020000);
+        sk_bytes = (uint32_t)s_k * 2u;
+#pragma unroll
+        for (int c = 0; c < kPerThread; ++c) {
+            const int id = threadIdx.x + c * kThreads;
+            const int i = i0 + (COL ? (id % (BI / 8)) * 8 : id / (BK / 8));
+            const int is = REMAP_I ? tbl(min(i, I - 1)) : i;
+            const uint32_t off = ((uint32_t)is * (uint32_t)s_i + (uint32_t)k_local(c) * (uint32_t)s_k) * 2u;
+            base[c] = (i < I) ? off : kOutside;
+        }
+    }
+
+    // slab starting at k0 (a multiple of 64 counted from 0), valid k < k_end
+    template <bool REMAP_K>
+    __device__ __forceinline__ void load(int k0, int k_end, const Remap64& tbl) {
+        const uint32_t kstart = REMAP_K ? (uint32_t)tbl.start[k0 >> 6] : (uint32_t)k0;
+        const uint32_t koff = kstart * sk_bytes;   // uniform over the workgroup
+        const int left = k_end - k0;
+#pragma unroll
+        for (int c = 0; c < kPerThread; ++c) {
+            const uint32_t off = (k_local(c) < left) ? base[c] : kOutside;
+            v[c] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, koff, 0);
+        }
+    }
+
+    __device__ __forceinline__ void store(bf16* lds) const {
+#pragma unroll
+        for (int c = 0; c < kPerThread; ++c) {
+            const int id = threadIdx.x + c * kThreads;
+            int off;
+            if (COL) {
+                off = (id / (BI / 8)) * col_form_stride<BI>() + (id % (BI / 8)) * 8;
+            } else {
+                off = (id / (BK / 8)) * row_form_stride<BK>() + (id % (BK / 8)) * 8;
+            }
+            *reinterpret_cast<u32x4*>(lds + off) = v[c];
+        }
+    }
+};
+
+// ---- LDS -> MFMA operand fragment: rows i_base + lane%32, k = kk + 8*(lane/32) .. +7 ----
+template <int BI, int BK, bool COL>
+__device__ __forceinline__ bf16x8 read_fragment(const bf16* lds, int i_base, int kk, int lane) {
+    if (!COL) {
+        const bf16* p = lds + (i_base + (lane & 31)) * row_form_stride<BK>() + kk + 8 * (lane >> 5);
+        return *reinterpret_cast<const bf16x8*>(p);
+    } else {
+        // transposing read: a group of 16 lanes turns a 4 (k) x 16 (index) block into 4 consecutive k per lane;
+        // lane j of the group supplies the address of row k = j/4, columns 4*(j%4) .. +3
+        const int j = lane & 15;
+        const int i_blk = i_base + 16 * ((lane >> 4) & 1);
+        const int k_blk = kk + 8 * (lane >> 5);
+        const bf16* p = lds + (k_blk + (j >> 2)) * col_form_stride<BI>() + i_blk + 4 * (j & 3);
+        typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * col_form_stride<BI>()));
+        typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+        s16x8 r;
+        r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+        r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+        return __builtin_bit_cast(bf16x8, r);
+    }
+}
+
+// ---- GELU for the bf16 epilogues ----
+// Phi(z) through the rational-exponential erf approximation of Abramowitz & Stegun 7.1.26
+// (absolute error below 1.5e-7, far under bf16 resolution): one reciprocal, one exponential and
+// a degree-5 polynomial instead of the library erff.  e = exp(-z^2/2) is shared with the density.
+__device__ __forceinline__ void phi_parts(float z, float& cdf, float& e) {
+    const float x = fabsf(z) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+    e = __expf(-0.5f * z * z);
+    float p = 1.061405429f;
+    p = fmaf(p, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float q = 0.5f * p * t * e;          // 0.5 * (1 - erf(|z|/sqrt2))
+    cdf = z >= 0.f ? 1.0f - q : q;
+}
+__device__ __forceinline__ float gelu_fast(float z) {
+    float cdf, e;
+    phi_parts(z, cdf, e);
+    return z * cdf;
+}
+__device__ __forceinline__ float gelu_grad_fast(float z) {
+    float cdf, e;
+    phi_parts(z, cdf, e);
+    return cdf + z * 0.39894228040143267794f * e;
+}
+
+// ---- workgroup -> tile mapping ----
+// The chip has 8 XCDs with one L2 each and workgroup ids are dealt to them round-robin, so ids
+// with the same value mod 8 are renumbered to a contiguous range of tiles; inside that range
+// tiles are walked in groups of 8 tile rows so that the workgroups resident on one XCD share
+// A and B slabs through its L2.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, int& split) {
+    const int total = gridDim.x;
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, idx = pid >> 3;
+    const int lid = xcd * (total >> 3) + min(xcd, total & 7) + idx;
+    const int per_split = tiles_m * tiles_n;
+    split = lid / per_split;
+    const int rem = lid - split * per_split;
+    constexpr int GM = 8;
+    const int group = rem / (GM * tiles_n);
+    const int first = group * GM;
+    const int gsize = min(tiles_m - first, GM);
+    const int in_group = rem - group * GM * tiles_n;
+    tm = first + in_group % gsize;
+    tn = in_group / gsize;
+}
+
+template <int BM, int BN, int BK, bool A_COL, bool B_COL, int REMAP>
+__global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g) {
+    constexpr int WTM = BM / 2, WTN = BN / 2;   // wavefront tile
+    constexpr int MT = WTM / 32, NT = WTN / 32; // MFMA tiles per wavefront
+    constexpr int A_ELEMS = slab_elems<BM, BK, A_COL>();
+    constexpr int B_ELEMS = slab_elems<BN, BK, B_COL>();
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+    bf16* const As0 = smem;
+    bf16* const Bs0 = smem + A_ELEMS;
+    bf16* const As1 = smem + A_ELEMS + B_ELEMS;
+    bf16* const Bs1 = smem + 2 * A_ELEMS + B_ELEMS;
+
+    const bf16* __restrict__ A = static_cast<const bf16*>(g.A);
+    const bf16* __restrict__ B = static_cast<const bf16*>(g.B);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int tile_m, tile_n, split;
+    tile_of_block((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, tile_m, tile_n, split);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    int kb = 0, ke = g.K;
+    if (g.partial) {
+        int per = (g.K + g.splits - 1) / g.splits;
+        per = (per + BK - 1) / BK * BK;
+        kb = split * per;
+        ke = min(g.K, kb + per);
+    }
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][u][e] = 0.f;
+
+    SlabLoader<BM, BK, A_COL> la;
+    SlabLoader<BN, BK, B_COL> lb;
+    // strides as (index stride, k stride)
+    la.template init<false>(A, g.a_rs, g.a_cs, m0, g.M, g.tbl);
+    lb.template init<REMAP == REMAP_B_N>(B, g.b_cs, g.b_rs, n0, g.N, g.tbl);
+
+    const int nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
+    if (nslabs > 0) {
+        la.template load<false>(kb, ke, g.tbl);
+        lb.template load<REMAP == REMAP_B_K>(kb, ke, g.tbl);
+        la.store(As0);
+        lb.store(Bs0);
+    }
+    __syncthreads();
+
+    for (int s = 0; s < nslabs; ++s) {
+        const bool odd = s & 1;
+        const bool more = (s + 1 < nslabs);
+        if (more) {
+            const int k0 = kb + (s + 1) * BK;
+            la.template load<false>(k0, ke, g.tbl);
+            lb.template load<REMAP == REMAP_B_K>(k0, ke, g.tbl);
+        }
+        const bf16* as = odd ? As1 : As0;
+        const bf16* bs = odd ? Bs1 : Bs0;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8 af[MT], bfg[NT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) af[t] = read_fragment<BM, BK, A_COL>(as, wm * WTM + t * 32, kk, lane);
+#pragma unroll
+            for (int u = 0; u < NT; ++u) bfg[u] = read_fragment<BN, BK, B_COL>(bs, wn * WTN + u * 32, kk, lane);
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+                    acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bfg[u], acc[t][u], 0, 0, 0);
+        }
+        if (more) {
+            la.store(odd ? As0 : As1);
+            lb.store(odd ? Bs0 : Bs1);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue ----
+    // Accumulator element e of MFMA tile (t,u) is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+    // Each wavefront passes one 32-row band of its tile through its own LDS area (fp32) and reads it
+    // back 8 consecutive columns per lane, so bias / residual / activation operands are fetched and
+    // results stored as 16-byte rows.
+    constexpr int SST = WTN + 4;                 // stage row stride in floats
+    constexpr int CPR = WTN / 8;                 // 8-column chunks per stage row
+    constexpr int CPL = 32 * CPR / 64;           // chunks per lane
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * (32 * SST);
+    const int col_l = lane & 31, row_l = 4 * (lane >> 5);
+    bf16* __restrict__ C = static_cast<bf16*>(g.C);
+    const bf16* bias = static_cast<const bf16*>(g.bias);
+    const bf16* R = static_cast<const bf16*>(g.residual);
+    bf16* Z = static_cast<bf16*>(g.Z);
+    float* P = g.partial ? g.partial + (long)split * g.M * g.N : nullptr;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stage[(8 * (e >> 2) + row_l + (e & 3)) * SST + u * 32 + col_l] = acc[t][u][e];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+        for (int c = 0; c < CPL; ++c) {
+            const int id = lane + 64 * c;
+            const int r = id / CPR, cc = (id % CPR) * 8;
+            const int m = m0 + wm * WTM + t * 32 + r;
+            const int n = n0 + wn * WTN + cc;
+            if (m < g.M && n < g.N) {
+                float v[8];
+                const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
+                const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
+                v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+                if (P) {
+                    store8(P + (long)m * g.N + n, v);
+                } else {
+                    if (bias) {
+                        float b[8];
+                        load8(bias + (g.bias_remap ? g.tbl(n) : n), b);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] += b[i];
+                    }
+                    if (g.act == ACT_GELU) {
+                        bf16* zp = Z + (long)m * g.ldz + n;
+                        store8(zp, v);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] = gelu_fast(static_cast<float>(static_cast<bf16>(v[i])));
+                    } else if (g.act == ACT_DGELU) {
+                        float z[8];
+                        load8(Z + (long)m * g.ldz + n, z);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast(z[i]);
+                    }
+                    if (R) {
+                        float rr[8];
+                        load8(R + (long)m * g.ldr + n, rr);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] += rr[i];
+                    }
+                    store8(C + (long)m * g.ldc + n, v);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <int BM, int BN, int BK, bool A_COL, bool B_COL>
+constexpr size_t lds_bytes() {
+    constexpr size_t slabs = 2 * (slab_elems<BM, BK, A_COL>() + slab_elems<BN, BK, B_COL>()) * sizeof(bf16);
+    constexpr size_t stage = 4 * 32 * (BN / 2 + 4) * sizeof(float);
+    return slabs > stage ? slabs : stage;
+}
+
+template <int BM, int BN, int BK, bool A_COL, bool B_COL, int REMAP>
+hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
+    constexpr size_t lds = lds_bytes<BM, BN, BK, A_COL, B_COL>();
+    auto kern = gemm_mfma_kernel<BM, BN, BK, A_COL, B_COL, REMAP>;
+    static bool attr_set = false;   // per instantiation; setting it again is harmless
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int splits = g.partial ? g.splits : 1;
+    const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * splits;
+    const dim3 grid((unsigned)tiles), block(kThreads);
+    hipLaunchKernelGGL(kern, grid, block, lds, s, g);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int BK, bool A_COL, bool B_COL>
+hipError_t launch_remap(const GemmArgs& g, hipStream_t s) {
+    switch (g.remap) {
+        case REMAP_B_N: return launch_cfg<BM, BN, BK, A_COL, B_COL, REMAP_B_N>(g, s);
+        case REMAP_B_K: return launch_cfg<BM, BN, BK, A_COL, B_COL, REMAP_B_K>(g, s);
+        default: return launch_cfg<BM, BN, BK, A_COL, B_COL, REMAP_NONE>(g, s);
+    }
+}
+
+template <int BM, int BN, int BK>
+hipError_t launch_layout(const GemmArgs& g, hipStream_t s) {
+    const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
+    if (!a_col && !b_col) return launch_remap<BM, BN, BK, false, false>(g, s);
+    if (!a_col && b_col) return launch_remap<BM, BN, BK, false, true>(g, s);
+    if (a_col && b_col) return launch_remap<BM, BN, BK, true, true>(g, s);
+    return hipErrorNotSupported;
+}
+
+inline bool mult8(long v) { return (v & 7) == 0; }
+inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+int g_gemm_tile_override = 0;   // development aid: 0 = heuristic, 1 = 256x256, 2 = 128x128
+
+bool gemm_mfma_supported(const GemmArgs& g) {
+    if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
+    const bool a_row = (g.a_cs == 1), a_col = (g.a_rs == 1);
+    const bool b_row = (g.b_rs == 1), b_col = (g.b_cs == 1);
+    if (!(a_row || a_col) || !(b_row || b_col)) return false;
+    if (!a_row && b_row) return false;   // A col-form with B row-form is never needed
+    // 16-byte chunks: contiguous extents and leading strides must be multiples of 8 elements
+    if (a_row ? !(mult8(g.K) && mult8(g.a_rs)) : !(mult8(g.M) && mult8(g.a_cs))) return false;
+    if (b_row ? !(mult8(g.K) && mult8(g.b_cs)) : !(mult8(g.N) && mult8(g.b_rs))) return false;
+    if (!al16(g.A) || !al16(g.B)) return false;
+    if (!mult8(g.N)) return false;
+    // operands are addressed with 32-bit byte offsets below 2 GiB
+    const long a_span = a_row ? (long)g.M * g.a_rs : (long)g.K * g.a_cs;
+    long b_n = g.N, b_k = g.K;   // extents of B as stored (through the remap, if any)
+    if (g.remap != REMAP_NONE) {
+        const int nblk = ((g.remap == REMAP_B_N ? g.N : g.K) + 63) / 64;
+        if (nblk > kMaxBlocks64) return false;
+        long top = 0;
+        for (int i = 0; i < nblk; ++i) {
+            if (g.tbl.start[i] < 0) return false;
+            if (g.tbl.start[i] + 64 > top) top = g.tbl.start[i] + 64;
+        }
+        (g.remap == REMAP_B_N ? b_n : b_k) = top;
+    }
+    const long b_span = b_row ? b_n * g.b_cs : b_k * g.b_rs;
+    if (a_span * 2 >= (1L << 31) || b_span * 2 >= (1L << 31)) return false;
+    if (g.partial) return al16(g.partial);
+    if (!g.C || !al16(g.C) || !mult8(g.ldc)) return false;
+    if (g.bias && !al16(g.bias)) return false;
+    if (g.residual && (!al16(g.residual) || !mult8(g.ldr))) return false;
+    if (g.act != ACT_NONE && (!g.Z || !al16(g.Z) || !mult8(g.ldz))) return false;
+    return true;
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
+    if (!gemm_mfma_supported(g)) return hipErrorNotSupported;
+    // tile choice: the large tile when it still fills the chip, else the small one
+    const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * (g.partial ? g.splits : 1);
+    const bool use_big = g_gemm_tile_override ? (g_gemm_tile_override == 1) : (big >= 256);
+    if (use_big) return launch_layout<256, 256, 64>(g, s);
+    return launch_layout<128, 128, 64>(g, s);
+}
+
 }  // namespace d2ft
