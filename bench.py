@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the head-selective ViT block stack on one MI355X.
+
+One step = forward through all blocks, then backward through all blocks (every
+row of the hot path: LayerNorms, QKV / attention / output projection over the
+live heads, MLP, and the backward kernels for p_f heads), on seeded synthetic
+token batches that are resident in HBM before the timed region.
+
+Prints ONE JSON line: images/s for the configured head-op mask, the all-full
+mask beside it, the roofline of the dominant kernel (measured live with HIP
+events inside the library) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops(w, ops) -> float:
+    """FLOPs one step must do: skipped heads and the backward of non-full heads are not counted."""
+    import d2ft_inputs as di
+    M, D, T, dh, Dm, r = w.rows, w.width, w.tokens, w.head_dim, w.mlp_hidden, w.lora_rank
+    total = 0.0
+    for l in range(ops.shape[0]):
+        n_full = int((ops[l] == di.OP_FULL).sum())
+        n_live = n_full + int((ops[l] == di.OP_FWD).sum())
+        head_fwd = 4.0 * M * dh * (2 * D + T)
+        if w.train_base:
+            total += (n_live + 2 * n_full) * head_fwd + 12.0 * M * D * Dm
+        else:   # LoRA: no base weight gradients
+            lora_fwd = 4.0 * M * r * (D + dh)
+            total += n_live * (head_fwd + lora_fwd)
+            total += n_full * (8.0 * M * dh * (D + T) + 8.0 * M * r * (D + dh))
+            total += 8.0 * M * D * Dm
+    return total
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="vit_b16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-full", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one device's head share, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import d2ft_inputs as di
+    import paper_2504_12471_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = di.WORKLOADS[args.workload]
+    s = di.draw_stack(w, args.seed)
+    if s.ops is None:   # op codes chosen by the bi-level knapsack on the GPU
+        ks = s.knapsack
+        codes = P.d2ft_select_knapsack(ks.score_full, ks.score_fwd, ks.cost_fwd, ks.cost_bwd, ks.cap_full, ks.cap_fwd)
+        ops = codes.reshape(w.blocks, w.heads)
+    else:
+        ops = s.ops
+    full_ops = di.all_full_ops(w)
+
+    desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype, w.lora_rank, w.lora_scale,
+                       w.ln_eps, w.head_dim)
+    dws = [{k: P.to_device(v, w.dtype) for k, v in bw.items()} for bw in s.weights]
+    if w.train_base:
+        grad_fields = [k for k in P.WEIGHT_FIELDS if not k.startswith("ln")]   # norm layers frozen (Sec. III-A)
+    else:
+        grad_fields = ["lora_a_q", "lora_a_v", "lora_b_q", "lora_b_v"]
+    stack = P.BlockStack(desc, dws, w.dtype, grad_fields)
+    x, dy = P.to_device(s.x, w.dtype), P.to_device(s.dy, w.dtype)
+
+    def timed(mask, steps, warmup):
+        for _ in range(warmup):
+            stack.step(x, dy, mask)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            stack.step(x, dy, mask)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    ms = timed(ops, args.steps, args.warmup)
+    ms_full = None if args.no_all_full else timed(full_ops, args.steps, min(args.warmup, 1))
+
+    # per-kernel durations, measured with HIP events inside the library on the launch stream
+    stack.step(x, dy, ops)
+    torch.cuda.synchronize()
+    P.d2ft_timing_enable(True)
+    n_prof = 2
+    for _ in range(n_prof):
+        stack.step(x, dy, ops)
+    torch.cuda.synchronize()
+    kern = P.d2ft_timing_read(64)
+    P.d2ft_timing_enable(False)
+    kern.sort(key=lambda k: -k["ms"])
+    total_kernel_ms = sum(k["ms"] for k in kern) / n_prof
+    dom = kern[0]
+    dom_tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["flops"] > 0 else 0.0
+    gemm_ms = sum(k["ms"] for k in kern if k["flops"] > 0)
+    gemm_fl = sum(k["flops"] for k in kern if k["flops"] > 0)
+    roofline = {
+        "bound": "mfma", "kernel": dom["name"], "achieved": round(dom_tflops, 1), "peak": PEAK_BF16_TFLOPS,
+        "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+        "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2), "launches_per_step": dom["launches"] // n_prof,
+        "all_gemm_kernels_tflops": round(gemm_fl / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms > 0 else None,
+    }
+    kernels = [{"name": k["name"], "launches_per_step": k["launches"] // n_prof,
+                "ms_per_step": round(k["ms"] / n_prof, 4),
+                "tflops": round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 1) if k["flops"] > 0 else None} for k in kern]
+
+    flops = algorithmic_flops(w, ops)
+    out = {
+        "metric": "fine-tune step images/sec, ViT block stack with per-head op codes",
+        "value": round(w.batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic (seeded N(0,1) tokens, N(0,0.02^2) weights)",
+        "config": {"workload": w.name, "batch": w.batch, "tokens": w.tokens, "width": w.width, "heads": w.heads,
+                   "mlp_hidden": w.mlp_hidden, "blocks": w.blocks, "lora_rank": w.lora_rank,
+                   "heads_full": int((ops == di.OP_FULL).sum()), "heads_fwd_only": int((ops == di.OP_FWD).sum()),
+                   "heads_skipped": int((ops == di.OP_SKIP).sum())},
+        "algorithmic_tflop_per_step": round(flops / 1e12, 3),
+        "step_mfma_frac": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "all_full": None if ms_full is None else {
+            "ms_per_step": round(ms_full, 4), "images_per_s": round(w.batch / (ms_full * 1e-3), 1),
+            "masked_over_all_full_time": round(ms / ms_full, 4)},
+        "kernel_ms_per_step_sum": round(total_kernel_ms, 4),
+        "roofline": roofline,
+        "kernels": kernels[:12],
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on the host cores: block 0 of the same workload, forward + backward
+        from oracle import d2ft_oracle as orc
+        cores = os.cpu_count() or 1
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except Exception:
+            pass
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        t0 = time.perf_counter()
+        y, cache = orc.block_fwd(s.weights[0], ops[0], s.x, w.head_dim, w.ln_eps, w.lora_scale)
+        orc.block_bwd(s.weights[0], cache, s.dy)
+        t_block = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(w.batch / (t_block * w.blocks), 3), "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"block 0 of {w.blocks} at full shape, fp64 numpy, forward+backward once ({t_block:.1f} s); "
+                      f"step time extrapolated as {w.blocks} x that"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -182,6 +182,25 @@ d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items,
                                  uint8_t *ops_out, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
 
+/* Diagnostics: per-kernel timing.  While enabled, every kernel launch the library makes is
+ * bracketed by a pair of HIP events on the stream of the call (this adds host work per launch:
+ * do not time whole steps while it is on).  d2ft_timing_enable(1) clears earlier records and
+ * starts recording, d2ft_timing_enable(0) stops.  d2ft_timing_read waits for the recorded
+ * events and returns one entry per kernel class - launch count, summed duration, and the
+ * algorithmic FLOPs the launches stood for (GEMM classes: 2*M*N*K; 0 elsewhere) - or -1 on a
+ * HIP error.  The measurement backs the roofline figures of the benchmark (measurement of
+ * the paper's compute-cost claim of Sec. IV-A on this hardware).  Not thread safe.
+ *   out  HOST [max_entries] */
+typedef struct d2ft_kernel_time {
+    char name[64];
+    int64_t launches;
+    double ms;
+    double flops;
+    double bytes;
+} d2ft_kernel_time;
+d2ft_status d2ft_timing_enable(int32_t on);
+int32_t d2ft_timing_read(d2ft_kernel_time *out, int32_t max_entries);
+
 /* Static description of a status code. */
 const char *d2ft_status_string(d2ft_status status);
 

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libd2ft.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        f"{LIB_PATH} is missing: build it with `python -m paper_2504_12471_amd.build` "
+        f"{LIB_PATH} is missing: build it with `python paper_2504_12471_amd/build.py` "
         "(there is no CPU or PyTorch fallback for the HIP path)")
 _lib = C.CDLL(LIB_PATH)
 
@@ -68,6 +68,31 @@ _lib.d2ft_knapsack_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_void_p,
 _lib.d2ft_select_knapsack.restype = C.c_int
 _lib.d2ft_select_knapsack.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
+_lib.d2ft_timing_enable.restype = C.c_int
+_lib.d2ft_timing_enable.argtypes = [C.c_int32]
+_lib.d2ft_timing_read.restype = C.c_int32
+_lib.d2ft_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int32]
+
+
+def d2ft_timing_enable(on: bool) -> None:
+    _check(_lib.d2ft_timing_enable(1 if on else 0), "d2ft_timing_enable")
+
+
+def d2ft_timing_read(max_entries: int = 64):
+    """List of dicts (name, launches, ms, flops, bytes), one per kernel class."""
+    buf = (KernelTime * max_entries)()
+    n = _lib.d2ft_timing_read(buf, max_entries)
+    if n < 0:
+        raise D2ftError(EDEVICE, "d2ft_timing_read")
+    return [dict(name=buf[i].name.decode(), launches=int(buf[i].launches), ms=float(buf[i].ms),
+                 flops=float(buf[i].flops), bytes=float(buf[i].bytes)) for i in range(n)]
 
 
 def d2ft_status_string(status: int) -> str:
@@ -176,4 +201,5 @@ def d2ft_select_knapsack(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, ca
 def exported_symbols():
     """Names this binding resolves in the shared library (used by the load test)."""
     return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
-            "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack"]
+            "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
+            "d2ft_timing_enable", "d2ft_timing_read"]

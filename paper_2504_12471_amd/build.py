@@ -1,6 +1,6 @@
 """Build libd2ft.so (HIP, gfx950) in-tree with hipcc.
 
-    python -m paper_2504_12471_amd.build
+    python paper_2504_12471_amd/build.py
 
 Every .hip file under csrc/ is compiled to an object under _build/ and the
 objects are linked into paper_2504_12471_amd/libd2ft.so.  hipcc cross-compiles

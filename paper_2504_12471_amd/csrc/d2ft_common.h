@@ -118,6 +118,8 @@ hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
+// static string naming the kernel instantiation launch_gemm_mfma would pick (for timing records)
+const char* gemm_mfma_config_name(const GemmArgs& g);
 
 hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean,
                          float* rstd, int rows, int width, float eps, hipStream_t s);

@@ -4,6 +4,10 @@
 #include <math.h>
 #include <string.h>
 
+#include <map>
+#include <string>
+#include <vector>
+
 #include "d2ft_common.h"
 
 namespace d2ft {
@@ -142,14 +146,77 @@ void fill_head_table(Remap64& t, const int32_t* live, int n) {
     for (int j = 0; j < n; ++j) t.start[j] = live[j] * 64;
 }
 
-#define D2FT_TRY(expr)                          \
-    do {                                        \
-        hipError_t e__ = (expr);                \
+// ---- optional per-kernel timing (diagnostics; see d2ft_timing_enable in d2ft.h) ----
+struct TimingRec {
+    std::string label;
+    double flops, bytes;
+    hipEvent_t a, b;
+};
+struct TimingState {
+    bool on = false;
+    std::vector<TimingRec> recs;
+    std::vector<hipEvent_t> pool;
+    const char* label = nullptr;   // set by a launcher wrapper to refine the class of the next record
+    double flops = 0, bytes = 0;
+    bool open = false;
+};
+TimingState g_timing;
+constexpr size_t kMaxTimingRecs = 100000;
+
+hipEvent_t timing_event() {
+    if (!g_timing.pool.empty()) {
+        hipEvent_t e = g_timing.pool.back();
+        g_timing.pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void timing_begin(hipStream_t st, const char* what) {
+    g_timing.open = false;
+    if (!g_timing.on || g_timing.recs.size() >= kMaxTimingRecs) return;
+    TimingRec r;
+    const char* paren = strchr(what, '(');
+    r.label = paren ? std::string(what, paren - what) : std::string(what);
+    r.flops = r.bytes = 0;
+    r.a = timing_event();
+    r.b = timing_event();
+    if (!r.a || !r.b) return;
+    g_timing.label = nullptr;
+    g_timing.flops = g_timing.bytes = 0;
+    if (hipEventRecord(r.a, st) != hipSuccess) return;
+    g_timing.recs.push_back(r);
+    g_timing.open = true;
+}
+
+void timing_end(hipStream_t st) {
+    if (!g_timing.open) return;
+    TimingRec& r = g_timing.recs.back();
+    (void)hipEventRecord(r.b, st);
+    if (g_timing.label) r.label = g_timing.label;
+    r.flops = g_timing.flops;
+    r.bytes = g_timing.bytes;
+    g_timing.open = false;
+}
+
+// every launch site has the stream in a variable called st
+#define D2FT_TRY(expr)                              \
+    do {                                            \
+        timing_begin(st, #expr);                    \
+        hipError_t e__ = (expr);                    \
+        timing_end(st);                             \
         if (e__ != hipSuccess) return D2FT_EDEVICE; \
     } while (0)
 
 hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) {
-    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
+    g_timing.flops = 2.0 * g.M * g.N * g.K;
+    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) {
+        g_timing.label = gemm_mfma_config_name(g);
+        return launch_gemm_mfma(g, s);
+    }
+    g_timing.label = "gemm_simple";
     return launch_gemm_simple(g, d->dtype, s);
 }
 
@@ -208,6 +275,43 @@ d2ft_status bias_grad(const d2ft_block_desc* d, const Dims& s, const void* X, lo
 using namespace d2ft;
 
 extern "C" {
+
+d2ft_status d2ft_timing_enable(int32_t on) {
+    // finished records go back to the event pool
+    for (TimingRec& r : g_timing.recs) {
+        g_timing.pool.push_back(r.a);
+        g_timing.pool.push_back(r.b);
+    }
+    g_timing.recs.clear();
+    g_timing.on = on != 0;
+    g_timing.open = false;
+    return D2FT_OK;
+}
+
+int32_t d2ft_timing_read(d2ft_kernel_time* out, int32_t max_entries) {
+    if (!out || max_entries < 0) return -1;
+    std::map<std::string, d2ft_kernel_time> agg;
+    for (TimingRec& r : g_timing.recs) {
+        if (hipEventSynchronize(r.b) != hipSuccess) return -1;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return -1;
+        d2ft_kernel_time& k = agg[r.label];
+        if (k.launches == 0) {
+            memset(&k, 0, sizeof(k));
+            strncpy(k.name, r.label.c_str(), sizeof(k.name) - 1);
+        }
+        k.launches += 1;
+        k.ms += ms;
+        k.flops += r.flops;
+        k.bytes += r.bytes;
+    }
+    int32_t n = 0;
+    for (auto& kv : agg) {
+        if (n >= max_entries) break;
+        out[n++] = kv.second;
+    }
+    return n;
+}
 
 const char* d2ft_status_string(d2ft_status status) {
     switch (status) {

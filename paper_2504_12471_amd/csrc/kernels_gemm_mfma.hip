@@ -411,11 +411,24 @@ bool gemm_mfma_supported(const GemmArgs& g) {
     return true;
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
-    if (!gemm_mfma_supported(g)) return hipErrorNotSupported;
+static bool use_big_tile(const GemmArgs& g) {
     // tile choice: the large tile when it still fills the chip, else the small one
     const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * (g.partial ? g.splits : 1);
-    const bool use_big = g_gemm_tile_override ? (g_gemm_tile_override == 1) : (big >= 256);
+    return g_gemm_tile_override ? (g_gemm_tile_override == 1) : (big >= 256);
+}
+
+const char* gemm_mfma_config_name(const GemmArgs& g) {
+    const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
+    const int layout = a_col ? 2 : (b_col ? 1 : 0);
+    static const char* names[2][3] = {
+        {"gemm_mfma<128,128,64> A[m][k] B[n][k]", "gemm_mfma<128,128,64> A[m][k] B[k][n]", "gemm_mfma<128,128,64> A[k][m] B[k][n]"},
+        {"gemm_mfma<256,256,64> A[m][k] B[n][k]", "gemm_mfma<256,256,64> A[m][k] B[k][n]", "gemm_mfma<256,256,64> A[k][m] B[k][n]"}};
+    return names[use_big_tile(g) ? 1 : 0][layout];
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
+    if (!gemm_mfma_supported(g)) return hipErrorNotSupported;
+    const bool use_big = use_big_tile(g);
     if (use_big) return launch_layout<256, 256, 64>(g, s);
     return launch_layout<128, 128, 64>(g, s);
 }
