@@ -168,6 +168,14 @@ hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, long ldq, const vo
                                   const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, int batch,
                                   int tokens, int n_full, hipStream_t s);
 
+// MFMA attention (bf16, head dimension 64, up to 256 tokens); same argument meaning as the simple launchers
+bool attn_mfma_supported(int tokens, long ldq, long ldo);
+hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
+                                int n_live, int n_full, hipStream_t s);
+hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
+                                const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
+                                int n_full, hipStream_t s);
+
 // bi-level knapsack (Alg. 1 + Alg. 2); all pointers are device pointers into the caller's workspace
 struct KnapsackArgs {
     int n_knapsacks, n_items;

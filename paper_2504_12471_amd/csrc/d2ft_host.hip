@@ -220,6 +220,31 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
     return launch_gemm_simple(g, d->dtype, s);
 }
 
+hipError_t run_attn_fwd(const d2ft_block_desc* d, const void* qkv, long ldq, void* o, long ldo, float* lse, int batch,
+                        int tokens, int n_live, int n_full, hipStream_t s) {
+    g_timing.flops = 4.0 * batch * n_live * (double)tokens * tokens * 64;
+    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && attn_mfma_supported(tokens, ldq, ldo)) {
+        g_timing.label = "attn_fwd_mfma";
+        return launch_attn_fwd_mfma(qkv, ldq, o, ldo, lse, batch, tokens, n_live, n_full, s);
+    }
+    g_timing.label = "attn_fwd_simple";
+    return launch_attn_fwd_simple(d->dtype, qkv, ldq, o, ldo, lse, batch, tokens, n_live, n_full, s);
+}
+
+hipError_t run_attn_bwd(const d2ft_block_desc* d, const void* qkv, long ldq, const void* o, long ldo, const float* lse,
+                        const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, int batch, int tokens,
+                        int n_full, hipStream_t s) {
+    g_timing.flops = 8.0 * batch * n_full * (double)tokens * tokens * 64;
+    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && attn_mfma_supported(tokens, ldq, ldo) &&
+        (ld_do % 8) == 0 && (ld_dqkv % 8) == 0) {
+        g_timing.label = "attn_bwd_mfma";
+        return launch_attn_bwd_mfma(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, s);
+    }
+    g_timing.label = "attn_bwd_simple";
+    return launch_attn_bwd_simple(d->dtype, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, delta, batch, tokens, n_full,
+                                  s);
+}
+
 GemmArgs gemm_base() {
     GemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -380,8 +405,8 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         }
         D2FT_TRY(run_gemm(g, desc, st));
         // softmax attention per (image, live head); log-sum-exp kept for p_f heads only
-        D2FT_TRY(launch_attn_fwd_simple(s.dtype, sv + SL.qkv, nl * 192, sv + SL.o, nl * 64, (float*)(sv + SL.lse), s.B,
-                                        s.T, nl, nf, st));
+        D2FT_TRY(run_attn_fwd(desc, sv + SL.qkv, nl * 192, sv + SL.o, nl * 64, (float*)(sv + SL.lse), s.B, s.T, nl, nf,
+                              st));
         // x1 = x + O Wo_live^T + b_o
         GemmArgs p = gemm_base();
         fill_head_table(p.tbl, live, nl);
@@ -549,8 +574,8 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
                          head_tbl, st);
         if (rc != D2FT_OK) return rc;
     }
-    D2FT_TRY(launch_attn_bwd_simple(s.dtype, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o,
-                                    ld_do, ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), s.B, s.T, nf, st));
+    D2FT_TRY(run_attn_bwd(desc, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o, ld_do,
+                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), s.B, s.T, nf, st));
     const void* u = sv + SL.u;
     const bool want_lora = s.r > 0 && (grads->lora_a_q || grads->lora_a_v || grads->lora_b_q || grads->lora_b_v);
     if (grads->w_qkv || want_lora) {   // G = dQKV^T u, rows in compacted order

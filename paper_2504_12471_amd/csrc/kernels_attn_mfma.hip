@@ -1,0 +1,441 @@
+// Fused softmax attention on the CDNA4 matrix cores for head dimension 64 and up to 256 tokens
+// (bf16 storage, fp32 accumulate).  One 256-thread workgroup owns one (image, head); K and V of
+// that pair stay in LDS for the whole kernel.
+//
+// Everything is computed in the transposed orientation S^T = K Q^T so that, in the MFMA result
+// layout, one lane owns ONE query column: the row-wise softmax reductions are then in-lane plus a
+// single cross-lane exchange, and a lane's 8 consecutive accumulator elements are exactly the
+// 8 k-slots the next MFMA wants, so probabilities go from the S^T accumulators into the P.V
+// product without leaving registers.  Operands whose reduction index is not their contiguous
+// index (V in the forward pass; Q, K, dO in the backward pass) are read from their natural
+// [token][channel] layout with the transposing LDS load (ds_read_b64_tr_b16).
+//
+// MFMA 32x32x16 bf16 layouts used throughout (h = lane / 32, c = lane % 32):
+//   operand:  row-or-column c, k-slots 8h .. 8h+7
+//   result :  column c, element e <-> row 8*(e/4) + 4h + e%4
+#include "d2ft_common.h"
+
+namespace d2ft {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+namespace {
+
+constexpr float kScale = 0.125f;                         // 1/sqrt(64)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) z[e] = 0.f;
+    return z;
+}
+
+// row-form operand: 8 consecutive channels of row `row` starting at channel ch (16-byte LDS read)
+__device__ __forceinline__ bf16x8 frag_rows(const bf16* lds, int stride, int row, int ch) {
+    return *reinterpret_cast<const bf16x8*>(lds + row * stride + ch);
+}
+
+// transposed operand from a [token][channel] tile: the lane gets, for channel ch0 + c, the tokens
+// t0 + 4h + {0..3} (slots 0..3) and t0 + 8 + 4h + {0..3} (slots 4..7): the slot order in which a lane
+// holds 8 consecutive result elements of a transposed score tile.
+__device__ __forceinline__ bf16x8 frag_tr(const bf16* lds, int stride, int t0, int ch0, int lane) {
+    const int j = lane & 15;
+    const bf16* p = lds + (t0 + 4 * (lane >> 5) + (j >> 2)) * stride + ch0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 8 * stride));
+    s16x8 r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// 8 consecutive result elements -> bf16 operand
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = static_cast<__bf16>(v[first + i]);
+    return r;
+}
+
+// copy rows [0, rows_valid) x 64 channels of a [token][ld] global tile to LDS rows of `stride`, zero rows above
+template <int TP>
+__device__ __forceinline__ void load_tile64(const bf16* __restrict__ g, long ld, int rows_valid, bf16* lds, int stride) {
+    for (int c = threadIdx.x; c < TP * 8; c += 256) {
+        const int r = c >> 3, ch = (c & 7) * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r < rows_valid) v = *reinterpret_cast<const u32x4*>(g + (long)r * ld + ch);
+        *reinterpret_cast<u32x4*>(lds + r * stride + ch) = v;
+    }
+}
+
+constexpr int kKS = 72;   // K rows in LDS: 144 bytes (row-form reads)
+constexpr int kVS = 96;   // V rows in LDS: 192 bytes (transposing reads)
+
+// ---------------------------------------------------------------------------
+// forward: O = softmax(Q K^T / 8) V per (image, live head); log-sum-exp saved for p_f heads
+// ---------------------------------------------------------------------------
+template <int KT>   // number of 32-token tiles
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
+                                                            bf16* __restrict__ o, long ldo, float* __restrict__ lse,
+                                                            int tokens, int n_live, int n_full, long rows_total) {
+    constexpr int TP = KT * 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* Ks = reinterpret_cast<bf16*>(smem_raw);
+    bf16* Vs = Ks + TP * kKS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int b = blockIdx.x / n_live, j = blockIdx.x % n_live;
+    const long row0 = (long)b * tokens;
+    const bf16* Qb = qkv + row0 * ldq + j * 192;
+    load_tile64<TP>(Qb + 64, ldq, tokens, Ks, kKS);
+    load_tile64<TP>(Qb + 128, ldq, tokens, Vs, kVS);
+    __syncthreads();
+
+    for (int qt = wave; qt < KT; qt += 4) {
+        const int q = qt * 32 + c;
+        const bool q_ok = q < tokens;
+        bf16x8 qf[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (q_ok) v = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + kk * 16 + 8 * h);
+            qf[kk] = __builtin_bit_cast(bf16x8, v);
+        }
+        // S^T tiles: rows = keys of tile u, column = this lane's query
+        f32x16 s[KT];
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            s[u] = zero16();
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kKS, u * 32 + c, kk * 16 + 8 * h), qf[kk],
+                                                               s[u], 0, 0, 0);
+        }
+        float m = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < KT; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = u * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+                const float v = key < tokens ? s[u][e] : -INFINITY;
+                s[u][e] = v;
+                m = fmaxf(m, v);
+            }
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        const float cexp = kScale * kLog2e;
+        float sum = 0.f;
+#pragma unroll
+        for (int u = 0; u < KT; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = __builtin_amdgcn_exp2f((s[u][e] - m) * cexp);
+                s[u][e] = p;
+                sum += p;
+            }
+        sum += __shfl_xor(sum, 32, 64);
+        // O^T = V^T P^T: rows = channels, column = this lane's query
+        f32x16 ot[2] = {zero16(), zero16()};
+#pragma unroll
+        for (int u = 0; u < KT; ++u)
+#pragma unroll
+            for (int gp = 0; gp < 2; ++gp) {
+                const bf16x8 pf = pack8(s[u], 8 * gp);
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+                    ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vs, kVS, u * 32 + 16 * gp, dt * 32, lane), pf,
+                                                                    ot[dt], 0, 0, 0);
+            }
+        if (q_ok) {
+            const float inv = 1.0f / sum;
+            bf16* orow = o + (row0 + q) * ldo + j * 64;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    uint2 pk;
+                    pk.x = pack_bf16x2(ot[dt][4 * eg] * inv, ot[dt][4 * eg + 1] * inv);
+                    pk.y = pack_bf16x2(ot[dt][4 * eg + 2] * inv, ot[dt][4 * eg + 3] * inv);
+                    *reinterpret_cast<uint2*>(orow + dt * 32 + 8 * eg + 4 * h) = pk;
+                }
+            if (h == 0 && j < n_full) lse[(long)j * rows_total + row0 + q] = m * kScale + __logf(sum);
+        }
+    }
+}
+
+template <int KT>
+hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* lse, int batch, int tokens, int n_live,
+                         int n_full, hipStream_t s) {
+    constexpr size_t lds = (size_t)KT * 32 * (kKS + kVS) * sizeof(bf16);
+    auto kern = attn_fwd_mfma_kernel<KT>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(batch * n_live), dim3(256), lds, s, qkv, ldq, o, ldo, lse, tokens, n_live, n_full,
+                       (long)batch * tokens);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// backward for p_f heads: dQ, dK, dV from Q, K, V, O, dO and the saved log-sum-exp
+//
+// Per 32x32 tile pair (query tile i, key tile u), in the orientation S = Q K^T (a lane owns one KEY
+// column, its 16 result elements are 16 queries):
+//     S  = Q_i K_u^T              P  = exp(S/8 - lse_q)          (probabilities are rebuilt, never stored)
+//     dP = dO_i V_u^T             dS = P * (dP - delta_q),       delta_q = sum_d dO[q][d] O[q][d]
+//     dV_u^T += dO_i^T P          dK_u^T += Q_i^T dS             (P, dS feed the MFMA straight from registers)
+//     dQ_i^T += K_u^T dS^T        (dS goes through a 2 KB per-wavefront LDS tile to change owner)
+// Wavefront w owns key tiles w and w+4 and keeps their dK, dV accumulators in registers for the
+// whole kernel; the four partial dQ_i tiles are summed through LDS in a fixed order.
+// ---------------------------------------------------------------------------
+constexpr int kTS = 104;   // rows that are read both ways (row-form and transposing): 208 bytes
+
+template <int KT>
+__global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
+                                                            const bf16* __restrict__ o, long ldo,
+                                                            const float* __restrict__ lse,
+                                                            const bf16* __restrict__ d_o, long ld_do,
+                                                            bf16* __restrict__ dqkv, long ld_dqkv, int tokens,
+                                                            int n_full, long rows_total) {
+    constexpr int TP = KT * 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* Ks = reinterpret_cast<bf16*>(smem_raw);        // [TP][kTS]
+    bf16* Vs = Ks + TP * kTS;                            // [TP][kKS]
+    bf16* Qs = Vs + TP * kKS;                            // [32][kTS]   current query tile
+    bf16* dOs = Qs + 32 * kTS;                           // [32][kTS]
+    bf16* dSs_all = dOs + 32 * kTS;                      // [4][32 keys][32 queries]
+    float* lse_s = reinterpret_cast<float*>(dSs_all + 4 * 32 * 32);   // [TP]
+    float* del_s = lse_s + TP;                           // [TP]
+    float* dQp = del_s + TP;                             // [4][64 channels][32 queries]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    bf16* dSs = dSs_all + wave * 32 * 32;
+    const int b = blockIdx.x / n_full, j = blockIdx.x % n_full;
+    const long row0 = (long)b * tokens;
+    const bf16* Qb = qkv + row0 * ldq + j * 192;
+    const bf16* dOb = d_o + row0 * ld_do + j * 64;
+    const bf16* Ob = o + row0 * ldo + j * 64;
+    bf16* dQb = dqkv + row0 * ld_dqkv + j * 192;
+
+    load_tile64<TP>(Qb + 64, ldq, tokens, Ks, kTS);
+    load_tile64<TP>(Qb + 128, ldq, tokens, Vs, kKS);
+    for (int q = threadIdx.x; q < TP; q += 256) {
+        float l = 0.f, dl = 0.f;
+        if (q < tokens) {
+            l = lse[(long)j * rows_total + row0 + q];
+            float a[8], g[8];
+#pragma unroll
+            for (int ch = 0; ch < 64; ch += 8) {
+                load8(dOb + (long)q * ld_do + ch, a);
+                load8(Ob + (long)q * ldo + ch, g);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dl = fmaf(a[i], g[i], dl);
+            }
+        }
+        lse_s[q] = l * kLog2e;
+        del_s[q] = dl;
+    }
+
+    f32x16 dKt[2][2], dVt[2][2];
+#pragma unroll
+    for (int us = 0; us < 2; ++us)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            dKt[us][dt] = zero16();
+            dVt[us][dt] = zero16();
+        }
+    const float cexp = kScale * kLog2e;
+
+    for (int i = 0; i < KT; ++i) {
+        __syncthreads();   // previous query tile fully consumed (and the prologue's LDS writes are visible)
+        {
+            const int r = threadIdx.x >> 3, ch = (threadIdx.x & 7) * 8;
+            const int q = i * 32 + r;
+            u32x4 vq = {0u, 0u, 0u, 0u}, vd = {0u, 0u, 0u, 0u};
+            if (q < tokens) {
+                vq = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + ch);
+                vd = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ch);
+            }
+            *reinterpret_cast<u32x4*>(Qs + r * kTS + ch) = vq;
+            *reinterpret_cast<u32x4*>(dOs + r * kTS + ch) = vd;
+        }
+        __syncthreads();
+        float L[16], DL[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int ql = i * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            L[e] = lse_s[ql];
+            DL[e] = del_s[ql];
+        }
+        f32x16 dqt[2] = {zero16(), zero16()};
+#pragma unroll
+        for (int us = 0; us < 2; ++us) {
+            const int u = wave + 4 * us;
+            if (u < KT) {
+                f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kTS, c, kk * 16 + 8 * h),
+                                                                frag_rows(Ks, kTS, u * 32 + c, kk * 16 + 8 * h), s, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dOs, kTS, c, kk * 16 + 8 * h),
+                                                                 frag_rows(Vs, kKS, u * 32 + c, kk * 16 + 8 * h), dp, 0, 0, 0);
+                }
+                const bool key_ok = (u * 32 + c) < tokens;
+                f32x16 ds;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float p = key_ok ? __builtin_amdgcn_exp2f(s[e] * cexp - L[e]) : 0.f;
+                    s[e] = p;
+                    ds[e] = p * (dp[e] - DL[e]);
+                }
+                // hand dS to the lanes that own queries: [key][query] tile, 8-byte writes
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    uint2 pk;
+                    pk.x = pack_bf16x2(ds[4 * eg], ds[4 * eg + 1]);
+                    pk.y = pack_bf16x2(ds[4 * eg + 2], ds[4 * eg + 3]);
+                    *reinterpret_cast<uint2*>(dSs + c * 32 + 8 * eg + 4 * h) = pk;
+                }
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) {
+                    const bf16x8 pf = pack8(s, 8 * gp);
+                    const bf16x8 dsf = pack8(ds, 8 * gp);
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt) {
+                        dVt[us][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOs, kTS, 16 * gp, dt * 32, lane), pf,
+                                                                              dVt[us][dt], 0, 0, 0);
+                        dKt[us][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qs, kTS, 16 * gp, dt * 32, lane), dsf,
+                                                                              dKt[us][dt], 0, 0, 0);
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) {
+                    const bf16x8 dst = frag_tr(dSs, 32, 16 * gp, 0, lane);   // column = query c, slots = keys
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+                        dqt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Ks, kTS, u * 32 + 16 * gp, dt * 32, lane), dst,
+                                                                          dqt[dt], 0, 0, 0);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        // partial dQ_i^T of this wavefront: rows = channels, column = query c
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                dQp[(wave * 64 + dt * 32 + 8 * (e >> 2) + 4 * h + (e & 3)) * 32 + c] = dqt[dt][e];
+        __syncthreads();
+        {
+            const int q = threadIdx.x & 31, dch = threadIdx.x >> 5;
+            float v[8];
+#pragma unroll
+            for (int i8 = 0; i8 < 8; ++i8) {
+                const int d = dch * 8 + i8;
+                v[i8] = ((dQp[(0 * 64 + d) * 32 + q] + dQp[(1 * 64 + d) * 32 + q]) +
+                         (dQp[(2 * 64 + d) * 32 + q] + dQp[(3 * 64 + d) * 32 + q])) * kScale;
+            }
+            const int qg = i * 32 + q;
+            if (qg < tokens) store8(dQb + (long)qg * ld_dqkv + dch * 8, v);
+        }
+    }
+
+    // dK^T, dV^T: rows = channels, column = key owned by the lane -> 8-byte stores of 4 channels
+#pragma unroll
+    for (int us = 0; us < 2; ++us) {
+        const int key = (wave + 4 * us) * 32 + c;
+        if (wave + 4 * us < KT && key < tokens) {
+            bf16* krow = dQb + (long)key * ld_dqkv + 64;
+            bf16* vrow = krow + 64;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int d = dt * 32 + 8 * eg + 4 * h;
+                    uint2 pk;
+                    pk.x = pack_bf16x2(dKt[us][dt][4 * eg] * kScale, dKt[us][dt][4 * eg + 1] * kScale);
+                    pk.y = pack_bf16x2(dKt[us][dt][4 * eg + 2] * kScale, dKt[us][dt][4 * eg + 3] * kScale);
+                    *reinterpret_cast<uint2*>(krow + d) = pk;
+                    pk.x = pack_bf16x2(dVt[us][dt][4 * eg], dVt[us][dt][4 * eg + 1]);
+                    pk.y = pack_bf16x2(dVt[us][dt][4 * eg + 2], dVt[us][dt][4 * eg + 3]);
+                    *reinterpret_cast<uint2*>(vrow + d) = pk;
+                }
+        }
+    }
+}
+
+template <int KT>
+hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, const float* lse, const bf16* d_o, long ld_do,
+                         bf16* dqkv, long ld_dqkv, int batch, int tokens, int n_full, hipStream_t s) {
+    constexpr int TP = KT * 32;
+    constexpr size_t lds = (size_t)(TP * kTS + TP * kKS + 2 * 32 * kTS + 4 * 32 * 32) * sizeof(bf16) +
+                           (size_t)(2 * TP + 4 * 64 * 32) * sizeof(float);
+    auto kern = attn_bwd_mfma_kernel<KT>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(256), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv,
+                       tokens, n_full, (long)batch * tokens);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma_supported(int tokens, long ldq, long ldo) {
+    return tokens >= 1 && tokens <= 256 && (ldq % 8) == 0 && (ldo % 8) == 0;
+}
+
+hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
+                                int n_live, int n_full, hipStream_t s) {
+    if (n_live <= 0) return hipSuccess;
+    const bf16* q = static_cast<const bf16*>(qkv);
+    bf16* op = static_cast<bf16*>(o);
+    switch ((tokens + 31) / 32) {
+        case 1: return launch_fwd_kt<1>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 2: return launch_fwd_kt<2>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 3: return launch_fwd_kt<3>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 4: return launch_fwd_kt<4>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 5: return launch_fwd_kt<5>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 6: return launch_fwd_kt<6>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 7: return launch_fwd_kt<7>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        case 8: return launch_fwd_kt<8>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        default: return hipErrorNotSupported;
+    }
+}
+
+}  // namespace d2ft
+
+namespace d2ft {
+
+hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse, const void* d_o,
+                                long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens, int n_full,
+                                hipStream_t s) {
+    if (n_full <= 0) return hipSuccess;
+    const bf16* q = static_cast<const bf16*>(qkv);
+    const bf16* op = static_cast<const bf16*>(o);
+    const bf16* dop = static_cast<const bf16*>(d_o);
+    bf16* dq = static_cast<bf16*>(dqkv);
+#define D2FT_BWD_CASE(KT) \
+    case KT: return launch_bwd_kt<KT>(q, ldq, op, ldo, lse, dop, ld_do, dq, ld_dqkv, batch, tokens, n_full, s);
+    switch ((tokens + 31) / 32) {
+        D2FT_BWD_CASE(1) D2FT_BWD_CASE(2) D2FT_BWD_CASE(3) D2FT_BWD_CASE(4)
+        D2FT_BWD_CASE(5) D2FT_BWD_CASE(6) D2FT_BWD_CASE(7) D2FT_BWD_CASE(8)
+        default: return hipErrorNotSupported;
+    }
+#undef D2FT_BWD_CASE
+}
+
+}  // namespace d2ft
