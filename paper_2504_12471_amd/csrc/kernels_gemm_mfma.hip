@@ -15,6 +15,8 @@
 //
 // B's n or k index may go through a 64-granular remap table: that is how the compacted
 // live-head list selects rows / columns of the full weight tensors without copying them.
+#include <type_traits>
+
 #include "d2ft_common.h"
 
 namespace d2ft {
@@ -26,7 +28,6 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 
 namespace {
 
-constexpr int kThreads = 256;
 
 // LDS row strides (in bf16 elements), chosen so that the fragment reads are bank-conflict free
 template <int BK> constexpr int row_form_stride() { return BK + 8; }          // [index][k]: +16 bytes
@@ -47,7 +48,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 constexpr uint32_t kBufBytes = 0x80000000u;   // declared buffer size; operands are checked to be smaller
 constexpr uint32_t kOutside = 0x80000000u;    // any offset >= kBufBytes reads as zero
 
-template <int BI, int BK, bool COL>
+template <int BI, int BK, bool COL, int kThreads>
 struct SlabLoader {
     static constexpr int kChunks = BI * BK / 8;
     static constexpr int kPerThread = kChunks / kThreads;
@@ -156,6 +157,22 @@ __device__ __forceinline__ float gelu_grad_fast(float z) {
     return cdf + z * 0.39894228040143267794f * e;
 }
 
+// ---- issue order of one MFMA group ----
+// NM MFMAs with NR LDS reads (and optionally NW LDS stores and NW global loads) spread evenly
+// between them, expressed as scheduling-group barriers for the compiler's instruction scheduler.
+template <int NM, int NR, int NW, bool READS, bool STORES, bool LOADS, int I = 0>
+__device__ __forceinline__ void pace_group() {
+    if constexpr (I < NM) {
+        constexpr int nw = (I + 1) * NW / NM - I * NW / NM;
+        constexpr int nr = (I + 1) * NR / NM - I * NR / NM;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   // MFMA
+        if constexpr (READS && nr > 0) __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);   // LDS read
+        if constexpr (STORES && nw > 0) __builtin_amdgcn_sched_group_barrier(0x200, nw, 0);  // LDS store
+        if constexpr (LOADS && nw > 0) __builtin_amdgcn_sched_group_barrier(0x020, nw, 0);   // global load
+        pace_group<NM, NR, NW, READS, STORES, LOADS, I + 1>();
+    }
+}
+
 // ---- workgroup -> tile mapping ----
 // The chip has 8 XCDs with one L2 each and workgroup ids are dealt to them round-robin, so ids
 // with the same value mod 8 are renumbered to a contiguous range of tiles; inside that range
@@ -178,9 +195,10 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
     tn = in_group / gsize;
 }
 
-template <int BM, int BN, int BK, bool A_COL, bool B_COL, int REMAP>
-__global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g) {
-    constexpr int WTM = BM / 2, WTN = BN / 2;   // wavefront tile
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
+    constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
     constexpr int MT = WTM / 32, NT = WTN / 32; // MFMA tiles per wavefront
     constexpr int A_ELEMS = slab_elems<BM, BK, A_COL>();
     constexpr int B_ELEMS = slab_elems<BN, BK, B_COL>();
@@ -194,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g) {
     const bf16* __restrict__ A = static_cast<const bf16*>(g.A);
     const bf16* __restrict__ B = static_cast<const bf16*>(g.B);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     int tile_m, tile_n, split;
     tile_of_block((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, tile_m, tile_n, split);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -215,50 +233,101 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[t][u][e] = 0.f;
 
-    SlabLoader<BM, BK, A_COL> la;
-    SlabLoader<BN, BK, B_COL> lb;
+    SlabLoader<BM, BK, A_COL, kThreads> la;
+    SlabLoader<BN, BK, B_COL, kThreads> lb;
     // strides as (index stride, k stride)
     la.template init<false>(A, g.a_rs, g.a_cs, m0, g.M, g.tbl);
     lb.template init<REMAP == REMAP_B_N>(B, g.b_cs, g.b_rs, n0, g.N, g.tbl);
 
     const int nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
+
+    // Software pipeline.  LDS buffer (s & 1) holds slab s; the registers of the slab loaders hold
+    // slab s + 1, fetched one slab ahead; operand fragments are double-buffered too, so every LDS
+    // read is issued one MFMA group (16 k) before it is used.  The single barrier of a slab sits
+    // before its last MFMA group: by then all fragment reads of the slab are done (its buffer may be
+    // refilled from the next slab on) and the stores of slab s + 1, issued at the top, have had three
+    // MFMA groups to land, so the first fragments of slab s + 1 are fetched behind that last group.
+    bf16x8 af[2][MT], bfg[2][NT];
+    auto read_frags = [&](int buf, const bf16* as, const bf16* bs, int kk) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) af[buf][t] = read_fragment<BM, BK, A_COL>(as, wm * WTM + t * 32, kk, lane);
+#pragma unroll
+        for (int u = 0; u < NT; ++u) bfg[buf][u] = read_fragment<BN, BK, B_COL>(bs, wn * WTN + u * 32, kk, lane);
+    };
+    auto mfma_group = [&](int buf) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+                acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][t], bfg[buf][u], acc[t][u], 0, 0, 0);
+    };
+    // Issue order of one MFMA group: the compiler is told to spread the group's LDS reads (and, in the
+    // first group of a slab, the LDS stores of the next slab and the global loads of the one after)
+    // evenly between the MFMAs instead of clumping them in front with a wait behind each.
+    constexpr int NM = MT * NT;
+    constexpr int NR = MT * (A_COL ? 2 : 1) + NT * (B_COL ? 2 : 1);                                  // LDS reads per group
+    constexpr int NW = SlabLoader<BM, BK, A_COL, kThreads>::kPerThread + SlabLoader<BN, BK, B_COL, kThreads>::kPerThread;   // stores = loads per slab
+    static_assert(BK == 64, "the pipeline below is written for four MFMA groups per slab");
+
     if (nslabs > 0) {
         la.template load<false>(kb, ke, g.tbl);
         lb.template load<REMAP == REMAP_B_K>(kb, ke, g.tbl);
         la.store(As0);
         lb.store(Bs0);
+        if (nslabs > 1) {
+            la.template load<false>(kb + BK, ke, g.tbl);
+            lb.template load<REMAP == REMAP_B_K>(kb + BK, ke, g.tbl);
+        }
     }
     __syncthreads();
+    if (nslabs > 0) read_frags(0, As0, Bs0, 0);
 
-    for (int s = 0; s < nslabs; ++s) {
+    // one slab; STORE: slab s+1 is in the loader registers and goes to the other buffer,
+    // LOAD: slab s+2 exists and is fetched into the loader registers
+    auto slab = [&](int s, auto store_tag, auto load_tag) {
+        constexpr bool STORE = decltype(store_tag)::value, LOAD = decltype(load_tag)::value;
         const bool odd = s & 1;
-        const bool more = (s + 1 < nslabs);
-        if (more) {
-            const int k0 = kb + (s + 1) * BK;
+        const bf16* as = odd ? As1 : As0;
+        const bf16* bs = odd ? Bs1 : Bs0;
+        bf16* as_next = odd ? As0 : As1;
+        bf16* bs_next = odd ? Bs0 : Bs1;
+        read_frags(1, as, bs, 16);   // ahead of the stores: LDS reads are not moved across LDS stores
+        if (STORE) {
+            la.store(as_next);
+            lb.store(bs_next);
+        }
+        if (LOAD) {
+            const int k0 = kb + (s + 2) * BK;
             la.template load<false>(k0, ke, g.tbl);
             lb.template load<REMAP == REMAP_B_K>(k0, ke, g.tbl);
         }
-        const bf16* as = odd ? As1 : As0;
-        const bf16* bs = odd ? Bs1 : Bs0;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 af[MT], bfg[NT];
-#pragma unroll
-            for (int t = 0; t < MT; ++t) af[t] = read_fragment<BM, BK, A_COL>(as, wm * WTM + t * 32, kk, lane);
-#pragma unroll
-            for (int u = 0; u < NT; ++u) bfg[u] = read_fragment<BN, BK, B_COL>(bs, wn * WTN + u * 32, kk, lane);
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int u = 0; u < NT; ++u)
-                    acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t], bfg[u], acc[t][u], 0, 0, 0);
-        }
-        if (more) {
-            la.store(odd ? As0 : As1);
-            lb.store(odd ? Bs0 : Bs1);
-        }
+        mfma_group(0);
+        pace_group<NM, NR, NW, true, STORE, LOAD>();
+        __builtin_amdgcn_sched_barrier(0);   // groups are scheduled one by one
+        read_frags(0, as, bs, 32);
+        mfma_group(1);
+        pace_group<NM, NR, NW, true, false, false>();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, as, bs, 48);
+        mfma_group(0);
+        pace_group<NM, NR, NW, true, false, false>();
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        if (STORE) read_frags(0, as_next, bs_next, 0);
+        mfma_group(1);
+        pace_group<NM, NR, NW, STORE, false, false>();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    {
+        int s = 0;
+        for (; s + 2 < nslabs; ++s) slab(s, std::true_type{}, std::true_type{});
+        if (s + 1 < nslabs) {
+            slab(s, std::true_type{}, std::false_type{});
+            ++s;
+        }
+        if (s < nslabs) slab(s, std::false_type{}, std::false_type{});
     }
+    __syncthreads();   // the epilogue reuses the operand buffers
 
     // ---- epilogue ----
     // Accumulator element e of MFMA tile (t,u) is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
@@ -328,17 +397,17 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmArgs g) {
     }
 }
 
-template <int BM, int BN, int BK, bool A_COL, bool B_COL>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 constexpr size_t lds_bytes() {
     constexpr size_t slabs = 2 * (slab_elems<BM, BK, A_COL>() + slab_elems<BN, BK, B_COL>()) * sizeof(bf16);
-    constexpr size_t stage = 4 * 32 * (BN / 2 + 4) * sizeof(float);
+    constexpr size_t stage = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
     return slabs > stage ? slabs : stage;
 }
 
-template <int BM, int BN, int BK, bool A_COL, bool B_COL, int REMAP>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
-    constexpr size_t lds = lds_bytes<BM, BN, BK, A_COL, B_COL>();
-    auto kern = gemm_mfma_kernel<BM, BN, BK, A_COL, B_COL, REMAP>;
+    constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, A_COL, B_COL>();
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP>;
     static bool attr_set = false;   // per instantiation; setting it again is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -347,26 +416,26 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     }
     const int splits = g.partial ? g.splits : 1;
     const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * splits;
-    const dim3 grid((unsigned)tiles), block(kThreads);
+    const dim3 grid((unsigned)tiles), block(64 * WGM * WGN);
     hipLaunchKernelGGL(kern, grid, block, lds, s, g);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, bool A_COL, bool B_COL>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 hipError_t launch_remap(const GemmArgs& g, hipStream_t s) {
     switch (g.remap) {
-        case REMAP_B_N: return launch_cfg<BM, BN, BK, A_COL, B_COL, REMAP_B_N>(g, s);
-        case REMAP_B_K: return launch_cfg<BM, BN, BK, A_COL, B_COL, REMAP_B_K>(g, s);
-        default: return launch_cfg<BM, BN, BK, A_COL, B_COL, REMAP_NONE>(g, s);
+        case REMAP_B_N: return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N>(g, s);
+        case REMAP_B_K: return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_K>(g, s);
+        default: return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE>(g, s);
     }
 }
 
-template <int BM, int BN, int BK>
+template <int BM, int BN, int BK, int WGM, int WGN>
 hipError_t launch_layout(const GemmArgs& g, hipStream_t s) {
     const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
-    if (!a_col && !b_col) return launch_remap<BM, BN, BK, false, false>(g, s);
-    if (!a_col && b_col) return launch_remap<BM, BN, BK, false, true>(g, s);
-    if (a_col && b_col) return launch_remap<BM, BN, BK, true, true>(g, s);
+    if (!a_col && !b_col) return launch_remap<BM, BN, BK, WGM, WGN, false, false>(g, s);
+    if (!a_col && b_col) return launch_remap<BM, BN, BK, WGM, WGN, false, true>(g, s);
+    if (a_col && b_col) return launch_remap<BM, BN, BK, WGM, WGN, true, true>(g, s);
     return hipErrorNotSupported;
 }
 
@@ -414,7 +483,7 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 static bool use_big_tile(const GemmArgs& g) {
     // tile choice: the large tile when it still fills the chip, else the small one
     const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * (g.partial ? g.splits : 1);
-    return g_gemm_tile_override ? (g_gemm_tile_override == 1) : (big >= 256);
+    return g_gemm_tile_override ? (g_gemm_tile_override != 2) : (big >= 256);
 }
 
 const char* gemm_mfma_config_name(const GemmArgs& g) {
@@ -429,8 +498,9 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     if (!gemm_mfma_supported(g)) return hipErrorNotSupported;
     const bool use_big = use_big_tile(g);
-    if (use_big) return launch_layout<256, 256, 64>(g, s);
-    return launch_layout<128, 128, 64>(g, s);
+    if (g_gemm_tile_override == 3) return launch_layout<256, 256, 64, 2, 2>(g, s);
+    if (use_big) return launch_layout<256, 256, 64, 2, 4>(g, s);
+    return launch_layout<128, 128, 64, 2, 2>(g, s);
 }
 
 }  // namespace d2ft
