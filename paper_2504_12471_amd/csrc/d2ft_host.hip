@@ -15,7 +15,7 @@ namespace d2ft {
 namespace {
 
 constexpr int kMaxSplits = 8;
-constexpr int kColChunks = 32;
+constexpr int kColChunks = 64;
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline size_t elem_size(int dtype) { return dtype == D2FT_F32 ? 4 : 2; }
@@ -260,7 +260,7 @@ int pick_splits(long out_rows, long out_cols, long K) {
 }
 
 int pick_chunks(long rows) {
-    long c = rows / 128;
+    long c = rows / 64;
     if (c < 1) c = 1;
     if (c > kColChunks) c = kColChunks;
     return (int)c;

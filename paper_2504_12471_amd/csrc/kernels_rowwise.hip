@@ -7,9 +7,11 @@
 namespace d2ft {
 
 // ---------------------------------------------------------------------------
-// LayerNorm forward: y = (x - mean) * rstd * gamma + beta, biased variance
+// LayerNorm forward: y = (x - mean) * rstd * gamma + beta, biased variance.
+// One wavefront per row; the row is read once and held in registers (NV 8-element vectors per
+// lane, width <= 512*NV); NV = 0 is the any-width version that re-reads the row (it then hits L2).
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ y,
                                                      float* __restrict__ mean, float* __restrict__ rstd, int rows,
@@ -18,44 +20,88 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     const T* xr = x + (long)row * width;
-    float v[8];
-    float s = 0.f;
-    for (int c = lane * 8; c < width; c += 512) {
-        load8(xr + c, v);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s += v[i];
-    }
-    const float mu = wave_sum(s) / (float)width;
-    float q = 0.f;
-    for (int c = lane * 8; c < width; c += 512) {
-        load8(xr + c, v);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float d = v[i] - mu;
-            q += d * d;
-        }
-    }
-    const float rs = 1.0f / sqrtf(wave_sum(q) / (float)width + eps);
     T* yr = y + (long)row * width;
     float g[8], b[8], o[8];
-    for (int c = lane * 8; c < width; c += 512) {
-        load8(xr + c, v);
-        load8(gamma + c, g);
-        load8(beta + c, b);
+    if (NV > 0) {
+        float v[NV > 0 ? NV : 1][8];
+        float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = (v[i] - mu) * rs * g[i] + b[i];
-        store8(yr + c, o);
-    }
-    if (lane == 0) {
-        mean[row] = mu;
-        rstd[row] = rs;
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+                load8(xr + c, v[j]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s += v[j][i];
+            }
+        }
+        const float mu = wave_sum(s) / (float)width;
+        float q = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float d = v[j][i] - mu;
+                    q += d * d;
+                }
+            }
+        }
+        const float rs = 1.0f / sqrtf(wave_sum(q) / (float)width + eps);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+                load8(gamma + c, g);
+                load8(beta + c, b);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[i] = (v[j][i] - mu) * rs * g[i] + b[i];
+                store8(yr + c, o);
+            }
+        }
+        if (lane == 0) {
+            mean[row] = mu;
+            rstd[row] = rs;
+        }
+    } else {
+        float v[8];
+        float s = 0.f;
+        for (int c = lane * 8; c < width; c += 512) {
+            load8(xr + c, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += v[i];
+        }
+        const float mu = wave_sum(s) / (float)width;
+        float q = 0.f;
+        for (int c = lane * 8; c < width; c += 512) {
+            load8(xr + c, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float d = v[i] - mu;
+                q += d * d;
+            }
+        }
+        const float rs = 1.0f / sqrtf(wave_sum(q) / (float)width + eps);
+        for (int c = lane * 8; c < width; c += 512) {
+            load8(xr + c, v);
+            load8(gamma + c, g);
+            load8(beta + c, b);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = (v[i] - mu) * rs * g[i] + b[i];
+            store8(yr + c, o);
+        }
+        if (lane == 0) {
+            mean[row] = mu;
+            rstd[row] = rs;
+        }
     }
 }
 
 // ---------------------------------------------------------------------------
 // LayerNorm backward wrt the input, plus a residual: dx = rstd*(dh - mean(dh) - xh*mean(dh*xh)) + res
+// Same register caching as the forward kernel (dh and xh are kept).
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ d, const T* __restrict__ x,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      const T* __restrict__ gamma, const T* __restrict__ res,
@@ -65,97 +111,160 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ d, co
     if (row >= rows) return;
     const long off = (long)row * width;
     const float mu = mean[row], rs = rstd[row];
-    float dv[8], xv[8], g[8];
-    float s1 = 0.f, s2 = 0.f;
-    for (int c = lane * 8; c < width; c += 512) {
-        load8(d + off + c, dv);
-        load8(x + off + c, xv);
-        load8(gamma + c, g);
+    float dv[8], xv[8], g[8], r[8], o[8];
+    if (NV > 0) {
+        float dh[NV > 0 ? NV : 1][8], xh[NV > 0 ? NV : 1][8];
+        float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float dh = dv[i] * g[i];
-            s1 += dh;
-            s2 += dh * ((xv[i] - mu) * rs);
-        }
-    }
-    const float m1 = wave_sum(s1) / (float)width;
-    const float m2 = wave_sum(s2) / (float)width;
-    float r[8], o[8];
-    for (int c = lane * 8; c < width; c += 512) {
-        load8(d + off + c, dv);
-        load8(x + off + c, xv);
-        load8(gamma + c, g);
-        if (res) {
-            load8(res + off + c, r);
-        } else {
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+                load8(d + off + c, dv);
+                load8(x + off + c, xv);
+                load8(gamma + c, g);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) r[i] = 0.f;
+                for (int i = 0; i < 8; ++i) {
+                    dh[j][i] = dv[i] * g[i];
+                    xh[j][i] = (xv[i] - mu) * rs;
+                    s1 += dh[j][i];
+                    s2 += dh[j][i] * xh[j][i];
+                }
+            }
         }
+        const float m1 = wave_sum(s1) / (float)width;
+        const float m2 = wave_sum(s2) / (float)width;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float xh = (xv[i] - mu) * rs;
-            o[i] = rs * (dv[i] * g[i] - m1 - xh * m2) + r[i];
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+                if (res) {
+                    load8(res + off + c, r);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) r[i] = 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[i] = rs * (dh[j][i] - m1 - xh[j][i] * m2) + r[i];
+                store8(dx + off + c, o);
+            }
         }
-        store8(dx + off + c, o);
+    } else {
+        float s1 = 0.f, s2 = 0.f;
+        for (int c = lane * 8; c < width; c += 512) {
+            load8(d + off + c, dv);
+            load8(x + off + c, xv);
+            load8(gamma + c, g);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float dh = dv[i] * g[i];
+                s1 += dh;
+                s2 += dh * ((xv[i] - mu) * rs);
+            }
+        }
+        const float m1 = wave_sum(s1) / (float)width;
+        const float m2 = wave_sum(s2) / (float)width;
+        for (int c = lane * 8; c < width; c += 512) {
+            load8(d + off + c, dv);
+            load8(x + off + c, xv);
+            load8(gamma + c, g);
+            if (res) {
+                load8(res + off + c, r);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float xh = (xv[i] - mu) * rs;
+                o[i] = rs * (dv[i] * g[i] - m1 - xh * m2) + r[i];
+            }
+            store8(dx + off + c, o);
+        }
     }
 }
 
 // ---------------------------------------------------------------------------
-// column sums over a chunk of rows: block = 64 columns x 4 row lanes
+// column sums over a chunk of rows.  A workgroup covers 256 columns (32 lanes x 8 columns, 16-byte
+// loads) and 8 row lanes; LN = true sums d*xhat and d (LayerNorm scale / shift gradients).
 // ---------------------------------------------------------------------------
 template <typename T, bool LN>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, long ldx, const T* __restrict__ x,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      int rows, int cols, float* __restrict__ partial,
                                                      float* __restrict__ partial2, int chunks) {
-    __shared__ float red[2][4][64];
-    const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
-    const int col = blockIdx.x * 64 + cl;
+    __shared__ float red[2][8][32][9];
+    const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int col = blockIdx.x * 256 + cl * 8;
     const int per = (rows + chunks - 1) / chunks;
     const int r0 = blockIdx.y * per;
     const int r1 = min(rows, r0 + per);
-    float a = 0.f, b = 0.f;
+    float a[8], b[8], dv[8], xv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = b[i] = 0.f;
     if (col < cols) {
-        for (int r = r0 + rg; r < r1; r += 4) {
-            const float dv = ld<T>(X + (long)r * ldx + col);
+        for (int r = r0 + rg; r < r1; r += 8) {
+            load8(X + (long)r * ldx + col, dv);
             if (LN) {
-                const float xh = (ld<T>(x + (long)r * ldx + col) - mean[r]) * rstd[r];
-                a += dv * xh;
-                b += dv;
+                load8(x + (long)r * ldx + col, xv);
+                const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    a[i] += dv[i] * ((xv[i] - mu) * rs);
+                    b[i] += dv[i];
+                }
             } else {
-                a += dv;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) a[i] += dv[i];
             }
         }
     }
-    red[0][rg][cl] = a;
-    red[1][rg][cl] = b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        red[0][rg][cl][i] = a[i];
+        if (LN) red[1][rg][cl][i] = b[i];
+    }
     __syncthreads();
-    if (rg == 0 && col < cols) {
-        partial[(long)blockIdx.y * cols + col] = (red[0][0][cl] + red[0][1][cl]) + (red[0][2][cl] + red[0][3][cl]);
-        if (LN)
-            partial2[(long)blockIdx.y * cols + col] =
-                (red[1][0][cl] + red[1][1][cl]) + (red[1][2][cl] + red[1][3][cl]);
+    // thread t sums column t of the workgroup's 256 over the 8 row lanes, in a fixed order
+    const int c2 = threadIdx.x >> 3, i2 = threadIdx.x & 7;
+    const int ocol = blockIdx.x * 256 + threadIdx.x;
+    if (ocol < cols) {
+        float s = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            s += red[0][g][c2][i2];
+            if (LN) s2 += red[1][g][c2][i2];
+        }
+        partial[(long)blockIdx.y * cols + ocol] = s;
+        if (LN) partial2[(long)blockIdx.y * cols + ocol] = s2;
     }
 }
 
 // ---------------------------------------------------------------------------
-// sum split partials in order and write (or add to) the output, with an optional remap
+// sum split partials in order and write (or add to) the output, with an optional 64-granular remap
+// of rows or columns; 4 consecutive columns per thread
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int splits,
                                                               long slice_stride, int rows, int cols,
                                                               T* __restrict__ out, long ldo, int remap,
                                                               int accumulate, Remap64 tbl) {
+    const int cq = cols >> 2;
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long)rows * cols) return;
-    const int r = (int)(idx / cols), c = (int)(idx % cols);
-    float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += partial[k * slice_stride + idx];
+    if (idx >= (long)rows * cq) return;
+    const int r = (int)(idx / cq), c = (int)(idx % cq) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* src = partial + (long)r * cols + c;
+    for (int k = 0; k < splits; ++k) {
+        const float4 v = *reinterpret_cast<const float4*>(src + k * slice_stride);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
     const int ro = (remap == RED_REMAP_ROWS) ? tbl(r) : r;
     const int co = (remap == RED_REMAP_COLS) ? tbl(c) : c;
     T* o = out + (long)ro * ldo + co;
-    if (accumulate) s += ld<T>(o);
-    st<T>(o, s);
+    if (accumulate) {
+        s.x += ld<T>(o); s.y += ld<T>(o + 1); s.z += ld<T>(o + 2); s.w += ld<T>(o + 3);
+    }
+    st<T>(o, s.x); st<T>(o + 1, s.y); st<T>(o + 2, s.z); st<T>(o + 3, s.w);
 }
 
 // ---------------------------------------------------------------------------
@@ -287,22 +396,28 @@ __global__ __launch_bounds__(256) void lora_project_kernel(const float* __restri
 hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean,
                          float* rstd, int rows, int width, float eps, hipStream_t s) {
     const dim3 grid((rows + 3) / 4), block(256);
-    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(ln_fwd_kernel<T>, grid, block, 0, s, (const T*)x, (const T*)gamma,
+#define D2FT_LN_FWD(NV)                                                                                        \
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL((ln_fwd_kernel<T, NV>), grid, block, 0, s, (const T*)x, (const T*)gamma, \
                                             (const T*)beta, (T*)y, mean, rstd, rows, width, eps);)
+    if (width <= 512) { D2FT_LN_FWD(1) } else if (width <= 1024) { D2FT_LN_FWD(2) } else if (width <= 2048) { D2FT_LN_FWD(4) } else { D2FT_LN_FWD(0) }
+#undef D2FT_LN_FWD
     return hipGetLastError();
 }
 
 hipError_t launch_ln_bwd(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
                          const void* gamma, const void* res, void* dx, int rows, int width, hipStream_t s) {
     const dim3 grid((rows + 3) / 4), block(256);
-    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(ln_bwd_kernel<T>, grid, block, 0, s, (const T*)d, (const T*)x, mean, rstd,
-                                            (const T*)gamma, (const T*)res, (T*)dx, rows, width);)
+#define D2FT_LN_BWD(NV)                                                                                             \
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL((ln_bwd_kernel<T, NV>), grid, block, 0, s, (const T*)d, (const T*)x, mean, \
+                                            rstd, (const T*)gamma, (const T*)res, (T*)dx, rows, width);)
+    if (width <= 512) { D2FT_LN_BWD(1) } else if (width <= 1024) { D2FT_LN_BWD(2) } else if (width <= 2048) { D2FT_LN_BWD(4) } else { D2FT_LN_BWD(0) }
+#undef D2FT_LN_BWD
     return hipGetLastError();
 }
 
 hipError_t launch_ln_param_grad(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
                                 float* partial_g, float* partial_b, int rows, int width, int chunks, hipStream_t s) {
-    const dim3 grid((width + 63) / 64, chunks), block(256);
+    const dim3 grid((width + 255) / 256, chunks), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL((colsum_kernel<T, true>), grid, block, 0, s, (const T*)d, (long)width,
                                             (const T*)x, mean, rstd, rows, width, partial_g, partial_b, chunks);)
     return hipGetLastError();
@@ -310,7 +425,7 @@ hipError_t launch_ln_param_grad(int dtype, const void* d, const void* x, const f
 
 hipError_t launch_colsum(int dtype, const void* X, long ld, int rows, int cols, float* partial, int chunks,
                          hipStream_t s) {
-    const dim3 grid((cols + 63) / 64, chunks), block(256);
+    const dim3 grid((cols + 255) / 256, chunks), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL((colsum_kernel<T, false>), grid, block, 0, s, (const T*)X, ld,
                                             (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, rows,
                                             cols, partial, (float*)nullptr, chunks);)
@@ -320,7 +435,7 @@ hipError_t launch_colsum(int dtype, const void* X, long ld, int rows, int cols, 
 hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, long slice_stride, int rows, int cols,
                                   void* out, long ldo, int remap, const Remap64& tbl, int accumulate,
                                   hipStream_t s) {
-    const long total = (long)rows * cols;
+    const long total = (long)rows * (cols / 4);   // cols is a multiple of 8 at every call site
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL(reduce_partials_kernel<T>, grid, block, 0, s, partial, splits,
                                             slice_stride, rows, cols, (T*)out, ldo, remap, accumulate, tbl);)
