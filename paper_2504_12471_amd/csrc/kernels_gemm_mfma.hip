@@ -173,6 +173,29 @@ __device__ __forceinline__ void pace_group() {
     }
 }
 
+// First MFMA group of a slab: LDS reads cannot be moved across LDS stores (the compiler must assume
+// the two buffers alias), so the group's reads all go behind its first quarter of MFMAs and the
+// stores of the next slab, each followed by the global load that refills its registers, behind the rest.
+template <int NM, int NR, int NW, int I = 0>
+__device__ __forceinline__ void pace_first_group() {
+    constexpr int RA = NM / 4 > 0 ? NM / 4 : 1;   // MFMAs that carry the reads
+    if constexpr (I < NM) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (I < RA) {
+            constexpr int nr = (I + 1) * NR / RA - I * NR / RA;
+            if constexpr (nr > 0) __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);
+        } else {
+            constexpr int J = I - RA, NB = NM - RA;
+            constexpr int nw = (J + 1) * NW / NB - J * NW / NB;
+            if constexpr (nw > 0) {
+                __builtin_amdgcn_sched_group_barrier(0x200, nw, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, nw, 0);
+            }
+        }
+        pace_first_group<NM, NR, NW, I + 1>();
+    }
+}
+
 // ---- workgroup -> tile mapping ----
 // The chip has 8 XCDs with one L2 each and workgroup ids are dealt to them round-robin, so ids
 // with the same value mod 8 are renumbered to a contiguous range of tiles; inside that range
@@ -302,7 +325,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
             lb.template load<REMAP == REMAP_B_K>(k0, ke, g.tbl);
         }
         mfma_group(0);
-        pace_group<NM, NR, NW, true, STORE, LOAD>();
+        if constexpr (STORE && LOAD)
+            pace_first_group<NM, NR, NW>();
+        else
+            pace_group<NM, NR, NW, true, false, false>();
         __builtin_amdgcn_sched_barrier(0);   // groups are scheduled one by one
         read_frags(0, as, bs, 32);
         mfma_group(1);
@@ -481,9 +507,10 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 }
 
 static bool use_big_tile(const GemmArgs& g) {
-    // tile choice: the large tile when it still fills the chip, else the small one
+    // tile choice: the 256x256 tile moves half the operand bytes per FLOP of the 128x128 one and
+    // measures faster on one MI355X even when it leaves CUs idle, down to about 100 workgroups
     const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * (g.partial ? g.splits : 1);
-    return g_gemm_tile_override ? (g_gemm_tile_override != 2) : (big >= 256);
+    return g_gemm_tile_override ? (g_gemm_tile_override != 2) : (big >= 96 && g.M >= 256 && g.N >= 256);
 }
 
 const char* gemm_mfma_config_name(const GemmArgs& g) {
@@ -498,7 +525,6 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     if (!gemm_mfma_supported(g)) return hipErrorNotSupported;
     const bool use_big = use_big_tile(g);
-    if (g_gemm_tile_override == 3) return launch_layout<256, 256, 64, 2, 2>(g, s);
     if (use_big) return launch_layout<256, 256, 64, 2, 4>(g, s);
     return launch_layout<128, 128, 64, 2, 2>(g, s);
 }
