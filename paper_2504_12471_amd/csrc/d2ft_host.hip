@@ -252,11 +252,23 @@ GemmArgs gemm_base() {
     return g;
 }
 
-int pick_splits(long out_rows, long out_cols, long K) {
-    const long tiles = ((out_rows + 127) / 128) * ((out_cols + 127) / 128);
-    int s = 1;
-    while (s < kMaxSplits && tiles * s < 512 && K / (s * 2) >= 512) s *= 2;
-    return s;
+// Split count and tile of a weight-gradient GEMM (reduction over the token rows).  The 256x256 tile
+// runs one workgroup per CU, so the splits should bring the grid close to, but not above, the 256
+// CUs; outputs too small for that use the 128x128 tile, of which three fit a CU.
+int pick_splits(long out_rows, long out_cols, long K, int* tile_hint) {
+    const long t256 = ((out_rows + 255) / 256) * ((out_cols + 255) / 256);
+    const long t128 = ((out_rows + 127) / 128) * ((out_cols + 127) / 128);
+    long s;
+    if (t256 >= 24 && out_rows >= 256 && out_cols >= 256) {
+        *tile_hint = 1;
+        s = 256 / t256;
+    } else {
+        *tile_hint = 2;
+        s = 768 / t128;
+    }
+    if (s > kMaxSplits) s = kMaxSplits;
+    while (s > 1 && K / s < 512) --s;
+    return s < 1 ? 1 : (int)s;
 }
 
 int pick_chunks(long rows) {
@@ -276,7 +288,7 @@ d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop
     g.B = Bop; g.b_rs = ldb; g.b_cs = 1;      // B(k = token, n = out col) = Bop[token][n]
     g.M = out_rows; g.N = out_cols; g.K = (int)s.M;
     g.partial = part;
-    g.splits = pick_splits(out_rows, out_cols, s.M);
+    g.splits = pick_splits(out_rows, out_cols, s.M, &g.tile_hint);
     if (splits_out) *splits_out = g.splits;
     D2FT_TRY(run_gemm(g, d, st));
     if (reduce)

@@ -510,7 +510,9 @@ static bool use_big_tile(const GemmArgs& g) {
     // tile choice: the 256x256 tile moves half the operand bytes per FLOP of the 128x128 one and
     // measures faster on one MI355X even when it leaves CUs idle, down to about 100 workgroups
     const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * (g.partial ? g.splits : 1);
-    return g_gemm_tile_override ? (g_gemm_tile_override != 2) : (big >= 96 && g.M >= 256 && g.N >= 256);
+    if (g_gemm_tile_override) return g_gemm_tile_override != 2;
+    if (g.tile_hint) return g.tile_hint == 1;
+    return big >= 96 && g.M >= 256 && g.N >= 256;
 }
 
 const char* gemm_mfma_config_name(const GemmArgs& g) {
