@@ -327,57 +327,97 @@ __global__ __launch_bounds__(256) void lora_merge_kernel(const T* __restrict__ w
 }
 
 // ---------------------------------------------------------------------------
-// LoRA gradients from G = gradient of the effective weight (fp32 split partials):
-//   dB[h][d][i] = scale * sum_k G_h[d][k] A[h][i][k]
-//   dA[h][i][k] = scale * sum_d B[h][d][i] G_h[d][k]
-// grid (n_full, 2 planes); G rows of head j, plane p start at (j*3+p)*64
+// LoRA gradients from G = gradient of the effective weight (fp32 split partials, rows of head j and
+// plane p start at (j*3+p)*64):
+//   dA[h][i][k] = scale * sum_d B[h][d][i] * G_h[d][k]      (lora_grad_a_kernel, grid (n_full*2, D/64))
+//   dB[h][d][i] = scale * sum_k G_h[d][k] * A[h][i][k]      (lora_grad_b_kernel, grid (n_full*2, 16))
+// Each kernel sums the split slices of G itself, in order, and owns complete outputs.
 // ---------------------------------------------------------------------------
+constexpr int kMaxRank = D2FT_MAX_LORA_RANK;
+
 template <typename T>
-__global__ __launch_bounds__(256) void lora_project_kernel(const float* __restrict__ G, int splits, long slice_stride,
-                                                           const T* __restrict__ la_q, const T* __restrict__ la_v,
-                                                           const T* __restrict__ lb_q, const T* __restrict__ lb_v,
-                                                           T* g_la_q, T* g_la_v, T* g_lb_q, T* g_lb_v, HeadList full,
-                                                           int H, int D, int r, float scale, int accumulate) {
-    const int j = blockIdx.x, plane = blockIdx.y;   // plane 0: query, 1: value
+__global__ __launch_bounds__(256) void lora_grad_a_kernel(const float* __restrict__ G, int splits, long slice_stride,
+                                                          const T* __restrict__ lb_q, const T* __restrict__ lb_v,
+                                                          T* g_la_q, T* g_la_v, HeadList full, int D, int r, float scale,
+                                                          int accumulate) {
+    __shared__ float Bs[64 * kMaxRank];          // B_h [64][r]
+    __shared__ float red[4][64];
+    const int j = blockIdx.x >> 1, plane = blockIdx.x & 1;
+    T* gA = plane == 0 ? g_la_q : g_la_v;
+    if (!gA) return;
+    const int p = plane == 0 ? 0 : 2;
+    const int h = full.h[j];
+    const T* B = (plane == 0 ? lb_q : lb_v) + (long)h * 64 * r;
+    for (int e = threadIdx.x; e < 64 * r; e += 256) Bs[e] = ld<T>(B + e);
+    __syncthreads();
+    const int kl = threadIdx.x & 63, dq = threadIdx.x >> 6;   // column within the chunk, group of 16 rows
+    const int k = blockIdx.y * 64 + kl;
+    float gs[16];
+#pragma unroll
+    for (int dd = 0; dd < 16; ++dd) {
+        float v = 0.f;
+        if (k < D) {
+            const float* src = G + ((long)(j * 3 + p) * 64 + dq * 16 + dd) * D + k;
+            for (int s = 0; s < splits; ++s) v += src[s * slice_stride];
+        }
+        gs[dd] = v;
+    }
+    gA += (long)h * r * D;
+    for (int i = 0; i < r; ++i) {
+        float acc = 0.f;
+#pragma unroll
+        for (int dd = 0; dd < 16; ++dd) acc = fmaf(Bs[(dq * 16 + dd) * r + i], gs[dd], acc);
+        red[dq][kl] = acc;
+        __syncthreads();
+        if (dq == 0 && k < D) {
+            float v = ((red[0][kl] + red[1][kl]) + (red[2][kl] + red[3][kl])) * scale;
+            if (accumulate) v += ld<T>(gA + (long)i * D + k);
+            st<T>(gA + (long)i * D + k, v);
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void lora_grad_b_kernel(const float* __restrict__ G, int splits, long slice_stride,
+                                                          const T* __restrict__ la_q, const T* __restrict__ la_v,
+                                                          T* g_lb_q, T* g_lb_v, HeadList full, int D, int r, float scale,
+                                                          int accumulate) {
+    __shared__ float red[4][4][kMaxRank];        // [wave][row][i]
+    const int j = blockIdx.x >> 1, plane = blockIdx.x & 1;
+    T* gB = plane == 0 ? g_lb_q : g_lb_v;
+    if (!gB) return;
     const int p = plane == 0 ? 0 : 2;
     const int h = full.h[j];
     const T* A = (plane == 0 ? la_q : la_v) + (long)h * r * D;
-    const T* B = (plane == 0 ? lb_q : lb_v) + (long)h * 64 * r;
-    T* gA = plane == 0 ? g_la_q : g_la_v;
-    T* gB = plane == 0 ? g_lb_q : g_lb_v;
-    const float* Gh = G + ((long)(j * 3 + p) * 64) * D;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (gB) {
-        gB += (long)h * 64 * r;
-        for (int pair = wave; pair < 64 * r; pair += 4) {
-            const int d = pair / r, i = pair % r;
-            float acc = 0.f;
-            for (int k = lane; k < D; k += 64) {
-                float gsum = 0.f;
-                for (int s = 0; s < splits; ++s) gsum += Gh[s * slice_stride + (long)d * D + k];
-                acc += gsum * ld<T>(A + (long)i * D + k);
+    const int d0 = blockIdx.y * 4;               // this workgroup's 4 rows of G_h
+    for (int i = 0; i < r; ++i) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int k = threadIdx.x; k < D; k += 256) {
+            const float a = ld<T>(A + (long)i * D + k);
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                const float* src = G + ((long)(j * 3 + p) * 64 + d0 + dd) * D + k;
+                float v = 0.f;
+                for (int s = 0; s < splits; ++s) v += src[s * slice_stride];
+                acc[dd] = fmaf(v, a, acc[dd]);
             }
-            acc = wave_sum(acc) * scale;
-            if (lane == 0) {
-                if (accumulate) acc += ld<T>(gB + d * r + i);
-                st<T>(gB + d * r + i, acc);
-            }
+        }
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) {
+            const float v = wave_sum(acc[dd]);
+            if (lane == 0) red[wave][dd][i] = v;
         }
     }
-    if (gA) {
-        gA += (long)h * r * D;
-        for (int e = threadIdx.x; e < r * D; e += 256) {
-            const int i = e / D, k = e % D;
-            float acc = 0.f;
-            for (int d = 0; d < 64; ++d) {
-                float gsum = 0.f;
-                for (int s = 0; s < splits; ++s) gsum += Gh[s * slice_stride + (long)d * D + k];
-                acc += ld<T>(B + d * r + i) * gsum;
-            }
-            acc *= scale;
-            if (accumulate) acc += ld<T>(gA + e);
-            st<T>(gA + e, acc);
-        }
+    __syncthreads();
+    gB += (long)h * 64 * r;
+    for (int e = threadIdx.x; e < 4 * r; e += 256) {
+        const int dd = e / r, i = e % r;
+        float v = ((red[0][dd][i] + red[1][dd][i]) + (red[2][dd][i] + red[3][dd][i])) * scale;
+        T* o = gB + (long)(d0 + dd) * r + i;
+        if (accumulate) v += ld<T>(o);
+        st<T>(o, v);
     }
 }
 
@@ -468,12 +508,23 @@ hipError_t launch_lora_project(int dtype, const float* G, int splits, long slice
                                const void* la_v, const void* lb_q, const void* lb_v, void* g_la_q, void* g_la_v,
                                void* g_lb_q, void* g_lb_v, const HeadList& full, int H, int D, int r, float scale,
                                int accumulate, hipStream_t s) {
+    (void)H;
     if (full.n <= 0) return hipSuccess;
-    const dim3 grid(full.n, 2), block(256);
-    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(lora_project_kernel<T>, grid, block, 0, s, G, splits, slice_stride,
-                                            (const T*)la_q, (const T*)la_v, (const T*)lb_q, (const T*)lb_v,
-                                            (T*)g_la_q, (T*)g_la_v, (T*)g_lb_q, (T*)g_lb_v, full, H, D, r, scale,
-                                            accumulate);)
+    const dim3 block(256);
+    if (g_la_q || g_la_v) {
+        const dim3 grid(full.n * 2, (D + 63) / 64);
+        D2FT_DISPATCH(dtype, hipLaunchKernelGGL(lora_grad_a_kernel<T>, grid, block, 0, s, G, splits, slice_stride,
+                                                (const T*)lb_q, (const T*)lb_v, (T*)g_la_q, (T*)g_la_v, full, D, r, scale,
+                                                accumulate);)
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (g_lb_q || g_lb_v) {
+        const dim3 grid(full.n * 2, 16);
+        D2FT_DISPATCH(dtype, hipLaunchKernelGGL(lora_grad_b_kernel<T>, grid, block, 0, s, G, splits, slice_stride,
+                                                (const T*)la_q, (const T*)la_v, (T*)g_lb_q, (T*)g_lb_v, full, D, r, scale,
+                                                accumulate);)
+    }
     return hipGetLastError();
 }
 
