@@ -214,6 +214,34 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
     g_timing.flops = 2.0 * g.M * g.N * g.K;
     if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) {
         g_timing.label = gemm_mfma_config_name(g);
+        // The 256x256 tile runs one workgroup per CU, so a grid of R*256 + f tiles takes R + 1 rounds
+        // however small f is.  When the last round would be under 60% full, the rows of whole rounds
+        // go to the large tile and the remaining rows to the 128x128 tile, three of which share a CU.
+        if (!g.partial && g.tile_hint == 0 && g.M >= 512 && g.N >= 256) {
+            const long tn = (g.N + 255) / 256, tm = (g.M + 255) / 256, total = tm * tn;
+            const long rounds = total / 256, tail = total % 256;
+            if (rounds >= 1 && tail > 0 && tail < 154) {
+                const long tm_big = rounds * 256 / tn;
+                const long m_split = tm_big * 256;
+                if (m_split > 0 && m_split < g.M) {
+                    GemmArgs big = g, rest = g;
+                    big.M = (int)m_split;
+                    big.tile_hint = 1;
+                    rest.M = g.M - (int)m_split;
+                    rest.tile_hint = 2;
+                    const size_t es = 2;
+                    rest.A = static_cast<const char*>(g.A) + m_split * g.a_rs * es;
+                    rest.C = static_cast<char*>(g.C) + m_split * g.ldc * es;
+                    if (g.residual) rest.residual = static_cast<const char*>(g.residual) + m_split * g.ldr * es;
+                    if (g.Z) rest.Z = static_cast<char*>(g.Z) + m_split * g.ldz * es;
+                    if (gemm_mfma_supported(big) && gemm_mfma_supported(rest)) {
+                        hipError_t e = launch_gemm_mfma(big, s);
+                        if (e != hipSuccess) return e;
+                        return launch_gemm_mfma(rest, s);
+                    }
+                }
+            }
+        }
         return launch_gemm_mfma(g, s);
     }
     g_timing.label = "gemm_simple";
