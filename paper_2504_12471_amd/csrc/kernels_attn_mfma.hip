@@ -64,14 +64,47 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
     return r;
 }
 
-// copy rows [0, rows_valid) x 64 channels of a [token][ld] global tile to LDS rows of `stride`, zero rows above
+// copy rows [0, rows_valid) x 64 channels of a [token][ld] global tile to LDS rows of `stride`, zero rows above.
+// All global loads of the tile are issued before the first LDS store, so their latencies overlap.
 template <int TP>
 __device__ __forceinline__ void load_tile64(const bf16* __restrict__ g, long ld, int rows_valid, bf16* lds, int stride) {
-    for (int c = threadIdx.x; c < TP * 8; c += 256) {
+    constexpr int N = TP * 8 / 256;
+    u32x4 v[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = threadIdx.x + i * 256;
         const int r = c >> 3, ch = (c & 7) * 8;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (r < rows_valid) v = *reinterpret_cast<const u32x4*>(g + (long)r * ld + ch);
-        *reinterpret_cast<u32x4*>(lds + r * stride + ch) = v;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (r < rows_valid) v[i] = *reinterpret_cast<const u32x4*>(g + (long)r * ld + ch);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = threadIdx.x + i * 256;
+        *reinterpret_cast<u32x4*>(lds + (c >> 3) * stride + (c & 7) * 8) = v[i];
+    }
+}
+// the same for two tiles at once (K and V): twice the loads in flight
+template <int TP>
+__device__ __forceinline__ void load_two_tiles64(const bf16* __restrict__ g0, const bf16* __restrict__ g1, long ld,
+                                                 int rows_valid, bf16* lds0, int stride0, bf16* lds1, int stride1) {
+    constexpr int N = TP * 8 / 256;
+    u32x4 v0[N], v1[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = threadIdx.x + i * 256;
+        const int r = c >> 3, ch = (c & 7) * 8;
+        v0[i] = u32x4{0u, 0u, 0u, 0u};
+        v1[i] = u32x4{0u, 0u, 0u, 0u};
+        if (r < rows_valid) {
+            v0[i] = *reinterpret_cast<const u32x4*>(g0 + (long)r * ld + ch);
+            v1[i] = *reinterpret_cast<const u32x4*>(g1 + (long)r * ld + ch);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = threadIdx.x + i * 256;
+        *reinterpret_cast<u32x4*>(lds0 + (c >> 3) * stride0 + (c & 7) * 8) = v0[i];
+        *reinterpret_cast<u32x4*>(lds1 + (c >> 3) * stride1 + (c & 7) * 8) = v1[i];
     }
 }
 
@@ -94,8 +127,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
     const int b = blockIdx.x / n_live, j = blockIdx.x % n_live;
     const long row0 = (long)b * tokens;
     const bf16* Qb = qkv + row0 * ldq + j * 192;
-    load_tile64<TP>(Qb + 64, ldq, tokens, Ks, kKS);
-    load_tile64<TP>(Qb + 128, ldq, tokens, Vs, kVS);
+    load_two_tiles64<TP>(Qb + 64, Qb + 128, ldq, tokens, Ks, kKS, Vs, kVS);
     __syncthreads();
 
     for (int qt = wave; qt < KT; qt += 4) {
@@ -108,50 +140,98 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
             if (q_ok) v = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + kk * 16 + 8 * h);
             qf[kk] = __builtin_bit_cast(bf16x8, v);
         }
-        // S^T tiles: rows = keys of tile u, column = this lane's query
+        // S^T tiles: rows = keys of tile u, column = this lane's query.  K fragments of tile u+1 are
+        // fetched from LDS while the MFMAs of tile u run (one read behind each MFMA).
         f32x16 s[KT];
+        const f32x16 zero_acc = zero16();   // shared C operand of every tile's first MFMA
+        bf16x8 kf[2][4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kf[0][kk] = frag_rows(Ks, kKS, c, kk * 16 + 8 * h);
 #pragma unroll
         for (int u = 0; u < KT; ++u) {
-            s[u] = zero16();
+            if (u + 1 < KT) {
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kKS, u * 32 + c, kk * 16 + 8 * h), qf[kk],
-                                                               s[u], 0, 0, 0);
+                for (int kk = 0; kk < 4; ++kk) kf[(u + 1) & 1][kk] = frag_rows(Ks, kKS, (u + 1) * 32 + c, kk * 16 + 8 * h);
+            }
+            s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u & 1][0], qf[0], zero_acc, 0, 0, 0);
+#pragma unroll
+            for (int kk = 1; kk < 4; ++kk)
+                s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u & 1][kk], qf[kk], s[u], 0, 0, 0);
+            if (u + 1 < KT) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // first V fragments are fetched under the softmax arithmetic
+        bf16x8 vf[2][4];
+#pragma unroll
+        for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) vf[0][gp * 2 + dt] = frag_tr(Vs, kVS, 16 * gp, dt * 32, lane);
         float m = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < KT; ++u)
+        for (int u = 0; u < KT; ++u) {
+            if (u * 32 + 31 >= tokens) {   // only tiles that reach past the last token need the mask
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = u * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                const float v = key < tokens ? s[u][e] : -INFINITY;
-                s[u][e] = v;
-                m = fmaxf(m, v);
+                for (int e = 0; e < 16; ++e) {
+                    const int key = u * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+                    if (key >= tokens) s[u][e] = -INFINITY;
+                }
             }
+            // three-input maxima: half the instructions of a chain of two-input ones
+            float t0 = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
+            float t1 = fmaxf(fmaxf(s[u][3], s[u][4]), s[u][5]);
+            float t2 = fmaxf(fmaxf(s[u][6], s[u][7]), s[u][8]);
+            float t3 = fmaxf(fmaxf(s[u][9], s[u][10]), s[u][11]);
+            float t4 = fmaxf(fmaxf(s[u][12], s[u][13]), s[u][14]);
+            t0 = fmaxf(fmaxf(t0, t1), t2);
+            t3 = fmaxf(fmaxf(t3, t4), s[u][15]);
+            m = fmaxf(fmaxf(m, t0), t3);
+        }
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         const float cexp = kScale * kLog2e;
+        const float mc = m * cexp;
         float sum = 0.f;
 #pragma unroll
         for (int u = 0; u < KT; ++u)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f((s[u][e] - m) * cexp);
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[u][e], cexp, -mc));
                 s[u][e] = p;
                 sum += p;
             }
         sum += __shfl_xor(sum, 32, 64);
-        // O^T = V^T P^T: rows = channels, column = this lane's query
+        // O^T = V^T P^T: rows = channels, column = this lane's query; V fragments one tile ahead
         f32x16 ot[2] = {zero16(), zero16()};
 #pragma unroll
-        for (int u = 0; u < KT; ++u)
+        for (int u = 0; u < KT; ++u) {
+            if (u + 1 < KT) {
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+                        vf[(u + 1) & 1][gp * 2 + dt] = frag_tr(Vs, kVS, (u + 1) * 32 + 16 * gp, dt * 32, lane);
+            }
 #pragma unroll
             for (int gp = 0; gp < 2; ++gp) {
                 const bf16x8 pf = pack8(s[u], 8 * gp);
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt)
-                    ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Vs, kVS, u * 32 + 16 * gp, dt * 32, lane), pf,
-                                                                    ot[dt], 0, 0, 0);
+                    ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u & 1][gp * 2 + dt], pf, ot[dt], 0, 0, 0);
             }
+            if (u + 1 < KT) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if (q_ok) {
             const float inv = 1.0f / sum;
             bf16* orow = o + (row0 + q) * ldo + j * 64;
@@ -226,20 +306,24 @@ __global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restri
     const bf16* Ob = o + row0 * ldo + j * 64;
     bf16* dQb = dqkv + row0 * ld_dqkv + j * 192;
 
-    load_tile64<TP>(Qb + 64, ldq, tokens, Ks, kTS);
-    load_tile64<TP>(Qb + 128, ldq, tokens, Vs, kKS);
+    load_two_tiles64<TP>(Qb + 64, Qb + 128, ldq, tokens, Ks, kTS, Vs, kKS);
     for (int q = threadIdx.x; q < TP; q += 256) {
         float l = 0.f, dl = 0.f;
         if (q < tokens) {
             l = lse[(long)j * rows_total + row0 + q];
-            float a[8], g[8];
+            u32x4 a[8], g[8];
 #pragma unroll
-            for (int ch = 0; ch < 64; ch += 8) {
-                load8(dOb + (long)q * ld_do + ch, a);
-                load8(Ob + (long)q * ldo + ch, g);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dl = fmaf(a[i], g[i], dl);
+            for (int ch = 0; ch < 8; ++ch) {
+                a[ch] = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ch * 8);
+                g[ch] = *reinterpret_cast<const u32x4*>(Ob + (long)q * ldo + ch * 8);
             }
+#pragma unroll
+            for (int ch = 0; ch < 8; ++ch)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    dl = fmaf(__uint_as_float(a[ch][i] << 16), __uint_as_float(g[ch][i] << 16), dl);
+                    dl = fmaf(__uint_as_float(a[ch][i] & 0xffff0000u), __uint_as_float(g[ch][i] & 0xffff0000u), dl);
+                }
         }
         lse_s[q] = l * kLog2e;
         del_s[q] = dl;
@@ -255,18 +339,25 @@ __global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restri
         }
     const float cexp = kScale * kLog2e;
 
+    // one 16-byte chunk of Q_i and of dO_i per thread; the chunks of tile i+1 are fetched while tile i is processed
+    const int ld_r = threadIdx.x >> 3, ld_ch = (threadIdx.x & 7) * 8;
+    u32x4 nq = {0u, 0u, 0u, 0u}, nd = {0u, 0u, 0u, 0u};
+    if (ld_r < tokens) {
+        nq = *reinterpret_cast<const u32x4*>(Qb + (long)ld_r * ldq + ld_ch);
+        nd = *reinterpret_cast<const u32x4*>(dOb + (long)ld_r * ld_do + ld_ch);
+    }
     for (int i = 0; i < KT; ++i) {
         __syncthreads();   // previous query tile fully consumed (and the prologue's LDS writes are visible)
+        *reinterpret_cast<u32x4*>(Qs + ld_r * kTS + ld_ch) = nq;
+        *reinterpret_cast<u32x4*>(dOs + ld_r * kTS + ld_ch) = nd;
         {
-            const int r = threadIdx.x >> 3, ch = (threadIdx.x & 7) * 8;
-            const int q = i * 32 + r;
-            u32x4 vq = {0u, 0u, 0u, 0u}, vd = {0u, 0u, 0u, 0u};
-            if (q < tokens) {
-                vq = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + ch);
-                vd = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ch);
+            const int q = (i + 1) * 32 + ld_r;
+            nq = u32x4{0u, 0u, 0u, 0u};
+            nd = u32x4{0u, 0u, 0u, 0u};
+            if (i + 1 < KT && q < tokens) {
+                nq = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + ld_ch);
+                nd = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ld_ch);
             }
-            *reinterpret_cast<u32x4*>(Qs + r * kTS + ch) = vq;
-            *reinterpret_cast<u32x4*>(dOs + r * kTS + ch) = vd;
         }
         __syncthreads();
         float L[16], DL[16];
