@@ -201,6 +201,12 @@ void timing_end(hipStream_t st) {
     g_timing.open = false;
 }
 
+#define D2FT_TRY_UNTIMED(expr)                      \
+    do {                                            \
+        hipError_t e__ = (expr);                    \
+        if (e__ != hipSuccess) return D2FT_EDEVICE; \
+    } while (0)
+
 // every launch site has the stream in a variable called st
 #define D2FT_TRY(expr)                              \
     do {                                            \
@@ -210,10 +216,18 @@ void timing_end(hipStream_t st) {
         if (e__ != hipSuccess) return D2FT_EDEVICE; \
     } while (0)
 
-hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) {
+// one timed GEMM launch (the launch sites use D2FT_TRY_UNTIMED around run_gemm)
+hipError_t timed_mfma(const GemmArgs& g, hipStream_t st) {
+    timing_begin(st, "gemm");
+    g_timing.label = gemm_mfma_config_name(g);
     g_timing.flops = 2.0 * g.M * g.N * g.K;
+    const hipError_t e = launch_gemm_mfma(g, st);
+    timing_end(st);
+    return e;
+}
+
+hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) {
     if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) {
-        g_timing.label = gemm_mfma_config_name(g);
         // The 256x256 tile runs one workgroup per CU, so a grid of R*256 + f tiles takes R + 1 rounds
         // however small f is.  When the last round would be under 60% full, the rows of whole rounds
         // go to the large tile and the remaining rows to the 128x128 tile, three of which share a CU.
@@ -235,17 +249,21 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
                     if (g.residual) rest.residual = static_cast<const char*>(g.residual) + m_split * g.ldr * es;
                     if (g.Z) rest.Z = static_cast<char*>(g.Z) + m_split * g.ldz * es;
                     if (gemm_mfma_supported(big) && gemm_mfma_supported(rest)) {
-                        hipError_t e = launch_gemm_mfma(big, s);
+                        hipError_t e = timed_mfma(big, s);
                         if (e != hipSuccess) return e;
-                        return launch_gemm_mfma(rest, s);
+                        return timed_mfma(rest, s);
                     }
                 }
             }
         }
-        return launch_gemm_mfma(g, s);
+        return timed_mfma(g, s);
     }
-    g_timing.label = "gemm_simple";
-    return launch_gemm_simple(g, d->dtype, s);
+    timing_begin(s, "gemm");
+    g_timing.label = "gemm_simple_kernel";
+    g_timing.flops = 2.0 * g.M * g.N * g.K;
+    const hipError_t e = launch_gemm_simple(g, d->dtype, s);
+    timing_end(s);
+    return e;
 }
 
 hipError_t run_attn_fwd(const d2ft_block_desc* d, const void* qkv, long ldq, void* o, long ldo, float* lse, int batch,
@@ -318,7 +336,7 @@ d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop
     g.partial = part;
     g.splits = pick_splits(out_rows, out_cols, s.M, &g.tile_hint);
     if (splits_out) *splits_out = g.splits;
-    D2FT_TRY(run_gemm(g, d, st));
+    D2FT_TRY_UNTIMED(run_gemm(g, d, st));
     if (reduce)
         D2FT_TRY(launch_reduce_partials(s.dtype, part, g.splits, (long)out_rows * out_cols, out_rows, out_cols, out,
                                         ldo, red_remap, tbl, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
@@ -443,7 +461,7 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         } else {
             g.B = w->w_qkv; g.b_rs = 1; g.b_cs = s.D; g.remap = REMAP_B_N;
         }
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
         // softmax attention per (image, live head); log-sum-exp kept for p_f heads only
         D2FT_TRY(run_attn_fwd(desc, sv + SL.qkv, nl * 192, sv + SL.o, nl * 64, (float*)(sv + SL.lse), s.B, s.T, nl, nf,
                               st));
@@ -456,7 +474,7 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         p.C = sv + SL.x1; p.ldc = s.D;
         p.bias = w->b_o;
         p.residual = x; p.ldr = s.D;
-        D2FT_TRY(run_gemm(p, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(p, desc, st));
         x1 = sv + SL.x1;
     }
     void* v = sv + SL.v;
@@ -470,7 +488,7 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         g.C = sv + SL.g; g.ldc = s.Dm;
         g.bias = w->b1;
         g.act = ACT_GELU; g.Z = sv + SL.z; g.ldz = s.Dm;
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     {   // y = x1 + g W2^T + b2
         GemmArgs g = gemm_base();
@@ -480,7 +498,7 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         g.C = y; g.ldc = s.D;
         g.bias = w->b2;
         g.residual = x1; g.ldr = s.D;
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     return D2FT_OK;
 }
@@ -536,7 +554,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         g.M = M; g.N = s.Dm; g.K = s.D;
         g.C = ws + WL.dz; g.ldc = s.Dm;
         g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = s.Dm;
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     if (grads->w1) {   // dW1 = dz^T v
         rc = weight_grad(desc, s, ws + WL.dz, s.Dm, sv + SL.v, s.D, s.Dm, s.D, part, grads->w1, s.D, RED_REMAP_NONE, none, st);
@@ -552,7 +570,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         g.B = w->w1; g.b_rs = s.D; g.b_cs = 1;
         g.M = M; g.N = s.D; g.K = s.Dm;
         g.C = ws + WL.dv; g.ldc = s.D;
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     if (grads->ln2_g || grads->ln2_b) {
         const int chunks = pick_chunks(s.M);
@@ -607,7 +625,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         g.B = w->w_o; g.b_rs = (long)s.H * 64; g.b_cs = 1; g.remap = REMAP_B_N;
         g.M = M; g.N = nf * 64; g.K = s.D;
         g.C = ws + WL.d_o; g.ldc = ld_do;
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     if (grads->w_o) {   // dWo[:, head cols] = dx1^T O_h
         rc = weight_grad(desc, s, dx1, s.D, sv + SL.o, ldo, s.D, nf * 64, part, grads->w_o, (long)s.H * 64, RED_REMAP_COLS,
@@ -651,7 +669,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         g.b_rs = s.D; g.b_cs = 1;
         g.M = M; g.N = s.D; g.K = nf * 192;
         g.C = ws + WL.du; g.ldc = s.D;
-        D2FT_TRY(run_gemm(g, desc, st));
+        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     if (grads->ln1_g || grads->ln1_b) {
         const int chunks = pick_chunks(s.M);
