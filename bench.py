@@ -70,8 +70,8 @@ def recorded_traffic(kernel: str, workload: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vit_b16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-all-full", action="store_true")
@@ -114,6 +114,7 @@ def main() -> int:
     stack = P.BlockStack(desc, dws, w.dtype, grad_fields)
     x, dy = P.to_device(s.x, w.dtype), P.to_device(s.dy, w.dtype)
 
+    # step time measured the same with 3 and with 100 warm-up steps; the default of 20 is margin
     def timed(mask, steps, warmup):
         for _ in range(warmup):
             stack.step(x, dy, mask)
@@ -131,13 +132,13 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     ms = timed(ops, args.steps, args.warmup)
-    ms_full = None if args.no_all_full else timed(full_ops, args.steps, min(args.warmup, 1))
+    ms_full = None if args.no_all_full else timed(full_ops, args.steps, min(args.warmup, 20))
 
     # per-kernel durations, measured with HIP events inside the library on the launch stream
     stack.step(x, dy, ops)
     torch.cuda.synchronize()
     P.d2ft_timing_enable(True)
-    n_prof = 2
+    n_prof = 10
     for _ in range(n_prof):
         stack.step(x, dy, ops)
     torch.cuda.synchronize()

@@ -110,7 +110,7 @@ struct GemmArgs {
     long ldz;
     float* partial;       // non-null: split-K mode, raw fp32 sums go to partial[split][M][N]
     int splits;
-    int tile_hint;        // 0: kernel chooses its tile, 1: 256x256, 2: 128x128
+    int tile_hint;        // 0: kernel chooses its tile, 1: 256x256, 2: 128x128, 3: 192x256
     Remap64 tbl;
 };
 

@@ -15,6 +15,7 @@
 //
 // B's n or k index may go through a 64-granular remap table: that is how the compacted
 // live-head list selects rows / columns of the full weight tensors without copying them.
+#include <cstdio>
 #include <type_traits>
 
 #include "d2ft_common.h"
@@ -196,14 +197,17 @@ __device__ __forceinline__ void pace_first_group() {
     }
 }
 
+// bytes of the epilogue's fp32 stage: one 32-row band of every wavefront's tile, rows padded by 4 floats
+template <int BN, int WGM, int WGN> constexpr size_t stage_bytes() {
+    return (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
+}
+
 // ---- workgroup -> tile mapping ----
 // The chip has 8 XCDs with one L2 each and workgroup ids are dealt to them round-robin, so ids
 // with the same value mod 8 are renumbered to a contiguous range of tiles; inside that range
 // tiles are walked in groups of 8 tile rows so that the workgroups resident on one XCD share
 // A and B slabs through its L2.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, int& split) {
-    const int total = gridDim.x;
-    const int pid = blockIdx.x;
+__device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, int tiles_n, int& tm, int& tn, int& split) {
     const int xcd = pid & 7, idx = pid >> 3;
     const int lid = xcd * (total >> 3) + min(xcd, total & 7) + idx;
     const int per_split = tiles_m * tiles_n;
@@ -236,33 +240,41 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
     const bf16* __restrict__ B = static_cast<const bf16*>(g.B);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    int tile_m, tile_n, split;
-    tile_of_block((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, tile_m, tile_n, split);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    int kb = 0, ke = g.K;
-    if (g.partial) {
-        int per = (g.K + g.splits - 1) / g.splits;
-        per = (per + BK - 1) / BK * BK;
-        kb = split * per;
-        ke = min(g.K, kb + per);
-    }
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n * (g.partial ? g.splits : 1);
 
     f32x16 acc[MT][NT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int u = 0; u < NT; ++u)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[t][u][e] = 0.f;
-
     SlabLoader<BM, BK, A_COL, kThreads> la;
     SlabLoader<BN, BK, B_COL, kThreads> lb;
-    // strides as (index stride, k stride)
-    la.template init<false>(A, g.a_rs, g.a_cs, m0, g.M, g.tbl);
-    lb.template init<REMAP == REMAP_B_N>(B, g.b_cs, g.b_rs, n0, g.N, g.tbl);
 
-    const int nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
+    // The kernel is persistent: workgroup b works on tiles b, b + gridDim.x, ... (the grid is a
+    // multiple of 8, so all of them map to its own XCD's range).  setup_tile fixes a tile's
+    // coordinates and K range and fetches its first slab into the loader registers; it is called for
+    // the next tile ahead of the current tile's epilogue, and the epilogue's global stores drain while
+    // the next tile is being multiplied.
+    int m0 = 0, n0 = 0, split = 0, kb = 0, ke = 0, nslabs = 0;
+    auto setup_tile = [&](int pid) {
+        int tile_m, tile_n;
+        tile_of_block(pid, total, tiles_m, tiles_n, tile_m, tile_n, split);
+        m0 = tile_m * BM;
+        n0 = tile_n * BN;
+        kb = 0;
+        ke = g.K;
+        if (g.partial) {
+            int per = (g.K + g.splits - 1) / g.splits;
+            per = (per + BK - 1) / BK * BK;
+            kb = split * per;
+            ke = min(g.K, kb + per);
+        }
+        // strides as (index stride, k stride)
+        la.template init<false>(A, g.a_rs, g.a_cs, m0, g.M, g.tbl);
+        lb.template init<REMAP == REMAP_B_N>(B, g.b_cs, g.b_rs, n0, g.N, g.tbl);
+        nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
+        if (nslabs > 0) {
+            la.template load<false>(kb, ke, g.tbl);
+            lb.template load<REMAP == REMAP_B_K>(kb, ke, g.tbl);
+        }
+    };
 
     // Software pipeline.  LDS buffer (s & 1) holds slab s; the registers of the slab loaders hold
     // slab s + 1, fetched one slab ahead; operand fragments are double-buffered too, so every LDS
@@ -292,9 +304,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int NW = SlabLoader<BM, BK, A_COL, kThreads>::kPerThread + SlabLoader<BN, BK, B_COL, kThreads>::kPerThread;   // stores = loads per slab
     static_assert(BK == 64, "the pipeline below is written for four MFMA groups per slab");
 
+    setup_tile(blockIdx.x);
+    for (int pid = blockIdx.x; pid < total; pid += gridDim.x) {
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][u][e] = 0.f;
     if (nslabs > 0) {
-        la.template load<false>(kb, ke, g.tbl);
-        lb.template load<REMAP == REMAP_B_K>(kb, ke, g.tbl);
         la.store(As0);
         lb.store(Bs0);
         if (nslabs > 1) {
@@ -354,6 +372,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
         if (s < nslabs) slab(s, std::false_type{}, std::false_type{});
     }
     __syncthreads();   // the epilogue reuses the operand buffers
+    const int em0 = m0, en0 = n0, esplit = split;
+    if (pid + (int)gridDim.x < total) setup_tile(pid + gridDim.x);   // its first slab arrives under the epilogue
 
     // ---- epilogue ----
     // Accumulator element e of MFMA tile (t,u) is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
@@ -369,7 +389,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
     const bf16* bias = static_cast<const bf16*>(g.bias);
     const bf16* R = static_cast<const bf16*>(g.residual);
     bf16* Z = static_cast<bf16*>(g.Z);
-    float* P = g.partial ? g.partial + (long)split * g.M * g.N : nullptr;
+    float* P = g.partial ? g.partial + (long)esplit * g.M * g.N : nullptr;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
 #pragma unroll
@@ -382,8 +402,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
         for (int c = 0; c < CPL; ++c) {
             const int id = lane + 64 * c;
             const int r = id / CPR, cc = (id % CPR) * 8;
-            const int m = m0 + wm * WTM + t * 32 + r;
-            const int n = n0 + wn * WTN + cc;
+            const int m = em0 + wm * WTM + t * 32 + r;
+            const int n = en0 + wn * WTN + cc;
             if (m < g.M && n < g.N) {
                 float v[8];
                 const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
@@ -421,12 +441,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
         }
         __builtin_amdgcn_wave_barrier();
     }
+    __syncthreads();   // the stage area is operand buffer space of the next tile
+    }
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 constexpr size_t lds_bytes() {
     constexpr size_t slabs = 2 * (slab_elems<BM, BK, A_COL>() + slab_elems<BN, BK, B_COL>()) * sizeof(bf16);
-    constexpr size_t stage = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
+    constexpr size_t stage = stage_bytes<BN, WGM, WGN>();
     return slabs > stage ? slabs : stage;
 }
 
@@ -434,15 +456,22 @@ template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int 
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, A_COL, B_COL>();
     auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP>;
-    static bool attr_set = false;   // per instantiation; setting it again is harmless
-    if (!attr_set) {
+    static int resident = 0;   // per instantiation: workgroups the chip holds at once, a multiple of 8
+    if (resident == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        int dev = 0, cus = 0, per_cu = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * WGM * WGN, lds)) != hipSuccess) return e;
+        if (per_cu < 1) per_cu = 1;
+        resident = cus * per_cu / 8 * 8;
+        if (resident < 8) resident = 8;
     }
     const int splits = g.partial ? g.splits : 1;
     const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * splits;
-    const dim3 grid((unsigned)tiles), block(64 * WGM * WGN);
+    // persistent: no more workgroups than are resident together; each walks tiles b, b + grid, ...
+    const dim3 grid((unsigned)(tiles < resident ? tiles : resident)), block(64 * WGM * WGN);
     hipLaunchKernelGGL(kern, grid, block, lds, s, g);
     return hipGetLastError();
 }
@@ -470,7 +499,7 @@ inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
 
-int g_gemm_tile_override = 0;   // development aid: 0 = heuristic, 1 = 256x256, 2 = 128x128
+int g_gemm_tile_override = 0;   // development aid: 0 = heuristic, 1 = 256x256, 2 = 128x128, 3 = 192x256
 
 bool gemm_mfma_supported(const GemmArgs& g) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
@@ -506,41 +535,43 @@ bool gemm_mfma_supported(const GemmArgs& g) {
     return true;
 }
 
-static bool use_big_tile(const GemmArgs& g) {
-    // tile choice: the 256x256 tile moves half the operand bytes per FLOP of the 128x128 one and
-    // measures faster on one MI355X even when it leaves CUs idle, down to about 100 workgroups
-    const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * (g.partial ? g.splits : 1);
-    if (g_gemm_tile_override) return g_gemm_tile_override != 2;
-    if (g.tile_hint) return g.tile_hint == 1;
-    return big >= 96 && g.M >= 256 && g.N >= 256;
+// Tile choice: 0 = 128x128 (two workgroups per CU), 1 = 256x256, 3 = 192x256 (one workgroup per CU each).
+// The 256x256 tile moves the fewest operand bytes per FLOP and measures fastest even when it leaves CUs
+// idle, down to about 100 workgroups; when its grid is under one round of the chip's 256 CUs, the
+// 192-row tile spreads the same work over more of them.
+static int pick_tile(const GemmArgs& g) {
+    if (g_gemm_tile_override) return g_gemm_tile_override == 2 ? 0 : g_gemm_tile_override;
+    if (g.tile_hint) return g.tile_hint == 2 ? 0 : g.tile_hint;
+    const long tn = (g.N + 255) / 256, splits = g.partial ? g.splits : 1;
+    const long big = (long)((g.M + 255) / 256) * tn * splits;
+    if (!(big >= 96 && g.M >= 256 && g.N >= 256)) return 0;
+    const long mid = (long)((g.M + 191) / 192) * tn * splits;
+    if (big < 256 && mid <= 256 && mid > big) return 3;
+    return 1;
 }
 
 const char* gemm_mfma_config_name(const GemmArgs& g) {
     // the instantiation's name as a profiler prints it, so timing records and kernel traces can be matched
     const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
-    const int layout = a_col ? 2 : (b_col ? 1 : 0);
-    const int remap = g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0);
-    static const char* names[2][3][3] = {
-        {{"gemm_mfma_kernel<128, 128, 64, 2, 2, false, false, 0>", "gemm_mfma_kernel<128, 128, 64, 2, 2, false, false, 1>",
-          "gemm_mfma_kernel<128, 128, 64, 2, 2, false, false, 2>"},
-         {"gemm_mfma_kernel<128, 128, 64, 2, 2, false, true, 0>", "gemm_mfma_kernel<128, 128, 64, 2, 2, false, true, 1>",
-          "gemm_mfma_kernel<128, 128, 64, 2, 2, false, true, 2>"},
-         {"gemm_mfma_kernel<128, 128, 64, 2, 2, true, true, 0>", "gemm_mfma_kernel<128, 128, 64, 2, 2, true, true, 1>",
-          "gemm_mfma_kernel<128, 128, 64, 2, 2, true, true, 2>"}},
-        {{"gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 0>", "gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 1>",
-          "gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 2>"},
-         {"gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 0>", "gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 1>",
-          "gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 2>"},
-         {"gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 0>", "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 1>",
-          "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 2>"}}};
-    return names[use_big_tile(g) ? 1 : 0][layout][remap];
+    const int tile = pick_tile(g);
+    static char names[4][3][3][64];
+    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)];
+    if (!name[0]) {
+        const int bm = tile == 0 ? 128 : (tile == 3 ? 192 : 256), bn = tile == 0 ? 128 : 256;
+        snprintf(name, sizeof(names[0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d>", bm, bn, tile == 0 ? 2 : 4,
+                 a_col ? "true" : "false", b_col ? "true" : "false",
+                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0));
+    }
+    return name;
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     if (!gemm_mfma_supported(g)) return hipErrorNotSupported;
-    const bool use_big = use_big_tile(g);
-    if (use_big) return launch_layout<256, 256, 64, 2, 4>(g, s);
-    return launch_layout<128, 128, 64, 2, 2>(g, s);
+    switch (pick_tile(g)) {
+        case 1: return launch_layout<256, 256, 64, 2, 4>(g, s);
+        case 3: return launch_layout<192, 256, 64, 2, 4>(g, s);
+        default: return launch_layout<128, 128, 64, 2, 2>(g, s);
+    }
 }
 
 }  // namespace d2ft

@@ -202,7 +202,20 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, lo
 #pragma unroll
     for (int i = 0; i < 8; ++i) a[i] = b[i] = 0.f;
     if (col < cols) {
-        for (int r = r0 + rg; r < r1; r += 8) {
+        int r = r0 + rg;
+        if (!LN) {
+            // four rows in flight per thread; each thread still adds its rows in ascending order
+            for (; r + 24 < r1; r += 32) {
+                float d4[4][8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) load8(X + (long)(r + 8 * j) * ldx + col, d4[j]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) a[i] += d4[j][i];
+            }
+        }
+        for (; r < r1; r += 8) {
             load8(X + (long)r * ldx + col, dv);
             if (LN) {
                 load8(x + (long)r * ldx + col, xv);
@@ -254,7 +267,17 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     const int r = (int)(idx / cq), c = (int)(idx % cq) * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     const float* src = partial + (long)r * cols + c;
-    for (int k = 0; k < splits; ++k) {
+    // slices are added in index order; eight loads are in flight at a time so that a reduction over many
+    // slices is not a chain of memory latencies
+    int k = 0;
+    for (; k + 8 <= splits; k += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4*>(src + (k + j) * slice_stride);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
+    }
+    for (; k < splits; ++k) {
         const float4 v = *reinterpret_cast<const float4*>(src + k * slice_stride);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
