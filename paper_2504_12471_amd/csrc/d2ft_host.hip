@@ -230,7 +230,7 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
     if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) {
         // The 256x256 tile runs one workgroup per CU, so a grid of R*256 + f tiles takes R + 1 rounds
         // however small f is.  When the last round would be under 60% full, the rows of whole rounds
-        // go to the large tile and the remaining rows to the 128x128 tile, three of which share a CU.
+        // go to the large tile and the remaining rows to the 128x128 tile, two of which share a CU.
         if (!g.partial && g.tile_hint == 0 && g.M >= 512 && g.N >= 256) {
             const long tn = (g.N + 255) / 256, tm = (g.M + 255) / 256, total = tm * tn;
             const long rounds = total / 256, tail = total % 256;
@@ -300,7 +300,7 @@ GemmArgs gemm_base() {
 
 // Split count and tile of a weight-gradient GEMM (reduction over the token rows).  The 256x256 tile
 // runs one workgroup per CU, so the splits should bring the grid close to, but not above, the 256
-// CUs; outputs too small for that use the 128x128 tile, of which three fit a CU.
+// CUs; outputs too small for that use the 128x128 tile, of which two fit a CU.
 int pick_splits(long out_rows, long out_cols, long K, int* tile_hint) {
     const long t256 = ((out_rows + 255) / 256) * ((out_cols + 255) / 256);
     const long t128 = ((out_rows + 127) / 128) * ((out_cols + 127) / 128);
@@ -310,7 +310,7 @@ int pick_splits(long out_rows, long out_cols, long K, int* tile_hint) {
         s = 256 / t256;
     } else {
         *tile_hint = 2;
-        s = 768 / t128;
+        s = 512 / t128;
     }
     if (s > kMaxSplits) s = kMaxSplits;
     while (s > 1 && K / s < 512) --s;

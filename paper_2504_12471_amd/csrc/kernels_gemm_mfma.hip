@@ -34,8 +34,10 @@ namespace {
 template <int BK> constexpr int row_form_stride() { return BK + 8; }          // [index][k]: +16 bytes
 template <int BI> constexpr int col_form_stride() { return BI + 32; }         // [k][index]: +64 bytes
 
+// elements of one slab buffer; the last row of a col-form slab carries no padding, which is what lets
+// two 128x128 workgroups with both operands in col form share a CU's 160 KB
 template <int BI, int BK, bool COL> constexpr int slab_elems() {
-    return COL ? BK * col_form_stride<BI>() : BI * row_form_stride<BK>();
+    return COL ? (BK - 1) * col_form_stride<BI>() + BI : BI * row_form_stride<BK>();
 }
 
 // ---- global -> registers: one slab of an operand, 16-byte chunks, zero fill outside the matrix ----
@@ -223,7 +225,7 @@ __device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, i
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
     constexpr int MT = WTM / 32, NT = WTN / 32; // MFMA tiles per wavefront
