@@ -84,27 +84,29 @@ __device__ __forceinline__ void load_tile64(const bf16* __restrict__ g, long ld,
     }
 }
 // the same for two tiles at once (K and V): twice the loads in flight
-template <int TP>
+template <int TP, int NTHR = 256>
 __device__ __forceinline__ void load_two_tiles64(const bf16* __restrict__ g0, const bf16* __restrict__ g1, long ld,
                                                  int rows_valid, bf16* lds0, int stride0, bf16* lds1, int stride1) {
-    constexpr int N = TP * 8 / 256;
+    constexpr int N = (TP * 8 + NTHR - 1) / NTHR;
     u32x4 v0[N], v1[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const int c = threadIdx.x + i * 256;
+        const int c = threadIdx.x + i * NTHR;
         const int r = c >> 3, ch = (c & 7) * 8;
         v0[i] = u32x4{0u, 0u, 0u, 0u};
         v1[i] = u32x4{0u, 0u, 0u, 0u};
-        if (r < rows_valid) {
+        if (r < rows_valid) {   // rows_valid <= TP, so chunks past the tile are skipped as well
             v0[i] = *reinterpret_cast<const u32x4*>(g0 + (long)r * ld + ch);
             v1[i] = *reinterpret_cast<const u32x4*>(g1 + (long)r * ld + ch);
         }
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const int c = threadIdx.x + i * 256;
-        *reinterpret_cast<u32x4*>(lds0 + (c >> 3) * stride0 + (c & 7) * 8) = v0[i];
-        *reinterpret_cast<u32x4*>(lds1 + (c >> 3) * stride1 + (c & 7) * 8) = v1[i];
+        const int c = threadIdx.x + i * NTHR;
+        if (TP * 8 % NTHR == 0 || c < TP * 8) {
+            *reinterpret_cast<u32x4*>(lds0 + (c >> 3) * stride0 + (c & 7) * 8) = v0[i];
+            *reinterpret_cast<u32x4*>(lds1 + (c >> 3) * stride1 + (c & 7) * 8) = v1[i];
+        }
     }
 }
 
@@ -115,7 +117,7 @@ constexpr int kVS = 96;   // V rows in LDS: 192 bytes (transposing reads)
 // forward: O = softmax(Q K^T / 8) V per (image, live head); log-sum-exp saved for p_f heads
 // ---------------------------------------------------------------------------
 template <int KT>   // number of 32-token tiles
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
                                                             bf16* __restrict__ o, long ldo, float* __restrict__ lse,
                                                             int tokens, int n_live, int n_full, long rows_total) {
     constexpr int TP = KT * 32;
@@ -274,26 +276,32 @@ hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* ls
 //     dP = dO_i V_u^T             dS = P * (dP - delta_q),       delta_q = sum_d dO[q][d] O[q][d]
 //     dV_u^T += dO_i^T P          dK_u^T += Q_i^T dS             (P, dS feed the MFMA straight from registers)
 //     dQ_i^T += K_u^T dS^T        (dS goes through a 2 KB per-wavefront LDS tile to change owner)
-// Wavefront w owns key tiles w and w+4 and keeps their dK, dV accumulators in registers for the
-// whole kernel; the four partial dQ_i tiles are summed through LDS in a fixed order.
+// The workgroup has eight wavefronts; wavefront w owns key tile w (a wavefront beyond the last tile
+// only takes part in the loads and barriers) and keeps its dK, dV accumulators in registers for the
+// whole kernel.  The partial dQ_i tiles are summed through four LDS slots in a fixed order:
+// wavefronts 0..3 write, wavefronts 4..7 add theirs onto slot w-4, then the slots are added as
+// (0+1)+(2+3).
 // ---------------------------------------------------------------------------
 constexpr int kTS = 104;   // rows that are read both ways (row-form and transposing): 208 bytes
+constexpr int kBwdWaves = 8;
 
 template <int KT>
-__global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
-                                                            const bf16* __restrict__ o, long ldo,
-                                                            const float* __restrict__ lse,
-                                                            const bf16* __restrict__ d_o, long ld_do,
-                                                            bf16* __restrict__ dqkv, long ld_dqkv, int tokens,
-                                                            int n_full, long rows_total) {
+__global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
+                                                                          const bf16* __restrict__ o, long ldo,
+                                                                          const float* __restrict__ lse,
+                                                                          const bf16* __restrict__ d_o, long ld_do,
+                                                                          bf16* __restrict__ dqkv, long ld_dqkv,
+                                                                          int tokens, int n_full, long rows_total) {
+    static_assert(KT <= kBwdWaves, "one key tile per wavefront");
     constexpr int TP = KT * 32;
+    constexpr int NTHR = 64 * kBwdWaves;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* Ks = reinterpret_cast<bf16*>(smem_raw);        // [TP][kTS]
     bf16* Vs = Ks + TP * kTS;                            // [TP][kKS]
     bf16* Qs = Vs + TP * kKS;                            // [32][kTS]   current query tile
     bf16* dOs = Qs + 32 * kTS;                           // [32][kTS]
-    bf16* dSs_all = dOs + 32 * kTS;                      // [4][32 keys][32 queries]
-    float* lse_s = reinterpret_cast<float*>(dSs_all + 4 * 32 * 32);   // [TP]
+    bf16* dSs_all = dOs + 32 * kTS;                      // [8][32 keys][32 queries]
+    float* lse_s = reinterpret_cast<float*>(dSs_all + kBwdWaves * 32 * 32);   // [TP]
     float* del_s = lse_s + TP;                           // [TP]
     float* dQp = del_s + TP;                             // [4][64 channels][32 queries]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -306,8 +314,8 @@ __global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restri
     const bf16* Ob = o + row0 * ldo + j * 64;
     bf16* dQb = dqkv + row0 * ld_dqkv + j * 192;
 
-    load_two_tiles64<TP>(Qb + 64, Qb + 128, ldq, tokens, Ks, kTS, Vs, kKS);
-    for (int q = threadIdx.x; q < TP; q += 256) {
+    load_two_tiles64<TP, NTHR>(Qb + 64, Qb + 128, ldq, tokens, Ks, kTS, Vs, kKS);
+    for (int q = threadIdx.x; q < TP; q += NTHR) {
         float l = 0.f, dl = 0.f;
         if (q < tokens) {
             l = lse[(long)j * rows_total + row0 + q];
@@ -329,123 +337,129 @@ __global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restri
         del_s[q] = dl;
     }
 
-    f32x16 dKt[2][2], dVt[2][2];
+    const int u = wave;                 // this wavefront's key tile
+    const bool has_tile = u < KT;
+    f32x16 dKt[2], dVt[2];
 #pragma unroll
-    for (int us = 0; us < 2; ++us)
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-            dKt[us][dt] = zero16();
-            dVt[us][dt] = zero16();
-        }
+    for (int dt = 0; dt < 2; ++dt) {
+        dKt[dt] = zero16();
+        dVt[dt] = zero16();
+    }
     const float cexp = kScale * kLog2e;
 
-    // one 16-byte chunk of Q_i and of dO_i per thread; the chunks of tile i+1 are fetched while tile i is processed
-    const int ld_r = threadIdx.x >> 3, ld_ch = (threadIdx.x & 7) * 8;
-    u32x4 nq = {0u, 0u, 0u, 0u}, nd = {0u, 0u, 0u, 0u};
-    if (ld_r < tokens) {
-        nq = *reinterpret_cast<const u32x4*>(Qb + (long)ld_r * ldq + ld_ch);
-        nd = *reinterpret_cast<const u32x4*>(dOb + (long)ld_r * ld_do + ld_ch);
-    }
+    // one 16-byte chunk of Q_i (threads 0..255) or of dO_i (threads 256..511) per thread; the chunks of
+    // tile i+1 are fetched while tile i is processed
+    const int ld_t = threadIdx.x & 255;
+    const int ld_r = ld_t >> 3, ld_ch = (ld_t & 7) * 8;
+    const bool ld_q = threadIdx.x < 256;
+    const bf16* ld_src = ld_q ? Qb : dOb;
+    const long ld_ld = ld_q ? ldq : ld_do;
+    bf16* ld_dst = (ld_q ? Qs : dOs) + ld_r * kTS + ld_ch;
+    u32x4 nx = {0u, 0u, 0u, 0u};
+    if (ld_r < tokens) nx = *reinterpret_cast<const u32x4*>(ld_src + (long)ld_r * ld_ld + ld_ch);
     for (int i = 0; i < KT; ++i) {
         __syncthreads();   // previous query tile fully consumed (and the prologue's LDS writes are visible)
-        *reinterpret_cast<u32x4*>(Qs + ld_r * kTS + ld_ch) = nq;
-        *reinterpret_cast<u32x4*>(dOs + ld_r * kTS + ld_ch) = nd;
+        *reinterpret_cast<u32x4*>(ld_dst) = nx;
         {
             const int q = (i + 1) * 32 + ld_r;
-            nq = u32x4{0u, 0u, 0u, 0u};
-            nd = u32x4{0u, 0u, 0u, 0u};
-            if (i + 1 < KT && q < tokens) {
-                nq = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + ld_ch);
-                nd = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ld_ch);
-            }
+            nx = u32x4{0u, 0u, 0u, 0u};
+            if (i + 1 < KT && q < tokens) nx = *reinterpret_cast<const u32x4*>(ld_src + (long)q * ld_ld + ld_ch);
         }
         __syncthreads();
-        float L[16], DL[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int ql = i * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-            L[e] = lse_s[ql];
-            DL[e] = del_s[ql];
-        }
         f32x16 dqt[2] = {zero16(), zero16()};
+        if (has_tile) {
+            float L[16], DL[16];
 #pragma unroll
-        for (int us = 0; us < 2; ++us) {
-            const int u = wave + 4 * us;
-            if (u < KT) {
-                f32x16 s = zero16(), dp = zero16();
+            for (int e = 0; e < 16; ++e) {
+                const int ql = i * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+                L[e] = lse_s[ql];
+                DL[e] = del_s[ql];
+            }
+            f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kTS, c, kk * 16 + 8 * h),
-                                                                frag_rows(Ks, kTS, u * 32 + c, kk * 16 + 8 * h), s, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dOs, kTS, c, kk * 16 + 8 * h),
-                                                                 frag_rows(Vs, kKS, u * 32 + c, kk * 16 + 8 * h), dp, 0, 0, 0);
+            for (int kk = 0; kk < 4; ++kk) {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kTS, c, kk * 16 + 8 * h),
+                                                            frag_rows(Ks, kTS, u * 32 + c, kk * 16 + 8 * h), s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dOs, kTS, c, kk * 16 + 8 * h),
+                                                             frag_rows(Vs, kKS, u * 32 + c, kk * 16 + 8 * h), dp, 0, 0, 0);
+            }
+            const bool key_ok = (u * 32 + c) < tokens;
+            f32x16 ds;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = key_ok ? __builtin_amdgcn_exp2f(s[e] * cexp - L[e]) : 0.f;
+                s[e] = p;
+                ds[e] = p * (dp[e] - DL[e]);
+            }
+            // hand dS to the lanes that own queries: [key][query] tile, 8-byte writes
+#pragma unroll
+            for (int eg = 0; eg < 4; ++eg) {
+                uint2 pk;
+                pk.x = pack_bf16x2(ds[4 * eg], ds[4 * eg + 1]);
+                pk.y = pack_bf16x2(ds[4 * eg + 2], ds[4 * eg + 3]);
+                *reinterpret_cast<uint2*>(dSs + c * 32 + 8 * eg + 4 * h) = pk;
+            }
+#pragma unroll
+            for (int gp = 0; gp < 2; ++gp) {
+                const bf16x8 pf = pack8(s, 8 * gp);
+                const bf16x8 dsf = pack8(ds, 8 * gp);
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    dVt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOs, kTS, 16 * gp, dt * 32, lane), pf,
+                                                                      dVt[dt], 0, 0, 0);
+                    dKt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qs, kTS, 16 * gp, dt * 32, lane), dsf,
+                                                                      dKt[dt], 0, 0, 0);
                 }
-                const bool key_ok = (u * 32 + c) < tokens;
-                f32x16 ds;
+            }
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = key_ok ? __builtin_amdgcn_exp2f(s[e] * cexp - L[e]) : 0.f;
-                    s[e] = p;
-                    ds[e] = p * (dp[e] - DL[e]);
-                }
-                // hand dS to the lanes that own queries: [key][query] tile, 8-byte writes
+            for (int gp = 0; gp < 2; ++gp) {
+                const bf16x8 dst = frag_tr(dSs, 32, 16 * gp, 0, lane);   // column = query c, slots = keys
 #pragma unroll
-                for (int eg = 0; eg < 4; ++eg) {
-                    uint2 pk;
-                    pk.x = pack_bf16x2(ds[4 * eg], ds[4 * eg + 1]);
-                    pk.y = pack_bf16x2(ds[4 * eg + 2], ds[4 * eg + 3]);
-                    *reinterpret_cast<uint2*>(dSs + c * 32 + 8 * eg + 4 * h) = pk;
-                }
-#pragma unroll
-                for (int gp = 0; gp < 2; ++gp) {
-                    const bf16x8 pf = pack8(s, 8 * gp);
-                    const bf16x8 dsf = pack8(ds, 8 * gp);
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        dVt[us][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOs, kTS, 16 * gp, dt * 32, lane), pf,
-                                                                              dVt[us][dt], 0, 0, 0);
-                        dKt[us][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qs, kTS, 16 * gp, dt * 32, lane), dsf,
-                                                                              dKt[us][dt], 0, 0, 0);
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int gp = 0; gp < 2; ++gp) {
-                    const bf16x8 dst = frag_tr(dSs, 32, 16 * gp, 0, lane);   // column = query c, slots = keys
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-                        dqt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Ks, kTS, u * 32 + 16 * gp, dt * 32, lane), dst,
-                                                                          dqt[dt], 0, 0, 0);
-                }
-                __builtin_amdgcn_wave_barrier();
+                for (int dt = 0; dt < 2; ++dt)
+                    dqt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Ks, kTS, u * 32 + 16 * gp, dt * 32, lane), dst,
+                                                                      dqt[dt], 0, 0, 0);
             }
         }
         // partial dQ_i^T of this wavefront: rows = channels, column = query c
+        float* slot = dQp + (wave & 3) * 64 * 32;
+        if (wave < 4) {
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+            for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                dQp[(wave * 64 + dt * 32 + 8 * (e >> 2) + 4 * h + (e & 3)) * 32 + c] = dqt[dt][e];
+                for (int e = 0; e < 16; ++e) slot[(dt * 32 + 8 * (e >> 2) + 4 * h + (e & 3)) * 32 + c] = dqt[dt][e];
+        }
+        __syncthreads();
+        if (wave >= 4 && has_tile) {
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) slot[(dt * 32 + 8 * (e >> 2) + 4 * h + (e & 3)) * 32 + c] += dqt[dt][e];
+        }
         __syncthreads();
         {
-            const int q = threadIdx.x & 31, dch = threadIdx.x >> 5;
-            float v[8];
+            const int q = threadIdx.x & 31, dch = threadIdx.x >> 5;   // 16 groups of 4 channels
+            float v[4];
 #pragma unroll
-            for (int i8 = 0; i8 < 8; ++i8) {
-                const int d = dch * 8 + i8;
-                v[i8] = ((dQp[(0 * 64 + d) * 32 + q] + dQp[(1 * 64 + d) * 32 + q]) +
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int d = dch * 4 + i4;
+                v[i4] = ((dQp[(0 * 64 + d) * 32 + q] + dQp[(1 * 64 + d) * 32 + q]) +
                          (dQp[(2 * 64 + d) * 32 + q] + dQp[(3 * 64 + d) * 32 + q])) * kScale;
             }
             const int qg = i * 32 + q;
-            if (qg < tokens) store8(dQb + (long)qg * ld_dqkv + dch * 8, v);
+            if (qg < tokens) {
+                uint2 pk;
+                pk.x = pack_bf16x2(v[0], v[1]);
+                pk.y = pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<uint2*>(dQb + (long)qg * ld_dqkv + dch * 4) = pk;
+            }
         }
     }
 
     // dK^T, dV^T: rows = channels, column = key owned by the lane -> 8-byte stores of 4 channels
-#pragma unroll
-    for (int us = 0; us < 2; ++us) {
-        const int key = (wave + 4 * us) * 32 + c;
-        if (wave + 4 * us < KT && key < tokens) {
+    {
+        const int key = u * 32 + c;
+        if (has_tile && key < tokens) {
             bf16* krow = dQb + (long)key * ld_dqkv + 64;
             bf16* vrow = krow + 64;
 #pragma unroll
@@ -454,11 +468,11 @@ __global__ __launch_bounds__(256) void attn_bwd_mfma_kernel(const bf16* __restri
                 for (int eg = 0; eg < 4; ++eg) {
                     const int d = dt * 32 + 8 * eg + 4 * h;
                     uint2 pk;
-                    pk.x = pack_bf16x2(dKt[us][dt][4 * eg] * kScale, dKt[us][dt][4 * eg + 1] * kScale);
-                    pk.y = pack_bf16x2(dKt[us][dt][4 * eg + 2] * kScale, dKt[us][dt][4 * eg + 3] * kScale);
+                    pk.x = pack_bf16x2(dKt[dt][4 * eg] * kScale, dKt[dt][4 * eg + 1] * kScale);
+                    pk.y = pack_bf16x2(dKt[dt][4 * eg + 2] * kScale, dKt[dt][4 * eg + 3] * kScale);
                     *reinterpret_cast<uint2*>(krow + d) = pk;
-                    pk.x = pack_bf16x2(dVt[us][dt][4 * eg], dVt[us][dt][4 * eg + 1]);
-                    pk.y = pack_bf16x2(dVt[us][dt][4 * eg + 2], dVt[us][dt][4 * eg + 3]);
+                    pk.x = pack_bf16x2(dVt[dt][4 * eg], dVt[dt][4 * eg + 1]);
+                    pk.y = pack_bf16x2(dVt[dt][4 * eg + 2], dVt[dt][4 * eg + 3]);
                     *reinterpret_cast<uint2*>(vrow + d) = pk;
                 }
         }
@@ -469,7 +483,7 @@ template <int KT>
 hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, const float* lse, const bf16* d_o, long ld_do,
                          bf16* dqkv, long ld_dqkv, int batch, int tokens, int n_full, hipStream_t s) {
     constexpr int TP = KT * 32;
-    constexpr size_t lds = (size_t)(TP * kTS + TP * kKS + 2 * 32 * kTS + 4 * 32 * 32) * sizeof(bf16) +
+    constexpr size_t lds = (size_t)(TP * kTS + TP * kKS + 2 * 32 * kTS + kBwdWaves * 32 * 32) * sizeof(bf16) +
                            (size_t)(2 * TP + 4 * 64 * 32) * sizeof(float);
     auto kern = attn_bwd_mfma_kernel<KT>;
     static bool attr_set = false;
@@ -478,8 +492,8 @@ hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(256), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv,
-                       tokens, n_full, (long)batch * tokens);
+    hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * kBwdWaves), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv,
+                       ld_dqkv, tokens, n_full, (long)batch * tokens);
     return hipGetLastError();
 }
 
