@@ -140,6 +140,20 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
                                   void* out, long ldo, int remap, const Remap64& tbl, int accumulate,
                                   hipStream_t s);
 
+// several independent column reductions out[c] = sum over chunks of partial[chunk][c] in one launch
+// (the bias gradients of one block); remap_cols sends column c to tbl(c)
+struct ColReduceJob {
+    const float* partial;
+    void* out;
+    int chunks, cols, remap_cols;
+};
+struct ColReduceBatch {
+    ColReduceJob job[4];
+    int n;
+};
+hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const Remap64& tbl, int accumulate,
+                                   hipStream_t s);
+
 struct HeadList {
     int32_t n;
     uint8_t h[D2FT_MAX_HEADS];

@@ -80,7 +80,7 @@ SavedLayout saved_layout(const Dims& s) {
 // ---- layout of the scratch buffer ----
 struct ScratchLayout {
     size_t part, colpart, dz, dv, dx1, d_o, dqkv, du, delta, weff, total;
-    size_t part_floats;
+    size_t part_floats, colpart_stride;
 };
 ScratchLayout scratch_layout(const Dims& s) {
     ScratchLayout L;
@@ -93,7 +93,8 @@ ScratchLayout scratch_layout(const Dims& s) {
     if ((size_t)s.D > cols) cols = s.D;
     L.part_floats = mat * kMaxSplits;
     L.part = take(L.part_floats * 4);
-    L.colpart = take(2 * kColChunks * cols * 4);
+    L.colpart_stride = (size_t)kColChunks * cols;   // floats per region: four bias reductions, two LayerNorm ones
+    L.colpart = take(6 * L.colpart_stride * 4);
     L.dz = take(s.M * s.Dm * s.es);
     L.dv = take(s.M * s.D * s.es);
     L.dx1 = take(s.M * s.D * s.es);
@@ -343,12 +344,25 @@ d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop
     return D2FT_OK;
 }
 
-d2ft_status bias_grad(const d2ft_block_desc* d, const Dims& s, const void* X, long ldx, int cols, float* colpart,
-                      void* out, int red_remap, const Remap64& tbl, hipStream_t st) {
+// bias gradient, first half: column sums of X over row chunks into its own partial region; the reduction
+// over the chunks is queued and done for all of a block's biases by one launch (flush_bias_grads)
+d2ft_status bias_grad(const Dims& s, const void* X, long ldx, int cols, float* region, void* out, int remap_cols,
+                      ColReduceBatch* batch, hipStream_t st) {
     const int chunks = pick_chunks(s.M);
-    D2FT_TRY(launch_colsum(s.dtype, X, ldx, (int)s.M, cols, colpart, chunks, st));
-    D2FT_TRY(launch_reduce_partials(s.dtype, colpart, chunks, cols, 1, cols, out, cols, red_remap, tbl,
-                                    (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+    D2FT_TRY(launch_colsum(s.dtype, X, ldx, (int)s.M, cols, region, chunks, st));
+    ColReduceJob& j = batch->job[batch->n++];
+    j.partial = region;
+    j.out = out;
+    j.chunks = chunks;
+    j.cols = cols;
+    j.remap_cols = remap_cols;
+    return D2FT_OK;
+}
+
+d2ft_status flush_bias_grads(const d2ft_block_desc* d, const Dims& s, ColReduceBatch* batch, const Remap64& tbl,
+                             hipStream_t st) {
+    D2FT_TRY(launch_col_reduce_batch(s.dtype, *batch, tbl, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+    batch->n = 0;
     return D2FT_OK;
 }
 
@@ -533,6 +547,9 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     const int accum = (desc->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
     float* part = (float*)(ws + WL.part);
     float* colpart = (float*)(ws + WL.colpart);
+    float* ln_part = colpart + 4 * WL.colpart_stride;
+    ColReduceBatch bias_batch;
+    memset(&bias_batch, 0, sizeof(bias_batch));
     Remap64 none;
     memset(&none, 0, sizeof(none));
     const void* x1 = nl > 0 ? (const void*)(sv + SL.x1) : x;
@@ -544,7 +561,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         if (rc != D2FT_OK) return rc;
     }
     if (grads->b2 && w->b2) {
-        rc = bias_grad(desc, s, dy, s.D, s.D, colpart, grads->b2, RED_REMAP_NONE, none, st);
+        rc = bias_grad(s, dy, s.D, s.D, colpart + 0 * WL.colpart_stride, grads->b2, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     {   // dz = (dy W2) * GELU'(z)
@@ -561,7 +578,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         if (rc != D2FT_OK) return rc;
     }
     if (grads->b1) {
-        rc = bias_grad(desc, s, ws + WL.dz, s.Dm, s.Dm, colpart, grads->b1, RED_REMAP_NONE, none, st);
+        rc = bias_grad(s, ws + WL.dz, s.Dm, s.Dm, colpart + 1 * WL.colpart_stride, grads->b1, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     {   // dv = dz W1
@@ -574,8 +591,8 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     }
     if (grads->ln2_g || grads->ln2_b) {
         const int chunks = pick_chunks(s.M);
-        float* pg = colpart;
-        float* pb = colpart + (size_t)kColChunks * s.D;
+        float* pg = ln_part;
+        float* pb = ln_part + WL.colpart_stride;
         D2FT_TRY(launch_ln_param_grad(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2),
                                       (const float*)(sv + SL.rstd2), pg, pb, M, s.D, chunks, st));
         if (grads->ln2_g)
@@ -590,7 +607,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
 
     // ---- attention side ----
     if (grads->b_o && w->b_o && nl > 0) {
-        rc = bias_grad(desc, s, dx1, s.D, s.D, colpart, grads->b_o, RED_REMAP_NONE, none, st);
+        rc = bias_grad(s, dx1, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     // heads that are not p_f: gradient slices are +0.0 in overwrite mode, untouched in accumulate mode
@@ -609,7 +626,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
             if (grads->ln1_b) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, 0, st));
         }
     }
-    if (nf == 0) return D2FT_OK;
+    if (nf == 0) return flush_bias_grads(desc, s, &bias_batch, none, st);
 
     const long ldq = (long)nl * 192, ldo = (long)nl * 64;
     const long ld_do = (long)nf * 64, ld_dq = (long)nf * 192;
@@ -650,7 +667,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         }
     }
     if (grads->b_qkv) {
-        rc = bias_grad(desc, s, ws + WL.dqkv, ld_dq, nf * 192, colpart, grads->b_qkv, RED_REMAP_COLS, qkv_tbl, st);
+        rc = bias_grad(s, ws + WL.dqkv, ld_dq, nf * 192, colpart + 3 * WL.colpart_stride, grads->b_qkv, 1, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     {   // du = dQKV W_eff (rows of the p_f heads)
@@ -673,8 +690,8 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     }
     if (grads->ln1_g || grads->ln1_b) {
         const int chunks = pick_chunks(s.M);
-        float* pg = colpart;
-        float* pb = colpart + (size_t)kColChunks * s.D;
+        float* pg = ln_part;
+        float* pb = ln_part + WL.colpart_stride;
         D2FT_TRY(launch_ln_param_grad(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1),
                                       (const float*)(sv + SL.rstd1), pg, pb, M, s.D, chunks, st));
         if (grads->ln1_g)
@@ -685,7 +702,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     // dx = dx1 + LN1bwd(du)
     D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1), (const float*)(sv + SL.rstd1), w->ln1_g,
                            dx1, dx, M, s.D, st));
-    return D2FT_OK;
+    return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, st);
 }
 
 size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const int32_t* cap_full,

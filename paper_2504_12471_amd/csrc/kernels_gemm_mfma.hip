@@ -2,10 +2,12 @@
 //
 //   C[m][n] = epilogue( sum_k A(m,k) * B(k,n) )
 //
-// One 256-thread workgroup (4 wavefronts, 2 x 2) owns a BM x BN tile of C; each wavefront owns
-// (BM/2) x (BN/2) of it as a grid of 32x32 MFMA tiles.  K is consumed BK at a time: the next
-// slab is fetched from global memory into registers while the current one is multiplied out of
-// LDS, then written to the other LDS buffer (one barrier per slab).
+// A workgroup of WGM x WGN wavefronts owns a BM x BN tile of C at a time (256x256 and 192x256 with
+// 2 x 4 wavefronts, one workgroup per CU; 128x128 with 2 x 2, two per CU); each wavefront owns
+// (BM/WGM) x (BN/WGN) of it as a grid of 32x32 MFMA tiles.  K is consumed BK at a time: the slab
+// after next is fetched from global memory into registers while the current one is multiplied
+// out of LDS and the next one is written to the other LDS buffer (one barrier per slab).
+// Workgroups are persistent: the grid is what the chip holds at once and each walks its tiles.
 //
 // Either operand may be stored with K contiguous ("row" form: A[m][k], B[n][k]) or with its
 // other index contiguous ("col" form: A[k][m], B[k][n]).  The MFMA wants 8 consecutive k per

@@ -291,6 +291,36 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 }
 
 // ---------------------------------------------------------------------------
+// up to four column reductions in one launch: blockIdx.y picks the job; chunks are added in index
+// order, eight loads in flight at a time (the same order as reduce_partials_kernel on one row)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void col_reduce_batch_kernel(ColReduceBatch batch, int accumulate, Remap64 tbl) {
+    const ColReduceJob job = batch.job[blockIdx.y];
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= job.cols) return;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* src = job.partial + c;
+    int k = 0;
+    for (; k + 8 <= job.chunks; k += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4*>(src + (long)(k + j) * job.cols);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
+    }
+    for (; k < job.chunks; ++k) {
+        const float4 v = *reinterpret_cast<const float4*>(src + (long)k * job.cols);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    T* o = static_cast<T*>(job.out) + (job.remap_cols ? tbl(c) : c);
+    if (accumulate) {
+        s.x += ld<T>(o); s.y += ld<T>(o + 1); s.z += ld<T>(o + 2); s.w += ld<T>(o + 3);
+    }
+    st<T>(o, s.x); st<T>(o + 1, s.y); st<T>(o + 2, s.z); st<T>(o + 3, s.w);
+}
+
+// ---------------------------------------------------------------------------
 // +0.0 into every gradient slice of the listed heads
 // ---------------------------------------------------------------------------
 template <typename T>
@@ -502,6 +532,16 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL(reduce_partials_kernel<T>, grid, block, 0, s, partial, splits,
                                             slice_stride, rows, cols, (T*)out, ldo, remap, accumulate, tbl);)
+    return hipGetLastError();
+}
+
+hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const Remap64& tbl, int accumulate,
+                                   hipStream_t s) {
+    if (batch.n <= 0) return hipSuccess;
+    int cols = 0;
+    for (int i = 0; i < batch.n; ++i) cols = batch.job[i].cols > cols ? batch.job[i].cols : cols;   // multiples of 8
+    const dim3 grid((unsigned)((cols / 4 + 255) / 256), batch.n), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(col_reduce_batch_kernel<T>, grid, block, 0, s, batch, accumulate, tbl);)
     return hipGetLastError();
 }
 
