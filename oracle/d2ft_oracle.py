@@ -24,8 +24,14 @@ design notes of the repository):
   * The output-projection bias is added iff at least one head is live, so an
     all-shortcut block leaves the attention residual untouched.
   * LayerNorm uses the biased variance; GELU is the exact erf form.
-  * The feed-forward network is not gated here: it always runs forward and
-    backward.
+  * By default the feed-forward network is not gated: it always runs forward
+    and backward.  With gate_ffn the subnet of Sec. II-A.1 is taken whole: head
+    h owns hidden units [h*Dm/H, (h+1)*Dm/H) of the feed-forward network (the
+    1/H part the paper assigns to it, Sec. IV-A "Full fine-tuning partition
+    settings") and the head's op code applies to that slice too: p_s drops the
+    slice, p_o keeps its forward term as a constant, p_f trains it.  The second
+    layer's bias is added iff at least one slice is live, the same rule as for
+    the output-projection bias, so an all-shortcut block is the identity.
   * In DPSearching the item weight tested and subtracted in the fill phase is
     the operation's own weight (W_p), as the backtracking phase uses; the
     backtracking index decrements by one.
@@ -109,7 +115,8 @@ def _f64(a):
 # ----------------------------------------------------------------------------
 def block_fwd(w: Dict[str, Optional[np.ndarray]], ops: Sequence[int], x: np.ndarray,
               head_dim: int, ln_eps: float = 1e-6, lora_scale: float = 1.0,
-              attn_const: Optional[np.ndarray] = None):
+              attn_const: Optional[np.ndarray] = None, gate_ffn: bool = False,
+              ffn_const: Optional[np.ndarray] = None):
     """Forward of one pre-LN block whose heads carry op codes.
 
     x: [B, T, D].  w: arrays named as in the library's weight struct
@@ -117,7 +124,10 @@ def block_fwd(w: Dict[str, Optional[np.ndarray]], ops: Sequence[int], x: np.ndar
     w2 [D,Dm], optional lora_a_q/v [H,r,D], lora_b_q/v [H,dh,r]).
     attn_const, if given, is a [B, T, D] constant added to the attention
     residual; a test uses it to hold a forward-only head's output fixed while
-    it perturbs parameters (the stop-gradient reading of p_o).
+    it perturbs parameters (the stop-gradient reading of p_o); ffn_const does
+    the same for the feed-forward residual.
+    gate_ffn: head h's op code also governs hidden units [h*Dm/H, (h+1)*Dm/H)
+    of the feed-forward network (the subnet of Sec. II-A.1).
     Returns (y, cache); cache holds what block_bwd needs.
     """
     w = {k: _f64(v) for k, v in w.items()}
@@ -156,14 +166,36 @@ def block_fwd(w: Dict[str, Optional[np.ndarray]], ops: Sequence[int], x: np.ndar
     if attn_const is not None:
         x1 = x1 + _f64(attn_const)
 
-    vv, xhat2, rstd2 = layer_norm(x1, w["ln2_g"], w["ln2_b"], ln_eps)
-    z = vv @ w["w1"].T + w["b1"]
-    g = gelu(z)
-    y = x1 + g @ w["w2"].T
-    if w.get("b2") is not None:
-        y = y + w["b2"]
-    cache.update(x1=x1, v=vv, xhat2=xhat2, rstd2=rstd2, z=z, g=g, head_dim=dh,
-                 lora_scale=lora_scale, has_lora=has_lora)
+    cache.update(x1=x1, head_dim=dh, lora_scale=lora_scale, has_lora=has_lora, gate_ffn=gate_ffn)
+    if not gate_ffn:
+        vv, xhat2, rstd2 = layer_norm(x1, w["ln2_g"], w["ln2_b"], ln_eps)
+        z = vv @ w["w1"].T + w["b1"]
+        g = gelu(z)
+        y = x1 + g @ w["w2"].T
+        if w.get("b2") is not None:
+            y = y + w["b2"]
+        cache.update(v=vv, xhat2=xhat2, rstd2=rstd2, z=z, g=g)
+    else:
+        Dm = w["w1"].shape[0]
+        if Dm % len(ops) != 0:
+            raise ValueError("the hidden width must divide evenly over the heads")
+        S = Dm // len(ops)
+        ffn = np.zeros_like(x1)
+        cache["slices"] = {}
+        if n_live > 0:
+            vv, xhat2, rstd2 = layer_norm(x1, w["ln2_g"], w["ln2_b"], ln_eps)
+            cache.update(v=vv, xhat2=xhat2, rstd2=rstd2)
+            for h in live:
+                sl = slice(h * S, (h + 1) * S)
+                z = vv @ w["w1"][sl].T + w["b1"][sl]
+                g = gelu(z)
+                ffn = ffn + g @ w["w2"][:, sl].T
+                cache["slices"][h] = dict(z=z, g=g)
+            if w.get("b2") is not None:
+                ffn = ffn + w["b2"]
+        y = x1 + ffn
+    if ffn_const is not None:
+        y = y + _f64(ffn_const)
     return y, cache
 
 
@@ -191,17 +223,37 @@ def block_bwd(w: Dict[str, Optional[np.ndarray]], cache: dict, dy: np.ndarray):
 
     g = {k: (None if v is None else np.zeros_like(v)) for k, v in w.items()}
 
-    # feed-forward network (never gated here)
-    g["w2"] = rows(dy).T @ rows(cache["g"])
-    if w.get("b2") is not None:
-        g["b2"] = rows(dy).sum(axis=0)
-    dg = dy @ w["w2"]
-    dz = dg * gelu_grad(cache["z"])
-    g["w1"] = rows(dz).T @ rows(cache["v"])
-    g["b1"] = rows(dz).sum(axis=0)
-    dv = dz @ w["w1"]
-    dln2, g["ln2_g"], g["ln2_b"] = layer_norm_bwd(dv, cache["xhat2"], cache["rstd2"], w["ln2_g"])
-    dx1 = dy + dln2
+    if not cache["gate_ffn"]:
+        # feed-forward network, not gated
+        g["w2"] = rows(dy).T @ rows(cache["g"])
+        if w.get("b2") is not None:
+            g["b2"] = rows(dy).sum(axis=0)
+        dg = dy @ w["w2"]
+        dz = dg * gelu_grad(cache["z"])
+        g["w1"] = rows(dz).T @ rows(cache["v"])
+        g["b1"] = rows(dz).sum(axis=0)
+        dv = dz @ w["w1"]
+        dln2, g["ln2_g"], g["ln2_b"] = layer_norm_bwd(dv, cache["xhat2"], cache["rstd2"], w["ln2_g"])
+        dx1 = dy + dln2
+    else:
+        # feed-forward slices of the p_f subnets only; the others leave exact zeros (Sec. II-A.2)
+        S = w["w1"].shape[0] // len(cache["ops"])
+        if len(live) > 0 and w.get("b2") is not None:
+            g["b2"] = rows(dy).sum(axis=0)
+        if n_full == 0:
+            dx1 = dy.copy()
+        else:
+            dv = np.zeros_like(cache["v"])
+            for h in full:
+                sl = slice(h * S, (h + 1) * S)
+                c = cache["slices"][h]
+                g["w2"][:, sl] = rows(dy).T @ rows(c["g"])
+                dz = (dy @ w["w2"][:, sl]) * gelu_grad(c["z"])
+                g["w1"][sl] = rows(dz).T @ rows(cache["v"])
+                g["b1"][sl] = rows(dz).sum(axis=0)
+                dv = dv + dz @ w["w1"][sl]
+            dln2, g["ln2_g"], g["ln2_b"] = layer_norm_bwd(dv, cache["xhat2"], cache["rstd2"], w["ln2_g"])
+            dx1 = dy + dln2
 
     # attention side
     if len(live) > 0 and w.get("b_o") is not None:
@@ -242,10 +294,10 @@ def block_bwd(w: Dict[str, Optional[np.ndarray]], cache: dict, dy: np.ndarray):
 # stack of blocks
 # ----------------------------------------------------------------------------
 def stack_fwd(weights: List[dict], ops: np.ndarray, x: np.ndarray, head_dim: int,
-              ln_eps: float = 1e-6, lora_scale: float = 1.0):
+              ln_eps: float = 1e-6, lora_scale: float = 1.0, gate_ffn: bool = False):
     caches, h = [], _f64(x)
     for l, w in enumerate(weights):
-        h, c = block_fwd(w, ops[l], h, head_dim, ln_eps, lora_scale)
+        h, c = block_fwd(w, ops[l], h, head_dim, ln_eps, lora_scale, gate_ffn=gate_ffn)
         caches.append(c)
     return h, caches
 
