@@ -35,7 +35,10 @@ def algorithmic_flops(w, ops) -> float:
         n_full = int((ops[l] == di.OP_FULL).sum())
         n_live = n_full + int((ops[l] == di.OP_FWD).sum())
         head_fwd = 4.0 * M * dh * (2 * D + T)
-        if w.train_base:
+        if w.gate_ffn:   # whole subnets: each head carries Dm/H hidden units
+            head_fwd += 4.0 * M * D * (Dm // w.heads)
+            total += (n_live + 2 * n_full) * head_fwd
+        elif w.train_base:
             total += (n_live + 2 * n_full) * head_fwd + 12.0 * M * D * Dm
         else:   # LoRA: no base weight gradients
             lora_fwd = 4.0 * M * r * (D + dh)
@@ -105,7 +108,7 @@ def main() -> int:
     full_ops = di.all_full_ops(w)
 
     desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype, w.lora_rank, w.lora_scale,
-                       w.ln_eps, w.head_dim)
+                       w.ln_eps, w.head_dim, P.FLAG_GATE_FFN if w.gate_ffn else 0)
     dws = [{k: P.to_device(v, w.dtype) for k, v in bw.items()} for bw in s.weights]
     if w.train_base:
         grad_fields = [k for k in P.WEIGHT_FIELDS if not k.startswith("ln")]   # norm layers frozen (Sec. III-A)
@@ -169,7 +172,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic (seeded N(0,1) tokens, N(0,0.02^2) weights)",
         "config": {"workload": w.name, "batch": w.batch, "tokens": w.tokens, "width": w.width, "heads": w.heads,
-                   "mlp_hidden": w.mlp_hidden, "blocks": w.blocks, "lora_rank": w.lora_rank,
+                   "mlp_hidden": w.mlp_hidden, "blocks": w.blocks, "lora_rank": w.lora_rank, "gate_ffn": w.gate_ffn,
                    "heads_full": int((ops == di.OP_FULL).sum()), "heads_fwd_only": int((ops == di.OP_FWD).sum()),
                    "heads_skipped": int((ops == di.OP_SKIP).sum())},
         "algorithmic_tflop_per_step": round(flops / 1e12, 3),
@@ -194,7 +197,8 @@ def main() -> int:
         t0 = time.perf_counter()
         n_done = 0
         while n_done < w.blocks and time.perf_counter() - t0 < 12.0:   # a bounded sample: about 12 s of CPU work
-            y, cache = orc.block_fwd(s.weights[n_done], ops[n_done], s.x, w.head_dim, w.ln_eps, w.lora_scale)
+            y, cache = orc.block_fwd(s.weights[n_done], ops[n_done], s.x, w.head_dim, w.ln_eps, w.lora_scale,
+                                     gate_ffn=w.gate_ffn)
             orc.block_bwd(s.weights[n_done], cache, s.dy)
             n_done += 1
         t_block = (time.perf_counter() - t0) / n_done

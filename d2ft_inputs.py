@@ -50,6 +50,7 @@ class Workload:
     mask: tuple = ("counts", 1.0, 0.0, 0.0)
     lora_b_zero: bool = True
     train_base: bool = True   # False: base weights frozen, only LoRA gradients wanted
+    gate_ffn: bool = False    # True: a head's op code also governs its 1/H slice of the feed-forward network
 
     @property
     def rows(self) -> int:
@@ -72,6 +73,12 @@ WORKLOADS: Dict[str, Workload] = {
     # ViT-L/16 stack, 40% skipped, 20% fwd-only
     "vit_l16": Workload("vit_l16", 32, 197, 1024, 16, 64, 4096, 24, "bf16",
                         mask=("counts", 0.4, 0.2, 0.4)),
+    # the ViT-B/16 stack with whole subnets gated (head + 1/12 of the FFN), same 60/20/20 mask
+    "vit_b16_ffn": Workload("vit_b16_ffn", 64, 197, 768, 12, 64, 3072, 12, "bf16",
+                            mask=("counts", 0.6, 0.2, 0.2), gate_ffn=True),
+    # the same with 40% of the subnets skipped and no forward-only ones
+    "vit_b16_ffn_skip40": Workload("vit_b16_ffn_skip40", 64, 197, 768, 12, 64, 3072, 12, "bf16",
+                                   mask=("counts", 0.6, 0.0, 0.4), gate_ffn=True),
     # ViT-B/16 with rank-8 LoRA on Wq and Wv, base frozen, 40% skipped
     "vit_b16_lora": Workload("vit_b16_lora", 64, 197, 768, 12, 64, 3072, 12, "bf16",
                              lora_rank=8, mask=("counts", 0.6, 0.0, 0.4), train_base=False),

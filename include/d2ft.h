@@ -57,7 +57,15 @@ enum {
     D2FT_FLAG_ACCUM_GRADS = 1u,
     /* bf16 only: run the vector-ALU kernels instead of the MFMA kernels (a cross-check
      * of the two kernel families; fp32 always runs on the vector ALUs). */
-    D2FT_FLAG_NO_MFMA = 2u
+    D2FT_FLAG_NO_MFMA = 2u,
+    /* The op code of head h also governs hidden units [h*mlp_hidden/heads, (h+1)*mlp_hidden/heads)
+     * of the feed-forward network, i.e. the whole subnet of Sec. II-A.1 (one attention head plus
+     * 1/H of the FFN; Sec. IV-A "Full fine-tuning partition settings"): a p_s subnet's slice is
+     * skipped, a p_o subnet's slice runs forward only (its term is a constant in backward), a p_f
+     * subnet's slice is trained.  b2 is then added iff at least one subnet is live, and with no
+     * live subnet the block is the identity.  Requires mlp_hidden divisible by heads with a
+     * quotient that is a multiple of 64; otherwise D2FT_ESHAPE. */
+    D2FT_FLAG_GATE_FFN = 4u
 };
 
 #define D2FT_MAX_HEADS 64

@@ -141,7 +141,7 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
                                   hipStream_t s);
 
 // several independent column reductions out[c] = sum over chunks of partial[chunk][c] in one launch
-// (the bias gradients of one block); remap_cols sends column c to tbl(c)
+// (the bias gradients of one block); remap_cols = 1 or 2 sends column c to tbl_a(c) or tbl_b(c)
 struct ColReduceJob {
     const float* partial;
     void* out;
@@ -151,8 +151,9 @@ struct ColReduceBatch {
     ColReduceJob job[4];
     int n;
 };
-hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const Remap64& tbl, int accumulate,
-                                   hipStream_t s);
+hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const Remap64& tbl_a, const Remap64& tbl_b,
+                                   int accumulate, hipStream_t s);
+
 
 struct HeadList {
     int32_t n;
@@ -162,6 +163,9 @@ struct HeadList {
 hipError_t launch_zero_head_slices(int dtype, const HeadList& heads, int H, int D, int r, void* g_wqkv, void* g_bqkv,
                                    void* g_wo, void* g_la_q, void* g_la_v, void* g_lb_q, void* g_lb_v,
                                    hipStream_t s);
+// +0.0 into the feed-forward gradient slices (w1 rows, b1, w2 columns) of the listed heads; slice = Dm / H
+hipError_t launch_zero_ffn_slices(int dtype, const HeadList& heads, int slice, int D, int Dm, void* g_w1, void* g_b1,
+                                  void* g_w2, hipStream_t s);
 
 // W_eff rows for compacted heads: out[(j*3+p)*64 + d][:] = W[p][live[j]][d][:] (+ s * B A for p in {query, value})
 hipError_t launch_lora_merge(int dtype, const void* w_qkv, const void* la_q, const void* la_v, const void* lb_q,

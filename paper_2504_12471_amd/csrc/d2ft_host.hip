@@ -40,6 +40,11 @@ bool desc_ok(const d2ft_block_desc* d, d2ft_status* why) {
     if (d->head_dim != D2FT_HEAD_DIM) return false;
     if (d->lora_rank < 0 || d->lora_rank > D2FT_MAX_LORA_RANK) return false;
     if ((long)d->batch * d->tokens > (1L << 24)) return false;
+    if (d->flags & D2FT_FLAG_GATE_FFN) {   // a head's feed-forward slice is a whole number of 64-column blocks
+        if (d->mlp_hidden % d->heads) return false;
+        const int slice = d->mlp_hidden / d->heads;
+        if (slice % 64 || d->mlp_hidden / 64 > kMaxBlocks64) return false;
+    }
     *why = D2FT_OK;
     return true;
 }
@@ -145,6 +150,12 @@ void fill_qkv_table(Remap64& t, const int32_t* live, int n, int H) {
 }
 void fill_head_table(Remap64& t, const int32_t* live, int n) {
     for (int j = 0; j < n; ++j) t.start[j] = live[j] * 64;
+}
+// hidden units of the feed-forward slices of the first n listed heads, slice = Dm / H (a multiple of 64)
+void fill_ffn_table(Remap64& t, const int32_t* live, int n, int slice) {
+    const int per = slice / 64;
+    for (int j = 0; j < n; ++j)
+        for (int b = 0; b < per; ++b) t.start[j * per + b] = live[j] * slice + b * 64;
 }
 
 // ---- optional per-kernel timing (diagnostics; see d2ft_timing_enable in d2ft.h) ----
@@ -359,9 +370,9 @@ d2ft_status bias_grad(const Dims& s, const void* X, long ldx, int cols, float* r
     return D2FT_OK;
 }
 
-d2ft_status flush_bias_grads(const d2ft_block_desc* d, const Dims& s, ColReduceBatch* batch, const Remap64& tbl,
-                             hipStream_t st) {
-    D2FT_TRY(launch_col_reduce_batch(s.dtype, *batch, tbl, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+d2ft_status flush_bias_grads(const d2ft_block_desc* d, const Dims& s, ColReduceBatch* batch, const Remap64& tbl_a,
+                             const Remap64& tbl_b, hipStream_t st) {
+    D2FT_TRY(launch_col_reduce_batch(s.dtype, *batch, tbl_a, tbl_b, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
     batch->n = 0;
     return D2FT_OK;
 }
@@ -491,24 +502,39 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         D2FT_TRY_UNTIMED(run_gemm(p, desc, st));
         x1 = sv + SL.x1;
     }
+    const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
+    if (gate && nl == 0) {   // no live subnet: the block is the identity (neither bias is applied)
+        timing_begin(st, "copy");
+        const hipError_t e = hipMemcpyAsync(y, x, (size_t)s.M * s.D * s.es, hipMemcpyDeviceToDevice, st);
+        timing_end(st);
+        return e == hipSuccess ? D2FT_OK : D2FT_EDEVICE;
+    }
+    // feed-forward columns in use: all of them, or the slices of the live heads in compacted order
+    const int slice = gate ? s.Dm / s.H : 0;
+    const int n_hid = gate ? nl * slice : s.Dm;
+    Remap64 ffn_tbl;
+    memset(&ffn_tbl, 0, sizeof(ffn_tbl));
+    if (gate) fill_ffn_table(ffn_tbl, live, nl, slice);
     void* v = sv + SL.v;
     D2FT_TRY(launch_ln_fwd(s.dtype, x1, w->ln2_g, w->ln2_b, v, (float*)(sv + SL.mean2), (float*)(sv + SL.rstd2), M, s.D,
                            desc->ln_eps, st));
     {   // z = v W1^T + b1, g = GELU(z)
         GemmArgs g = gemm_base();
+        g.tbl = ffn_tbl;
         g.A = v; g.a_rs = s.D; g.a_cs = 1;
-        g.B = w->w1; g.b_rs = 1; g.b_cs = s.D;
-        g.M = M; g.N = s.Dm; g.K = s.D;
-        g.C = sv + SL.g; g.ldc = s.Dm;
-        g.bias = w->b1;
-        g.act = ACT_GELU; g.Z = sv + SL.z; g.ldz = s.Dm;
+        g.B = w->w1; g.b_rs = 1; g.b_cs = s.D; g.remap = gate ? REMAP_B_N : REMAP_NONE;
+        g.M = M; g.N = n_hid; g.K = s.D;
+        g.C = sv + SL.g; g.ldc = n_hid;
+        g.bias = w->b1; g.bias_remap = gate ? 1 : 0;
+        g.act = ACT_GELU; g.Z = sv + SL.z; g.ldz = n_hid;
         D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     {   // y = x1 + g W2^T + b2
         GemmArgs g = gemm_base();
-        g.A = sv + SL.g; g.a_rs = s.Dm; g.a_cs = 1;
-        g.B = w->w2; g.b_rs = 1; g.b_cs = s.Dm;
-        g.M = M; g.N = s.D; g.K = s.Dm;
+        g.tbl = ffn_tbl;
+        g.A = sv + SL.g; g.a_rs = n_hid; g.a_cs = 1;
+        g.B = w->w2; g.b_rs = 1; g.b_cs = s.Dm; g.remap = gate ? REMAP_B_K : REMAP_NONE;
+        g.M = M; g.N = s.D; g.K = n_hid;
         g.C = y; g.ldc = s.D;
         g.bias = w->b2;
         g.residual = x1; g.ldr = s.D;
@@ -555,59 +581,89 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     const void* x1 = nl > 0 ? (const void*)(sv + SL.x1) : x;
     d2ft_status rc;
 
-    // ---- MLP (never gated) ----
-    if (grads->w2) {   // dW2 = dy^T g
-        rc = weight_grad(desc, s, dy, s.D, sv + SL.g, s.Dm, s.D, s.Dm, part, grads->w2, s.Dm, RED_REMAP_NONE, none, st);
-        if (rc != D2FT_OK) return rc;
+    // ---- feed-forward network: all of it, or (gated) the slices of the p_f heads, a prefix of the compacted layout ----
+    const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
+    const int slice = gate ? s.Dm / s.H : 0;
+    const int ld_hid = gate ? nl * slice : s.Dm;      // row stride of the saved z and g
+    const int n_hid = gate ? nf * slice : s.Dm;       // hidden units that take part in backward
+    Remap64 ffn_tbl;
+    memset(&ffn_tbl, 0, sizeof(ffn_tbl));
+    if (gate) fill_ffn_table(ffn_tbl, live, nf, slice);
+    if (gate && !accum) {   // feed-forward slices of subnets that are not p_f: +0.0
+        HeadList nonfull; nonfull.n = 0;
+        for (int h = 0; h < s.H; ++h)
+            if (ops[h] != D2FT_OP_FULL) nonfull.h[nonfull.n++] = (uint8_t)h;
+        D2FT_TRY(launch_zero_ffn_slices(s.dtype, nonfull, slice, s.D, s.Dm, grads->w1, grads->b1, grads->w2, st));
+        if (nl == 0 && grads->b2 && w->b2)   // bias was not applied: its gradient is zero
+            D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->b2, s.D, RED_REMAP_NONE, none, 0, st));
+        if (nf == 0) {
+            if (grads->ln2_g) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln2_g, s.D, RED_REMAP_NONE, none, 0, st));
+            if (grads->ln2_b) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, 0, st));
+        }
     }
-    if (grads->b2 && w->b2) {
+    if (grads->b2 && w->b2 && (!gate || nl > 0)) {
         rc = bias_grad(s, dy, s.D, s.D, colpart + 0 * WL.colpart_stride, grads->b2, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
-    {   // dz = (dy W2) * GELU'(z)
-        GemmArgs g = gemm_base();
-        g.A = dy; g.a_rs = s.D; g.a_cs = 1;
-        g.B = w->w2; g.b_rs = s.Dm; g.b_cs = 1;   // B(k = width index, n = hidden index) = W2[k][n]
-        g.M = M; g.N = s.Dm; g.K = s.D;
-        g.C = ws + WL.dz; g.ldc = s.Dm;
-        g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = s.Dm;
-        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+    const void* dx1_in = dy;   // gated with no p_f subnet: the residual route alone, dx1 = dy
+    void* dx1 = nullptr;
+    if (n_hid > 0) {
+        if (grads->w2) {   // dW2[:, hidden] = dy^T g
+            rc = weight_grad(desc, s, dy, s.D, sv + SL.g, ld_hid, s.D, n_hid, part, grads->w2, s.Dm,
+                             gate ? RED_REMAP_COLS : RED_REMAP_NONE, ffn_tbl, st);
+            if (rc != D2FT_OK) return rc;
+        }
+        {   // dz = (dy W2[:, hidden]) * GELU'(z)
+            GemmArgs g = gemm_base();
+            g.tbl = ffn_tbl;
+            g.A = dy; g.a_rs = s.D; g.a_cs = 1;
+            g.B = w->w2; g.b_rs = s.Dm; g.b_cs = 1;   // B(k = width index, n = hidden index) = W2[k][n]
+            g.remap = gate ? REMAP_B_N : REMAP_NONE;
+            g.M = M; g.N = n_hid; g.K = s.D;
+            g.C = ws + WL.dz; g.ldc = n_hid;
+            g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = ld_hid;
+            D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        }
+        if (grads->w1) {   // dW1[hidden] = dz^T v
+            rc = weight_grad(desc, s, ws + WL.dz, n_hid, sv + SL.v, s.D, n_hid, s.D, part, grads->w1, s.D,
+                             gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, st);
+            if (rc != D2FT_OK) return rc;
+        }
+        if (grads->b1) {
+            rc = bias_grad(s, ws + WL.dz, n_hid, n_hid, colpart + 1 * WL.colpart_stride, grads->b1, gate ? 2 : 0,
+                           &bias_batch, st);
+            if (rc != D2FT_OK) return rc;
+        }
+        {   // dv = dz W1[hidden]
+            GemmArgs g = gemm_base();
+            g.tbl = ffn_tbl;
+            g.A = ws + WL.dz; g.a_rs = n_hid; g.a_cs = 1;
+            g.B = w->w1; g.b_rs = s.D; g.b_cs = 1; g.remap = gate ? REMAP_B_K : REMAP_NONE;
+            g.M = M; g.N = s.D; g.K = n_hid;
+            g.C = ws + WL.dv; g.ldc = s.D;
+            D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        }
+        if (grads->ln2_g || grads->ln2_b) {
+            const int chunks = pick_chunks(s.M);
+            float* pg = ln_part;
+            float* pb = ln_part + WL.colpart_stride;
+            D2FT_TRY(launch_ln_param_grad(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2),
+                                          (const float*)(sv + SL.rstd2), pg, pb, M, s.D, chunks, st));
+            if (grads->ln2_g)
+                D2FT_TRY(launch_reduce_partials(s.dtype, pg, chunks, s.D, 1, s.D, grads->ln2_g, s.D, RED_REMAP_NONE, none, accum, st));
+            if (grads->ln2_b)
+                D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, accum, st));
+        }
+        // dx1 = dy + LN2bwd(dv); with no p_f head this already is dx (residual route only)
+        dx1 = (nf > 0) ? (void*)(ws + WL.dx1) : dx;
+        D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2), (const float*)(sv + SL.rstd2),
+                               w->ln2_g, dy, dx1, M, s.D, st));
+        dx1_in = dx1;
     }
-    if (grads->w1) {   // dW1 = dz^T v
-        rc = weight_grad(desc, s, ws + WL.dz, s.Dm, sv + SL.v, s.D, s.Dm, s.D, part, grads->w1, s.D, RED_REMAP_NONE, none, st);
-        if (rc != D2FT_OK) return rc;
-    }
-    if (grads->b1) {
-        rc = bias_grad(s, ws + WL.dz, s.Dm, s.Dm, colpart + 1 * WL.colpart_stride, grads->b1, 0, &bias_batch, st);
-        if (rc != D2FT_OK) return rc;
-    }
-    {   // dv = dz W1
-        GemmArgs g = gemm_base();
-        g.A = ws + WL.dz; g.a_rs = s.Dm; g.a_cs = 1;
-        g.B = w->w1; g.b_rs = s.D; g.b_cs = 1;
-        g.M = M; g.N = s.D; g.K = s.Dm;
-        g.C = ws + WL.dv; g.ldc = s.D;
-        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
-    }
-    if (grads->ln2_g || grads->ln2_b) {
-        const int chunks = pick_chunks(s.M);
-        float* pg = ln_part;
-        float* pb = ln_part + WL.colpart_stride;
-        D2FT_TRY(launch_ln_param_grad(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2),
-                                      (const float*)(sv + SL.rstd2), pg, pb, M, s.D, chunks, st));
-        if (grads->ln2_g)
-            D2FT_TRY(launch_reduce_partials(s.dtype, pg, chunks, s.D, 1, s.D, grads->ln2_g, s.D, RED_REMAP_NONE, none, accum, st));
-        if (grads->ln2_b)
-            D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, accum, st));
-    }
-    // dx1 = dy + LN2bwd(dv); with no p_f head this already is dx (residual route only)
-    void* dx1 = (nf > 0) ? (void*)(ws + WL.dx1) : dx;
-    D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2), (const float*)(sv + SL.rstd2),
-                           w->ln2_g, dy, dx1, M, s.D, st));
 
     // ---- attention side ----
     if (grads->b_o && w->b_o && nl > 0) {
-        rc = bias_grad(s, dx1, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
+        rc = bias_grad(s, dx1_in, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     // heads that are not p_f: gradient slices are +0.0 in overwrite mode, untouched in accumulate mode
@@ -626,7 +682,15 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
             if (grads->ln1_b) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, 0, st));
         }
     }
-    if (nf == 0) return flush_bias_grads(desc, s, &bias_batch, none, st);
+    if (nf == 0) {
+        if (!dx1) {   // gated, no p_f subnet: the gradient passes by the residual route unchanged
+            timing_begin(st, "copy");
+            const hipError_t e = hipMemcpyAsync(dx, dy, (size_t)s.M * s.D * s.es, hipMemcpyDeviceToDevice, st);
+            timing_end(st);
+            if (e != hipSuccess) return D2FT_EDEVICE;
+        }
+        return flush_bias_grads(desc, s, &bias_batch, none, ffn_tbl, st);
+    }
 
     const long ldq = (long)nl * 192, ldo = (long)nl * 64;
     const long ld_do = (long)nf * 64, ld_dq = (long)nf * 192;
@@ -667,7 +731,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         }
     }
     if (grads->b_qkv) {
-        rc = bias_grad(s, ws + WL.dqkv, ld_dq, nf * 192, colpart + 3 * WL.colpart_stride, grads->b_qkv, 1, &bias_batch, st);
+        rc = bias_grad(s, ws + WL.dqkv, ld_dq, nf * 192, colpart + 3 * WL.colpart_stride, grads->b_qkv, 1, &bias_batch, st);   // table a
         if (rc != D2FT_OK) return rc;
     }
     {   // du = dQKV W_eff (rows of the p_f heads)
@@ -702,7 +766,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     // dx = dx1 + LN1bwd(du)
     D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1), (const float*)(sv + SL.rstd1), w->ln1_g,
                            dx1, dx, M, s.D, st));
-    return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, st);
+    return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st);
 }
 
 size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const int32_t* cap_full,

@@ -295,7 +295,8 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 // order, eight loads in flight at a time (the same order as reduce_partials_kernel on one row)
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void col_reduce_batch_kernel(ColReduceBatch batch, int accumulate, Remap64 tbl) {
+__global__ __launch_bounds__(256) void col_reduce_batch_kernel(ColReduceBatch batch, int accumulate, Remap64 tbl_a,
+                                                                Remap64 tbl_b) {
     const ColReduceJob job = batch.job[blockIdx.y];
     const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c >= job.cols) return;
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(256) void col_reduce_batch_kernel(ColReduceBatch ba
         const float4 v = *reinterpret_cast<const float4*>(src + (long)k * job.cols);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
-    T* o = static_cast<T*>(job.out) + (job.remap_cols ? tbl(c) : c);
+    T* o = static_cast<T*>(job.out) + (job.remap_cols == 1 ? tbl_a(c) : (job.remap_cols == 2 ? tbl_b(c) : c));
     if (accumulate) {
         s.x += ld<T>(o); s.y += ld<T>(o + 1); s.z += ld<T>(o + 2); s.w += ld<T>(o + 3);
     }
@@ -349,6 +350,21 @@ __global__ __launch_bounds__(256) void zero_head_slices_kernel(HeadList heads, i
         if (g_lb_q) zero_span(g_lb_q + (long)h * 64 * r, (long)64 * r, tid, nth);
         if (g_lb_v) zero_span(g_lb_v + (long)h * 64 * r, (long)64 * r, tid, nth);
     }
+}
+
+// ---------------------------------------------------------------------------
+// +0.0 into the feed-forward gradient slices of the listed heads: rows [h*S, (h+1)*S) of w1 [Dm][D]
+// and of b1, columns [h*S, (h+1)*S) of w2 [D][Dm]
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void zero_ffn_slices_kernel(HeadList heads, int S, int D, int Dm, T* g_w1, T* g_b1,
+                                                              T* g_w2) {
+    const int h = heads.h[blockIdx.y];
+    const int tid = blockIdx.x * 256 + threadIdx.x, nth = gridDim.x * 256;
+    if (g_w1) zero_span(g_w1 + (long)h * S * D, (long)S * D, tid, nth);
+    if (g_b1) zero_span(g_b1 + (long)h * S, S, tid, nth);
+    if (g_w2)
+        for (long i = tid; i < (long)D * S; i += nth) g_w2[(i / S) * Dm + (long)h * S + (i % S)] = static_cast<T>(0.0f);
 }
 
 // ---------------------------------------------------------------------------
@@ -535,13 +551,22 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
     return hipGetLastError();
 }
 
-hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const Remap64& tbl, int accumulate,
-                                   hipStream_t s) {
+hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const Remap64& tbl_a, const Remap64& tbl_b,
+                                   int accumulate, hipStream_t s) {
     if (batch.n <= 0) return hipSuccess;
     int cols = 0;
     for (int i = 0; i < batch.n; ++i) cols = batch.job[i].cols > cols ? batch.job[i].cols : cols;   // multiples of 8
     const dim3 grid((unsigned)((cols / 4 + 255) / 256), batch.n), block(256);
-    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(col_reduce_batch_kernel<T>, grid, block, 0, s, batch, accumulate, tbl);)
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(col_reduce_batch_kernel<T>, grid, block, 0, s, batch, accumulate, tbl_a, tbl_b);)
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_ffn_slices(int dtype, const HeadList& heads, int slice, int D, int Dm, void* g_w1, void* g_b1,
+                                  void* g_w2, hipStream_t s) {
+    if (heads.n <= 0 || (!g_w1 && !g_b1 && !g_w2)) return hipSuccess;
+    const dim3 grid(32, heads.n), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(zero_ffn_slices_kernel<T>, grid, block, 0, s, heads, slice, D, Dm, (T*)g_w1,
+                                            (T*)g_b1, (T*)g_w2);)
     return hipGetLastError();
 }
 

@@ -21,9 +21,13 @@ def rel_inf(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))
 
 
-def oracle_block(w: di.Workload, weights: Dict[str, Optional[np.ndarray]], ops: Sequence[int], x, dy):
+FLAG_GATE_FFN = 4   # the op code of a head also governs its 1/H slice of the feed-forward network
+
+
+def oracle_block(w: di.Workload, weights: Dict[str, Optional[np.ndarray]], ops: Sequence[int], x, dy,
+                 gate_ffn: bool = False):
     from oracle import d2ft_oracle as orc
-    y, cache = orc.block_fwd(weights, ops, x, w.head_dim, w.ln_eps, w.lora_scale)
+    y, cache = orc.block_fwd(weights, ops, x, w.head_dim, w.ln_eps, w.lora_scale, gate_ffn=gate_ffn)
     dx, g = orc.block_bwd(weights, cache, dy)
     return y, dx, g, cache
 
@@ -58,7 +62,8 @@ def gpu_block(w: di.Workload, weights: Dict[str, Optional[np.ndarray]], ops: Seq
     return host(y), host(dx), {k: host(v) for k, v in grads.items()}
 
 
-def compare_block(w: di.Workload, ops, got, ref, tol: float, grad_fields=GRAD_FIELDS_ALL, report=None):
+def compare_block(w: di.Workload, ops, got, ref, tol: float, grad_fields=GRAD_FIELDS_ALL, report=None,
+                  gate_ffn: bool = False):
     """got = (y, dx, grads) from the GPU, ref = (y, dx, grads) from the oracle."""
     y, dx, g = got
     ry, rdx, rg = ref[:3]
@@ -83,6 +88,11 @@ def compare_block(w: di.Workload, ops, got, ref, tol: float, grad_fields=GRAD_FI
         if g.get("w_o") is not None: slices.append(g["w_o"][:, h * dh:(h + 1) * dh])
         for k in ("lora_a_q", "lora_a_v", "lora_b_q", "lora_b_v"):
             if g.get(k) is not None: slices.append(g[k][h])
+        if gate_ffn:
+            S = w.mlp_hidden // w.heads
+            if g.get("w1") is not None: slices.append(g["w1"][h * S:(h + 1) * S])
+            if g.get("b1") is not None: slices.append(g["b1"][h * S:(h + 1) * S])
+            if g.get("w2") is not None: slices.append(g["w2"][:, h * S:(h + 1) * S])
         for s in slices:
             assert np.all(s == 0.0) and not np.any(np.signbit(s)), f"head {h} (op {o}) has a non-zero gradient"
     return errs
