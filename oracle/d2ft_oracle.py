@@ -13,6 +13,8 @@ What it follows:
   * The LoRA extension: per-head adapters, base frozen (Sec. II-D).
   * The analytic cost rules (Sec. IV-A "Analysis of computational and
     communicational cost").
+  * The two contribution scores of a subnet (Sec. II-B "Contribution scores"):
+    Fisher information (sum of squared gradient entries) and weight magnitude.
 
 Readings taken where the paper is silent or garbled (each also listed in the
 design notes of the repository):
@@ -32,6 +34,12 @@ design notes of the repository):
     slice, p_o keeps its forward term as a constant, p_f trains it.  The second
     layer's bias is added iff at least one slice is live, the same rule as for
     the output-projection bias, so an all-shortcut block is the identity.
+  * "Weight magnitude" is the sum of absolute values of the subnet's weights.
+    A subnet's tensors are the slices that belong to one head alone: its
+    Q/K/V weight rows and biases, its output-projection columns, its LoRA
+    adapters, and (whole-subnet gating) its feed-forward slice.  LayerNorm
+    parameters (frozen and replicated, Sec. IV-A) and the two shared output
+    biases belong to no single subnet and are left out.
   * In DPSearching the item weight tested and subtracted in the fill phase is
     the operation's own weight (W_p), as the backtracking phase uses; the
     backtracking index decrements by one.
@@ -307,6 +315,47 @@ def stack_bwd(weights: List[dict], caches: List[dict], dy: np.ndarray):
     for l in range(len(weights) - 1, -1, -1):
         d, grads[l] = block_bwd(weights[l], caches[l], d)
     return d, grads
+
+
+# ----------------------------------------------------------------------------
+# contribution scores (Sec. II-B)
+# ----------------------------------------------------------------------------
+def subnet_scores(t: Dict[str, Optional[np.ndarray]], heads: int, head_dim: int, kind: str,
+                  gate_ffn: bool = False) -> np.ndarray:
+    """Score of every subnet of one block from tensors in the weight layout.
+
+    kind "fisher": sum of squared entries (t holds the gradients of one sample or
+    micro-batch: empirical Fisher information); kind "magnitude": sum of absolute
+    values (t holds the weights).  Fields that are None are skipped.
+    Returns [heads] float64.
+    """
+    if kind not in ("fisher", "magnitude"):
+        raise ValueError(kind)
+    f = (lambda a: float((a * a).sum())) if kind == "fisher" else (lambda a: float(np.abs(a).sum()))
+    t = {k: _f64(v) for k, v in t.items()}
+    dh = head_dim
+    out = np.zeros(heads, dtype=np.float64)
+    for h in range(heads):
+        parts = []
+        if t.get("w_qkv") is not None:
+            parts.append(t["w_qkv"][:, h])
+        if t.get("b_qkv") is not None:
+            parts.append(t["b_qkv"][:, h])
+        if t.get("w_o") is not None:
+            parts.append(t["w_o"][:, h * dh:(h + 1) * dh])
+        for k in ("lora_a_q", "lora_a_v", "lora_b_q", "lora_b_v"):
+            if t.get(k) is not None:
+                parts.append(t[k][h])
+        if gate_ffn:
+            S = (t["w1"] if t.get("w1") is not None else t["w2"].T).shape[0] // heads
+            if t.get("w1") is not None:
+                parts.append(t["w1"][h * S:(h + 1) * S])
+            if t.get("b1") is not None:
+                parts.append(t["b1"][h * S:(h + 1) * S])
+            if t.get("w2") is not None:
+                parts.append(t["w2"][:, h * S:(h + 1) * S])
+        out[h] = sum(f(a) for a in parts)
+    return out
 
 
 # ----------------------------------------------------------------------------
