@@ -146,7 +146,20 @@ def main() -> int:
         stack.step(x, dy, ops)
     torch.cuda.synchronize()
     kern = P.d2ft_timing_read(64)
+    # contribution-score kernels (Sec. II-B): Fisher scores of every block's gradients, timed the same way
+    P.d2ft_timing_enable(True)
+    for l in range(w.blocks):
+        P.d2ft_subnet_scores(desc, stack.grads[l], P.SCORE_FISHER)
+    sc = [k for k in P.d2ft_timing_read(8) if "scores" in k["name"]]
     P.d2ft_timing_enable(False)
+    head_bytes = sum(t.numel() * t.element_size() for k, t in stack.grads[0].items()
+                     if t is not None and (k in ("w_qkv", "b_qkv", "w_o") or k.startswith("lora")
+                                           or (w.gate_ffn and k in ("w1", "b1", "w2"))))
+    scores = None
+    if sc:
+        us = sc[0]["ms"] / sc[0]["launches"] * 1e3
+        scores = {"kind": "fisher", "us_per_block": round(us, 2), "bytes_per_block": head_bytes,
+                  "GB_per_s": round(head_bytes / (us * 1e-6) / 1e9, 1)}
     kern.sort(key=lambda k: -k["ms"])
     total_kernel_ms = sum(k["ms"] for k in kern) / n_prof
     dom = kern[0]
@@ -182,6 +195,7 @@ def main() -> int:
             "masked_over_all_full_time": round(ms / ms_full, 4)},
         "kernel_ms_per_step_sum": round(total_kernel_ms, 4),
         "roofline": roofline,
+        "subnet_scores": scores,
         "kernels": kernels[:12],
     }
 

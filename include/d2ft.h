@@ -190,6 +190,28 @@ d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items,
                                  uint8_t *ops_out, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
 
+/* Contribution scores of the subnets of one block (Sec. II-B, contribution scores): for every
+ * head h, over the tensor slices that belong to that subnet alone - Q/K/V weight rows and
+ * biases, output-projection columns, LoRA adapters and, with D2FT_FLAG_GATE_FFN, the head's
+ * feed-forward slice (w1 rows, b1, w2 columns) -
+ *   D2FT_SCORE_FISHER     sum of squared entries: with `tensors` holding the gradients of one sample
+ *                         or micro-batch this is the empirical Fisher information, the backward score;
+ *   D2FT_SCORE_MAGNITUDE  sum of absolute values: with `tensors` holding the weights this is the
+ *                         weight magnitude, the forward score.
+ * LayerNorm parameters and the shared biases b_o, b2 belong to no single subnet and are not
+ * read.  Sums are accumulated in fp64 in a fixed order (the result does not depend on timing).
+ * The scores feed d2ft_select_knapsack; like it, the call synchronises the stream before it returns.
+ *   tensors     HOST struct of DEVICE pointers in the weight layout (gradients are passed through
+ *               the same struct); NULL fields are skipped
+ *   scores_out  HOST [heads]
+ *   workspace   DEVICE, at least d2ft_scores_workspace_bytes(desc) bytes, 256-byte aligned
+ * Errors: D2FT_EINVAL for NULL desc / tensors / scores_out / workspace, a bad kind or a
+ * misaligned pointer; D2FT_ESHAPE for an unsupported shape or a workspace that is too small. */
+typedef enum { D2FT_SCORE_FISHER = 0, D2FT_SCORE_MAGNITUDE = 1 } d2ft_score_kind;
+size_t d2ft_scores_workspace_bytes(const d2ft_block_desc *desc);
+d2ft_status d2ft_subnet_scores(const d2ft_block_desc *desc, const d2ft_block_weights *tensors, int32_t kind,
+                               double *scores_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Diagnostics: per-kernel timing.  While enabled, every kernel launch the library makes is
  * bracketed by a pair of HIP events on the stream of the call (this adds host work per launch:
  * do not time whole steps while it is on).  d2ft_timing_enable(1) clears earlier records and

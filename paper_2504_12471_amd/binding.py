@@ -70,6 +70,14 @@ _lib.d2ft_select_knapsack.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 
 
+_lib.d2ft_scores_workspace_bytes.restype = C.c_size_t
+_lib.d2ft_scores_workspace_bytes.argtypes = [C.POINTER(BlockDesc)]
+_lib.d2ft_subnet_scores.restype = C.c_int
+_lib.d2ft_subnet_scores.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.c_size_t, C.c_void_p]
+SCORE_FISHER, SCORE_MAGNITUDE = 0, 1
+
+
 class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -198,8 +206,23 @@ def d2ft_select_knapsack(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, ca
     return out
 
 
+def d2ft_subnet_scores(desc: BlockDesc, tensors: Dict[str, Optional[torch.Tensor]], kind: int,
+                       workspace: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> np.ndarray:
+    """Per-head contribution scores (host float64 [heads]) of tensors laid out like the block's weights."""
+    need = int(_lib.d2ft_scores_workspace_bytes(C.byref(desc)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    out = np.zeros(desc.heads, dtype=np.float64)
+    ptrs = _ptr_struct(tensors)
+    st = _lib.d2ft_subnet_scores(C.byref(desc), C.byref(ptrs), int(kind), out.ctypes.data, _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "d2ft_subnet_scores")
+    return out
+
+
 def exported_symbols():
     """Names this binding resolves in the shared library (used by the load test)."""
     return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
             "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
-            "d2ft_timing_enable", "d2ft_timing_read"]
+            "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_timing_enable", "d2ft_timing_read"]

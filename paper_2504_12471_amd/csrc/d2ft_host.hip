@@ -769,6 +769,36 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st);
 }
 
+size_t d2ft_scores_workspace_bytes(const d2ft_block_desc* desc) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    return align256((size_t)desc->heads * (kScoreChunks + 1) * sizeof(double));
+}
+
+d2ft_status d2ft_subnet_scores(const d2ft_block_desc* desc, const d2ft_block_weights* t, int32_t kind, double* scores_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!t || !scores_out || !workspace || ((uintptr_t)workspace & 255)) return D2FT_EINVAL;
+    if (kind != D2FT_SCORE_FISHER && kind != D2FT_SCORE_MAGNITUDE) return D2FT_EINVAL;
+    if (workspace_bytes < d2ft_scores_workspace_bytes(desc)) return D2FT_ESHAPE;
+    const Dims s = dims_of(desc);
+    ScoreTensors st_;
+    st_.w_qkv = t->w_qkv; st_.b_qkv = t->b_qkv; st_.w_o = t->w_o;
+    st_.la_q = t->lora_a_q; st_.la_v = t->lora_a_v; st_.lb_q = t->lora_b_q; st_.lb_v = t->lora_b_v;
+    st_.w1 = t->w1; st_.b1 = t->b1; st_.w2 = t->w2;
+    st_.H = s.H; st_.D = s.D; st_.Dm = s.Dm; st_.r = s.r;
+    st_.slice = (desc->flags & D2FT_FLAG_GATE_FFN) ? s.Dm / s.H : 0;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    double* partial = static_cast<double*>(workspace);
+    double* out = partial + (size_t)s.H * kScoreChunks;
+    D2FT_TRY(launch_subnet_scores(s.dtype, st_, kind, partial, out, st));
+    if (hipMemcpyAsync(scores_out, out, (size_t)s.H * sizeof(double), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return D2FT_EDEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return D2FT_EDEVICE;
+    return D2FT_OK;
+}
+
 size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const int32_t* cap_full,
                                      const int32_t* cap_fwd) {
     if (n_knapsacks < 1 || n_items < 1 || !cap_full || !cap_fwd) return 0;

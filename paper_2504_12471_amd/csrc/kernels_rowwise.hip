@@ -502,6 +502,60 @@ __global__ __launch_bounds__(256) void lora_grad_b_kernel(const float* __restric
         __VA_ARGS__                                \
     }
 
+// ---------------------------------------------------------------------------
+// contribution scores: blockIdx.y = head, blockIdx.x = chunk.  A chunk's threads stride over every
+// slice the head owns and add x*x (kind 0) or |x| (kind 1) in fp64; the workgroup's 256 sums are
+// added by a fixed tree, the chunks of a head in index order by score_final_kernel.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void score_partial_kernel(ScoreTensors t, int kind, double* __restrict__ partial) {
+    __shared__ double red[256];
+    const int h = blockIdx.y;
+    const long tid = (long)blockIdx.x * 256 + threadIdx.x, nth = (long)gridDim.x * 256;
+    double acc = 0.0;
+    // elements base[r * stride + c], r < rows, c < cols
+    auto span = [&](const void* p, long first, long rows, long cols, long stride) {
+        if (!p) return;
+        const T* base = static_cast<const T*>(p) + first;
+        for (long i = tid; i < rows * cols; i += nth) {
+            const double v = (double)ld<T>(base + (i / cols) * stride + (i % cols));
+            acc += kind == 0 ? v * v : fabs(v);
+        }
+    };
+    const long D = t.D, H = t.H, r = t.r, S = t.slice;
+    for (int p = 0; p < 3; ++p) {
+        span(t.w_qkv, ((long)p * H + h) * 64 * D, 1, 64 * D, 64 * D);
+        span(t.b_qkv, ((long)p * H + h) * 64, 1, 64, 64);
+    }
+    span(t.w_o, (long)h * 64, D, 64, H * 64);
+    if (r > 0) {
+        span(t.la_q, (long)h * r * D, 1, r * D, r * D);
+        span(t.la_v, (long)h * r * D, 1, r * D, r * D);
+        span(t.lb_q, (long)h * 64 * r, 1, 64 * r, 64 * r);
+        span(t.lb_v, (long)h * 64 * r, 1, 64 * r, 64 * r);
+    }
+    if (S > 0) {
+        span(t.w1, (long)h * S * D, 1, S * D, S * D);
+        span(t.b1, (long)h * S, 1, S, S);
+        span(t.w2, (long)h * S, D, S, t.Dm);
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[(long)h * gridDim.x + blockIdx.x] = red[0];
+}
+
+__global__ void score_final_kernel(const double* __restrict__ partial, int chunks, int H, double* __restrict__ out) {
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= H) return;
+    double s = 0.0;
+    for (int c = 0; c < chunks; ++c) s += partial[(long)h * chunks + c];
+    out[h] = s;
+}
+
 hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean,
                          float* rstd, int rows, int width, float eps, hipStream_t s) {
     const dim3 grid((rows + 3) / 4), block(256);
@@ -548,6 +602,15 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL(reduce_partials_kernel<T>, grid, block, 0, s, partial, splits,
                                             slice_stride, rows, cols, (T*)out, ldo, remap, accumulate, tbl);)
+    return hipGetLastError();
+}
+
+hipError_t launch_subnet_scores(int dtype, const ScoreTensors& t, int kind, double* partial, double* out, hipStream_t s) {
+    const dim3 grid(kScoreChunks, t.H), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(score_partial_kernel<T>, grid, block, 0, s, t, kind, partial);)
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(score_final_kernel, dim3((t.H + 63) / 64), dim3(64), 0, s, partial, kScoreChunks, t.H, out);
     return hipGetLastError();
 }
 
