@@ -40,6 +40,10 @@ design notes of the repository):
     adapters, and (whole-subnet gating) its feed-forward slice.  LayerNorm
     parameters (frozen and replicated, Sec. IV-A) and the two shared output
     biases belong to no single subnet and are left out.
+  * Micro-batches: the scheduling table holds one code per (subnet, micro-batch)
+    (Alg. 1, T_opt[k][x_i]); a block call over several micro-batches applies
+    each micro-batch's codes to its own images, and a weight gradient is the
+    sum of the micro-batches' gradients (gradient accumulation).
   * In DPSearching the item weight tested and subtracted in the fill phase is
     the operation's own weight (W_p), as the backtracking phase uses; the
     backtracking index decrements by one.
@@ -296,6 +300,40 @@ def block_bwd(w: Dict[str, Optional[np.ndarray]], cache: dict, dy: np.ndarray):
                 du = du + dt @ a
     dln1, g["ln1_g"], g["ln1_b"] = layer_norm_bwd(du, cache["xhat1"], cache["rstd1"], w["ln1_g"])
     return dx1 + dln1, g
+
+
+# ----------------------------------------------------------------------------
+# one block over several micro-batches, each with its own op codes (Alg. 1, T_opt[k][x_i])
+# ----------------------------------------------------------------------------
+def block_fwd_mb(w, ops_mb: Sequence[Sequence[int]], mb_images: Sequence[int], x: np.ndarray, head_dim: int,
+                 ln_eps: float = 1e-6, lora_scale: float = 1.0, gate_ffn: bool = False):
+    """x: [B, T, D] with B = sum(mb_images); micro-batch i is the next mb_images[i] images and runs
+    under ops_mb[i].  Returns (y, caches)."""
+    x = _f64(x)
+    if sum(mb_images) != x.shape[0] or len(ops_mb) != len(mb_images):
+        raise ValueError("micro-batch sizes must add up to the batch")
+    ys, caches, b0 = [], [], 0
+    for ops, nb in zip(ops_mb, mb_images):
+        y, c = block_fwd(w, ops, x[b0:b0 + nb], head_dim, ln_eps, lora_scale, gate_ffn=gate_ffn)
+        ys.append(y)
+        caches.append(c)
+        b0 += nb
+    return np.concatenate(ys, axis=0), caches
+
+
+def block_bwd_mb(w, caches: List[dict], mb_images: Sequence[int], dy: np.ndarray):
+    """Backward of block_fwd_mb: dx per micro-batch, weight gradients summed over the micro-batches."""
+    dy = _f64(dy)
+    dxs, total, b0 = [], None, 0
+    for c, nb in zip(caches, mb_images):
+        dx, g = block_bwd(w, c, dy[b0:b0 + nb])
+        dxs.append(dx)
+        if total is None:
+            total = g
+        else:
+            total = {k: (None if v is None else v + g[k]) for k, v in total.items()}
+        b0 += nb
+    return np.concatenate(dxs, axis=0), total
 
 
 # ----------------------------------------------------------------------------
