@@ -26,10 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
-def algorithmic_flops(w, ops) -> float:
+def algorithmic_flops(w, ops, rows=None) -> float:
     """FLOPs one step must do: skipped heads and the backward of non-full heads are not counted."""
     import d2ft_inputs as di
-    M, D, T, dh, Dm, r = w.rows, w.width, w.tokens, w.head_dim, w.mlp_hidden, w.lora_rank
+    M, D, T, dh, Dm, r = (w.rows if rows is None else rows), w.width, w.tokens, w.head_dim, w.mlp_hidden, w.lora_rank
     total = 0.0
     for l in range(ops.shape[0]):
         n_full = int((ops[l] == di.OP_FULL).sum())
@@ -79,6 +79,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-all-full", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--micro", type=int, default=0,
+                    help="split the batch into this many micro-batches, each with its own op codes (0: one code per head)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -114,7 +116,19 @@ def main() -> int:
         grad_fields = [k for k in P.WEIGHT_FIELDS if not k.startswith("ln")]   # norm layers frozen (Sec. III-A)
     else:
         grad_fields = ["lora_a_q", "lora_a_v", "lora_b_q", "lora_b_v"]
-    stack = P.BlockStack(desc, dws, w.dtype, grad_fields)
+    mb_images = None
+    if args.micro > 0:
+        # one code per (subnet, micro-batch) (Alg. 1, T_opt[k][x_i]); the same mask recipe over all of them
+        base, extra = divmod(w.batch, args.micro)
+        mb_images = [base + (1 if i < extra else 0) for i in range(args.micro)]
+        if w.mask[0] != "counts" or base < 1:
+            print("bench.py: --micro needs a counts mask and at least one image per micro-batch", file=sys.stderr)
+            return 2
+        rng = np.random.default_rng(args.seed + 1000)
+        ops = di.exact_count_masks(rng, w.blocks * args.micro, w.heads, *w.mask[1:]).reshape(
+            w.blocks, args.micro, w.heads)
+        full_ops = np.full_like(ops, di.OP_FULL)
+    stack = P.BlockStack(desc, dws, w.dtype, grad_fields, mb_images)
     x, dy = P.to_device(s.x, w.dtype), P.to_device(s.dy, w.dtype)
 
     # step time measured the same with 3 and with 100 warm-up steps; the default of 20 is margin
@@ -178,7 +192,10 @@ def main() -> int:
                 "ms_per_step": round(k["ms"] / n_prof, 4),
                 "tflops": round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 1) if k["flops"] > 0 else None} for k in kern]
 
-    flops = algorithmic_flops(w, ops)
+    if mb_images is None:
+        flops = algorithmic_flops(w, ops)
+    else:
+        flops = sum(algorithmic_flops(w, ops[:, i], mb_images[i] * w.tokens) for i in range(args.micro))
     out = {
         "metric": "fine-tune step images/sec, ViT block stack with per-head op codes",
         "value": round(w.batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
@@ -186,7 +203,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic (seeded N(0,1) tokens, N(0,0.02^2) weights)",
         "config": {"workload": w.name, "batch": w.batch, "tokens": w.tokens, "width": w.width, "heads": w.heads,
                    "mlp_hidden": w.mlp_hidden, "blocks": w.blocks, "lora_rank": w.lora_rank, "gate_ffn": w.gate_ffn,
-                   "heads_full": int((ops == di.OP_FULL).sum()), "heads_fwd_only": int((ops == di.OP_FWD).sum()),
+                   "micro_batches": mb_images, "heads_full": int((ops == di.OP_FULL).sum()), "heads_fwd_only": int((ops == di.OP_FWD).sum()),
                    "heads_skipped": int((ops == di.OP_SKIP).sum())},
         "algorithmic_tflop_per_step": round(flops / 1e12, 3),
         "step_mfma_frac": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -211,9 +228,14 @@ def main() -> int:
         t0 = time.perf_counter()
         n_done = 0
         while n_done < w.blocks and time.perf_counter() - t0 < 12.0:   # a bounded sample: about 12 s of CPU work
-            y, cache = orc.block_fwd(s.weights[n_done], ops[n_done], s.x, w.head_dim, w.ln_eps, w.lora_scale,
-                                     gate_ffn=w.gate_ffn)
-            orc.block_bwd(s.weights[n_done], cache, s.dy)
+            if mb_images is None:
+                y, cache = orc.block_fwd(s.weights[n_done], ops[n_done], s.x, w.head_dim, w.ln_eps, w.lora_scale,
+                                         gate_ffn=w.gate_ffn)
+                orc.block_bwd(s.weights[n_done], cache, s.dy)
+            else:
+                y, caches = orc.block_fwd_mb(s.weights[n_done], ops[n_done], mb_images, s.x, w.head_dim, w.ln_eps,
+                                             w.lora_scale, gate_ffn=w.gate_ffn)
+                orc.block_bwd_mb(s.weights[n_done], caches, mb_images, s.dy)
             n_done += 1
         t_block = (time.perf_counter() - t0) / n_done
         out["cpu_baseline"] = {

@@ -145,7 +145,7 @@ d2ft_status d2ft_compact_heads(const uint8_t *ops, int32_t heads, int32_t *live,
  *   u  = LN1(x)                                   (skipped if no head is live)
  *   for live heads h: [Q K V]_h = u W_{qkv,h}^T + b (+ LoRA), O_h = softmax(Q K^T / 8) V
  *   x1 = x + sum_{live h} O_h W_{o,h}^T (+ b_o if any head is live)
- *   y  = x1 + W2 GELU(W1 LN2(x1) + b1) + b2       (erf GELU; the MLP is never gated)
+ *   y  = x1 + W2 GELU(W1 LN2(x1) + b1) + b2       (erf GELU; not gated unless D2FT_FLAG_GATE_FFN is set)
  *   ops      HOST [heads]
  *   x        [B][T][D] input hidden states
  *   y        [B][T][D] output; must not alias x
@@ -167,6 +167,29 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc *desc, const d2ft_block_weights
                            const uint8_t *ops, const void *x, const void *dy, void *dx,
                            const d2ft_block_grads *grads, const void *saved, void *scratch,
                            void *hip_stream);
+
+/* One block over several micro-batches, each with its own op codes: the scheduling table of
+ * Alg. 1 holds one code per (subnet, micro-batch), T_opt[k][x_i], and Sec. IV-A splits a batch into
+ * micro-batches.  Micro-batch i is the next mb_images[i] images of x; it runs under
+ * ops[i*heads .. (i+1)*heads).  The backward adds the micro-batches' weight gradients
+ * (gradient accumulation): with D2FT_FLAG_ACCUM_GRADS clear the result overwrites the buffers
+ * and a subnet that is p_f in no micro-batch gets +0.0; with it set everything is added to what
+ * the buffers hold.  Micro-batches run one after the other on the stream.
+ *   n_micro    1 .. D2FT_MAX_MICRO
+ *   mb_images  HOST [n_micro], each >= 1, summing to desc->batch
+ *   ops        HOST [n_micro][heads]
+ *   saved      d2ft_block_saved_bytes_mb(desc, n_micro, mb_images) bytes
+ *   scratch    d2ft_block_scratch_bytes(desc) bytes
+ * Other arguments and errors as for d2ft_block_fwd / d2ft_block_bwd; bad micro-batch sizes give
+ * D2FT_ESHAPE. */
+#define D2FT_MAX_MICRO 64
+size_t d2ft_block_saved_bytes_mb(const d2ft_block_desc *desc, int32_t n_micro, const int32_t *mb_images);
+d2ft_status d2ft_block_fwd_mb(const d2ft_block_desc *desc, const d2ft_block_weights *weights, int32_t n_micro,
+                              const int32_t *mb_images, const uint8_t *ops, const void *x, void *y, void *saved,
+                              void *scratch, void *hip_stream);
+d2ft_status d2ft_block_bwd_mb(const d2ft_block_desc *desc, const d2ft_block_weights *weights, int32_t n_micro,
+                              const int32_t *mb_images, const uint8_t *ops, const void *x, const void *dy, void *dx,
+                              const d2ft_block_grads *grads, const void *saved, void *scratch, void *hip_stream);
 
 /* Bi-level knapsack selection of operation codes: Alg. 1 (KnapsackScheduling)
  * calling Alg. 2 (DPSearching) twice per knapsack - p_f items by backward

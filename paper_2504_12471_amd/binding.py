@@ -63,6 +63,14 @@ _lib.d2ft_block_fwd.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_void
 _lib.d2ft_block_bwd.restype = C.c_int
 _lib.d2ft_block_bwd.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.POINTER(_Ptrs), C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.d2ft_block_saved_bytes_mb.restype = C.c_size_t
+_lib.d2ft_block_saved_bytes_mb.argtypes = [C.POINTER(BlockDesc), C.c_int32, C.c_void_p]
+_lib.d2ft_block_fwd_mb.restype = C.c_int
+_lib.d2ft_block_fwd_mb.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.d2ft_block_bwd_mb.restype = C.c_int
+_lib.d2ft_block_bwd_mb.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.POINTER(_Ptrs), C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.d2ft_knapsack_workspace_bytes.restype = C.c_size_t
 _lib.d2ft_knapsack_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 _lib.d2ft_select_knapsack.restype = C.c_int
@@ -176,6 +184,40 @@ def d2ft_block_bwd(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], 
     _check(st, "d2ft_block_bwd")
 
 
+def _mb_arrays(desc: BlockDesc, mb_images: Sequence[int], ops) -> tuple:
+    mb = np.ascontiguousarray(np.asarray(mb_images, dtype=np.int32))
+    a = np.ascontiguousarray(np.asarray(ops, dtype=np.uint8))
+    if a.shape != (mb.shape[0], desc.heads):
+        raise ValueError("ops must be [n_micro, heads]")
+    return mb, a
+
+
+def d2ft_block_saved_bytes_mb(desc: BlockDesc, mb_images: Sequence[int]) -> int:
+    mb = np.ascontiguousarray(np.asarray(mb_images, dtype=np.int32))
+    return int(_lib.d2ft_block_saved_bytes_mb(C.byref(desc), mb.shape[0], mb.ctypes.data))
+
+
+def d2ft_block_fwd_mb(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], mb_images: Sequence[int], ops,
+                      x: torch.Tensor, y: torch.Tensor, saved: torch.Tensor, scratch: torch.Tensor,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+    mb, a = _mb_arrays(desc, mb_images, ops)
+    w = _ptr_struct(weights)
+    st = _lib.d2ft_block_fwd_mb(C.byref(desc), C.byref(w), mb.shape[0], mb.ctypes.data, a.ctypes.data, _ptr(x), _ptr(y),
+                                _ptr(saved), _ptr(scratch), _stream_ptr(stream))
+    _check(st, "d2ft_block_fwd_mb")
+
+
+def d2ft_block_bwd_mb(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], mb_images: Sequence[int], ops,
+                      x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, grads: Dict[str, Optional[torch.Tensor]],
+                      saved: torch.Tensor, scratch: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    mb, a = _mb_arrays(desc, mb_images, ops)
+    w = _ptr_struct(weights)
+    g = _ptr_struct(grads)
+    st = _lib.d2ft_block_bwd_mb(C.byref(desc), C.byref(w), mb.shape[0], mb.ctypes.data, a.ctypes.data, _ptr(x), _ptr(dy),
+                                _ptr(dx), C.byref(g), _ptr(saved), _ptr(scratch), _stream_ptr(stream))
+    _check(st, "d2ft_block_bwd_mb")
+
+
 def d2ft_knapsack_workspace_bytes(n_knapsacks: int, n_items: int, cap_full, cap_fwd) -> int:
     cf = np.ascontiguousarray(cap_full, dtype=np.int32)
     co = np.ascontiguousarray(cap_fwd, dtype=np.int32)
@@ -224,5 +266,6 @@ def d2ft_subnet_scores(desc: BlockDesc, tensors: Dict[str, Optional[torch.Tensor
 def exported_symbols():
     """Names this binding resolves in the shared library (used by the load test)."""
     return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
-            "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
+            "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_block_saved_bytes_mb", "d2ft_block_fwd_mb", "d2ft_block_bwd_mb",
+            "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
             "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_timing_enable", "d2ft_timing_read"]

@@ -140,14 +140,20 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
                                   void* out, long ldo, int remap, const Remap64& tbl, int accumulate,
                                   hipStream_t s);
 
-// per-head sums of squares (kind 0) or absolute values (kind 1) over the slices a head owns;
-// partial: [H][kScoreChunks] doubles, out: [H] doubles (both device)
-constexpr int kScoreChunks = 32;
-struct ScoreTensors {
-    const void *w_qkv, *b_qkv, *w_o, *la_q, *la_v, *lb_q, *lb_v, *w1, *b1, *w2;
-    int H, D, Dm, r, slice;   // slice = hidden units per head (0: the feed-forward network is not part of a subnet)
+// per-head sums of squares (kind 0) or absolute values (kind 1) over the slices a head owns.
+// A span is one slice family: for head h, elements p[first + h*head_stride + r*stride + c], r < rows,
+// c < 8*cols8; it is worked on by nchunks workgroups (chunk0 = index of its first one).
+// partial: [H][total_chunks] doubles, out: [H] doubles (both device)
+struct ScoreSpan {
+    const void* p;
+    long first, head_stride, stride;
+    int rows, cols8, chunk0, nchunks;
 };
-hipError_t launch_subnet_scores(int dtype, const ScoreTensors& t, int kind, double* partial, double* out, hipStream_t s);
+struct ScoreArgs {
+    ScoreSpan span[16];
+    int n, total_chunks, H;
+};
+hipError_t launch_subnet_scores(int dtype, const ScoreArgs& a, int kind, double* partial, double* out, hipStream_t s);
 
 // several independent column reductions out[c] = sum over chunks of partial[chunk][c] in one launch
 // (the bias gradients of one block); remap_cols = 1 or 2 sends column c to tbl_a(c) or tbl_b(c)

@@ -769,10 +769,122 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st);
 }
 
+// ---- micro-batches: the block calls applied to consecutive image ranges ----
+static bool micro_ok(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
+    if (n_micro < 1 || n_micro > D2FT_MAX_MICRO || !mb_images) return false;
+    long sum = 0;
+    for (int i = 0; i < n_micro; ++i) {
+        if (mb_images[i] < 1) return false;
+        sum += mb_images[i];
+    }
+    return sum == desc->batch;
+}
+
+size_t d2ft_block_saved_bytes_mb(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why) || !micro_ok(desc, n_micro, mb_images)) return 0;
+    size_t total = 0;
+    for (int i = 0; i < n_micro; ++i) {
+        d2ft_block_desc d = *desc;
+        d.batch = mb_images[i];
+        total += saved_layout(dims_of(&d)).total;
+    }
+    return total;
+}
+
+d2ft_status d2ft_block_fwd_mb(const d2ft_block_desc* desc, const d2ft_block_weights* w, int32_t n_micro,
+                              const int32_t* mb_images, const uint8_t* ops, const void* x, void* y, void* saved,
+                              void* scratch, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!micro_ok(desc, n_micro, mb_images)) return mb_images ? D2FT_ESHAPE : D2FT_EINVAL;
+    if (!ops || !x || !y || !saved) return D2FT_EINVAL;
+    for (int i = 0; i < n_micro * desc->heads; ++i)   // validate every code before the first launch
+        if (ops[i] < D2FT_OP_FULL || ops[i] > D2FT_OP_SKIP) return D2FT_EINVAL;
+    const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
+    size_t img0 = 0, sv0 = 0;
+    for (int i = 0; i < n_micro; ++i) {
+        d2ft_block_desc d = *desc;
+        d.batch = mb_images[i];
+        const d2ft_status rc = d2ft_block_fwd(&d, w, ops + (size_t)i * desc->heads, static_cast<const char*>(x) + img0 * row_bytes,
+                                              static_cast<char*>(y) + img0 * row_bytes, static_cast<char*>(saved) + sv0,
+                                              scratch, hip_stream);
+        if (rc != D2FT_OK) return rc;
+        img0 += mb_images[i];
+        sv0 += saved_layout(dims_of(&d)).total;
+    }
+    return D2FT_OK;
+}
+
+d2ft_status d2ft_block_bwd_mb(const d2ft_block_desc* desc, const d2ft_block_weights* w, int32_t n_micro,
+                              const int32_t* mb_images, const uint8_t* ops, const void* x, const void* dy, void* dx,
+                              const d2ft_block_grads* grads, const void* saved, void* scratch, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!micro_ok(desc, n_micro, mb_images)) return mb_images ? D2FT_ESHAPE : D2FT_EINVAL;
+    if (!ops || !x || !dy || !dx || !saved || !grads) return D2FT_EINVAL;
+    for (int i = 0; i < n_micro * desc->heads; ++i)
+        if (ops[i] < D2FT_OP_FULL || ops[i] > D2FT_OP_SKIP) return D2FT_EINVAL;
+    const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
+    size_t img0 = 0, sv0 = 0;
+    for (int i = 0; i < n_micro; ++i) {
+        d2ft_block_desc d = *desc;
+        d.batch = mb_images[i];
+        if (i > 0) d.flags |= D2FT_FLAG_ACCUM_GRADS;   // later micro-batches add to the first one's result
+        const d2ft_status rc = d2ft_block_bwd(&d, w, ops + (size_t)i * desc->heads, static_cast<const char*>(x) + img0 * row_bytes,
+                                              static_cast<const char*>(dy) + img0 * row_bytes,
+                                              static_cast<char*>(dx) + img0 * row_bytes, grads,
+                                              static_cast<const char*>(saved) + sv0, scratch, hip_stream);
+        if (rc != D2FT_OK) return rc;
+        img0 += mb_images[i];
+        sv0 += saved_layout(dims_of(&d)).total;
+    }
+    return D2FT_OK;
+}
+
+// spans of the tensors one head owns; pointers may be NULL (then the span is dropped)
+static ScoreArgs score_spans(const d2ft_block_desc* desc, const d2ft_block_weights* t) {
+    const Dims s = dims_of(desc);
+    const long D = s.D, H = s.H, r = s.r, Dm = s.Dm;
+    const long S = (desc->flags & D2FT_FLAG_GATE_FFN) ? Dm / H : 0;
+    ScoreArgs a;
+    memset(&a, 0, sizeof(a));
+    a.H = (int)H;
+    auto add = [&](const void* p, bool present, long first, long head_stride, long rows, long cols, long stride) {
+        if (!present) return;
+        ScoreSpan& sp = a.span[a.n++];
+        sp.p = p; sp.first = first; sp.head_stride = head_stride; sp.stride = stride;
+        sp.rows = (int)rows; sp.cols8 = (int)(cols / 8);
+        long n = (rows * cols / 8 + 1023) / 1024;   // about four 8-element pieces per thread
+        sp.nchunks = (int)(n < 1 ? 1 : (n > 64 ? 64 : n));
+        sp.chunk0 = a.total_chunks;
+        a.total_chunks += sp.nchunks;
+    };
+    // with t == NULL every span counts (sizing the workspace)
+    for (long p = 0; p < 3; ++p) {
+        add(t ? t->w_qkv : nullptr, !t || t->w_qkv, p * H * 64 * D, 64 * D, 1, 64 * D, 64 * D);
+        add(t ? t->b_qkv : nullptr, !t || t->b_qkv, p * H * 64, 64, 1, 64, 64);
+    }
+    add(t ? t->w_o : nullptr, !t || t->w_o, 0, 64, D, 64, H * 64);
+    if (r > 0) {
+        add(t ? t->lora_a_q : nullptr, !t || t->lora_a_q, 0, r * D, 1, r * D, r * D);
+        add(t ? t->lora_a_v : nullptr, !t || t->lora_a_v, 0, r * D, 1, r * D, r * D);
+        add(t ? t->lora_b_q : nullptr, !t || t->lora_b_q, 0, 64 * r, 1, 64 * r, 64 * r);
+        add(t ? t->lora_b_v : nullptr, !t || t->lora_b_v, 0, 64 * r, 1, 64 * r, 64 * r);
+    }
+    if (S > 0) {
+        add(t ? t->w1 : nullptr, !t || t->w1, 0, S * D, 1, S * D, S * D);
+        add(t ? t->b1 : nullptr, !t || t->b1, 0, S, 1, S, S);
+        add(t ? t->w2 : nullptr, !t || t->w2, 0, S, D, S, Dm);
+    }
+    return a;
+}
+
 size_t d2ft_scores_workspace_bytes(const d2ft_block_desc* desc) {
     d2ft_status why;
     if (!desc_ok(desc, &why)) return 0;
-    return align256((size_t)desc->heads * (kScoreChunks + 1) * sizeof(double));
+    const ScoreArgs a = score_spans(desc, nullptr);
+    return align256((size_t)desc->heads * (a.total_chunks + 1) * sizeof(double));
 }
 
 d2ft_status d2ft_subnet_scores(const d2ft_block_desc* desc, const d2ft_block_weights* t, int32_t kind, double* scores_out,
@@ -781,19 +893,23 @@ d2ft_status d2ft_subnet_scores(const d2ft_block_desc* desc, const d2ft_block_wei
     if (!desc_ok(desc, &why)) return why;
     if (!t || !scores_out || !workspace || ((uintptr_t)workspace & 255)) return D2FT_EINVAL;
     if (kind != D2FT_SCORE_FISHER && kind != D2FT_SCORE_MAGNITUDE) return D2FT_EINVAL;
-    if (workspace_bytes < d2ft_scores_workspace_bytes(desc)) return D2FT_ESHAPE;
-    const Dims s = dims_of(desc);
-    ScoreTensors st_;
-    st_.w_qkv = t->w_qkv; st_.b_qkv = t->b_qkv; st_.w_o = t->w_o;
-    st_.la_q = t->lora_a_q; st_.la_v = t->lora_a_v; st_.lb_q = t->lora_b_q; st_.lb_v = t->lora_b_v;
-    st_.w1 = t->w1; st_.b1 = t->b1; st_.w2 = t->w2;
-    st_.H = s.H; st_.D = s.D; st_.Dm = s.Dm; st_.r = s.r;
-    st_.slice = (desc->flags & D2FT_FLAG_GATE_FFN) ? s.Dm / s.H : 0;
+    const size_t need = d2ft_scores_workspace_bytes(desc);
+    if (need == 0 || workspace_bytes < need) return D2FT_ESHAPE;
+    {
+        const void* ps[] = {t->w_qkv, t->b_qkv, t->w_o, t->lora_a_q, t->lora_a_v, t->lora_b_q, t->lora_b_v, t->w1, t->b1, t->w2};
+        for (const void* p : ps)
+            if (p && !aligned16(p)) return D2FT_EINVAL;
+    }
+    const ScoreArgs a = score_spans(desc, t);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     double* partial = static_cast<double*>(workspace);
-    double* out = partial + (size_t)s.H * kScoreChunks;
-    D2FT_TRY(launch_subnet_scores(s.dtype, st_, kind, partial, out, st));
-    if (hipMemcpyAsync(scores_out, out, (size_t)s.H * sizeof(double), hipMemcpyDeviceToHost, st) != hipSuccess)
+    double* out = partial + (size_t)desc->heads * score_spans(desc, nullptr).total_chunks;
+    if (a.n == 0) {
+        for (int h = 0; h < desc->heads; ++h) scores_out[h] = 0.0;
+        return D2FT_OK;
+    }
+    D2FT_TRY(launch_subnet_scores(desc->dtype, a, kind, partial, out, st));
+    if (hipMemcpyAsync(scores_out, out, (size_t)desc->heads * sizeof(double), hipMemcpyDeviceToHost, st) != hipSuccess)
         return D2FT_EDEVICE;
     if (hipStreamSynchronize(st) != hipSuccess) return D2FT_EDEVICE;
     return D2FT_OK;

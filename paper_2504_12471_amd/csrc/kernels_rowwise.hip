@@ -503,41 +503,31 @@ __global__ __launch_bounds__(256) void lora_grad_b_kernel(const float* __restric
     }
 
 // ---------------------------------------------------------------------------
-// contribution scores: blockIdx.y = head, blockIdx.x = chunk.  A chunk's threads stride over every
-// slice the head owns and add x*x (kind 0) or |x| (kind 1) in fp64; the workgroup's 256 sums are
-// added by a fixed tree, the chunks of a head in index order by score_final_kernel.
+// contribution scores: blockIdx.y = head, blockIdx.x = chunk of one span.  The chunk's threads stride
+// over the span in 16-byte (fp32: 32-byte) pieces and add x*x (kind 0) or |x| (kind 1) in fp64; the
+// workgroup's 256 sums are added by a fixed tree, the chunks of a head in index order by
+// score_final_kernel, so the result does not depend on timing.
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void score_partial_kernel(ScoreTensors t, int kind, double* __restrict__ partial) {
+__global__ __launch_bounds__(256) void score_partial_kernel(ScoreArgs a, int kind, double* __restrict__ partial) {
     __shared__ double red[256];
-    const int h = blockIdx.y;
-    const long tid = (long)blockIdx.x * 256 + threadIdx.x, nth = (long)gridDim.x * 256;
+    const int h = blockIdx.y, cidx = blockIdx.x;
+    int si = 0;
+    for (int i = 1; i < a.n; ++i)
+        if (cidx >= a.span[i].chunk0) si = i;
+    const ScoreSpan sp = a.span[si];
+    const T* base = static_cast<const T*>(sp.p) + sp.first + (long)h * sp.head_stride;
+    const int n8 = sp.rows * sp.cols8;
     double acc = 0.0;
-    // elements base[r * stride + c], r < rows, c < cols
-    auto span = [&](const void* p, long first, long rows, long cols, long stride) {
-        if (!p) return;
-        const T* base = static_cast<const T*>(p) + first;
-        for (long i = tid; i < rows * cols; i += nth) {
-            const double v = (double)ld<T>(base + (i / cols) * stride + (i % cols));
-            acc += kind == 0 ? v * v : fabs(v);
+    for (int i8 = (cidx - sp.chunk0) * 256 + threadIdx.x; i8 < n8; i8 += sp.nchunks * 256) {
+        const int r = i8 / sp.cols8, c8 = i8 - r * sp.cols8;
+        float v[8];
+        load8(base + (long)r * sp.stride + c8 * 8, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const double d = (double)v[j];
+            acc += kind == 0 ? d * d : fabs(d);
         }
-    };
-    const long D = t.D, H = t.H, r = t.r, S = t.slice;
-    for (int p = 0; p < 3; ++p) {
-        span(t.w_qkv, ((long)p * H + h) * 64 * D, 1, 64 * D, 64 * D);
-        span(t.b_qkv, ((long)p * H + h) * 64, 1, 64, 64);
-    }
-    span(t.w_o, (long)h * 64, D, 64, H * 64);
-    if (r > 0) {
-        span(t.la_q, (long)h * r * D, 1, r * D, r * D);
-        span(t.la_v, (long)h * r * D, 1, r * D, r * D);
-        span(t.lb_q, (long)h * 64 * r, 1, 64 * r, 64 * r);
-        span(t.lb_v, (long)h * 64 * r, 1, 64 * r, 64 * r);
-    }
-    if (S > 0) {
-        span(t.w1, (long)h * S * D, 1, S * D, S * D);
-        span(t.b1, (long)h * S, 1, S, S);
-        span(t.w2, (long)h * S, D, S, t.Dm);
     }
     red[threadIdx.x] = acc;
     __syncthreads();
@@ -545,7 +535,7 @@ __global__ __launch_bounds__(256) void score_partial_kernel(ScoreTensors t, int 
         if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
         __syncthreads();
     }
-    if (threadIdx.x == 0) partial[(long)h * gridDim.x + blockIdx.x] = red[0];
+    if (threadIdx.x == 0) partial[(long)h * a.total_chunks + cidx] = red[0];
 }
 
 __global__ void score_final_kernel(const double* __restrict__ partial, int chunks, int H, double* __restrict__ out) {
@@ -605,12 +595,12 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
     return hipGetLastError();
 }
 
-hipError_t launch_subnet_scores(int dtype, const ScoreTensors& t, int kind, double* partial, double* out, hipStream_t s) {
-    const dim3 grid(kScoreChunks, t.H), block(256);
-    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(score_partial_kernel<T>, grid, block, 0, s, t, kind, partial);)
+hipError_t launch_subnet_scores(int dtype, const ScoreArgs& a, int kind, double* partial, double* out, hipStream_t s) {
+    const dim3 grid(a.total_chunks, a.H), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(score_partial_kernel<T>, grid, block, 0, s, a, kind, partial);)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(score_final_kernel, dim3((t.H + 63) / 64), dim3(64), 0, s, partial, kScoreChunks, t.H, out);
+    hipLaunchKernelGGL(score_final_kernel, dim3((a.H + 63) / 64), dim3(64), 0, s, partial, a.total_chunks, a.H, out);
     return hipGetLastError();
 }
 

@@ -34,13 +34,18 @@ class BlockStack:
     """L blocks with their weights on the device, one saved buffer per block, one scratch buffer."""
 
     def __init__(self, desc: B.BlockDesc, weights: List[Dict[str, Optional[torch.Tensor]]], dtype: str,
-                 grad_fields: Optional[Sequence[str]] = None):
+                 grad_fields: Optional[Sequence[str]] = None, mb_images: Optional[Sequence[int]] = None):
+        """mb_images: images per micro-batch; when given, ops passed to forward/backward are
+        [L][n_micro][heads] and every block call goes through the micro-batch entry points."""
         self.desc = desc
+        self.mb_images = None if mb_images is None else [int(b) for b in mb_images]
         self.dtype = dtype
         self.weights = weights
         self.L = len(weights)
         tdt = torch_dtype(dtype)
-        sb, wb = B.d2ft_block_saved_bytes(desc), B.d2ft_block_scratch_bytes(desc)
+        sb = (B.d2ft_block_saved_bytes(desc) if self.mb_images is None
+              else B.d2ft_block_saved_bytes_mb(desc, self.mb_images))
+        wb = B.d2ft_block_scratch_bytes(desc)
         if sb == 0 or wb == 0:
             raise B.D2ftError(B.ESHAPE, "descriptor rejected")
         self.saved = [torch.empty(sb, dtype=torch.uint8, device="cuda") for _ in range(self.L)]
@@ -57,16 +62,24 @@ class BlockStack:
     def forward(self, x: torch.Tensor, ops: np.ndarray, stream=None) -> torch.Tensor:
         self.acts[0] = x
         for l in range(self.L):
-            B.d2ft_block_fwd(self.desc, self.weights[l], ops[l], self.acts[l], self.acts[l + 1], self.saved[l],
-                             self.scratch, stream)
+            if self.mb_images is None:
+                B.d2ft_block_fwd(self.desc, self.weights[l], ops[l], self.acts[l], self.acts[l + 1], self.saved[l],
+                                 self.scratch, stream)
+            else:
+                B.d2ft_block_fwd_mb(self.desc, self.weights[l], self.mb_images, ops[l], self.acts[l], self.acts[l + 1],
+                                    self.saved[l], self.scratch, stream)
         return self.acts[self.L]
 
     def backward(self, dy: torch.Tensor, ops: np.ndarray, stream=None) -> torch.Tensor:
         cur = dy
         for l in range(self.L - 1, -1, -1):
             out = self.dacts[l & 1]
-            B.d2ft_block_bwd(self.desc, self.weights[l], ops[l], self.acts[l], cur, out, self.grads[l],
-                             self.saved[l], self.scratch, stream)
+            if self.mb_images is None:
+                B.d2ft_block_bwd(self.desc, self.weights[l], ops[l], self.acts[l], cur, out, self.grads[l],
+                                 self.saved[l], self.scratch, stream)
+            else:
+                B.d2ft_block_bwd_mb(self.desc, self.weights[l], self.mb_images, ops[l], self.acts[l], cur, out,
+                                    self.grads[l], self.saved[l], self.scratch, stream)
             cur = out
         return cur
 

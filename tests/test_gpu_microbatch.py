@@ -1,0 +1,96 @@
+"""GPU parity for d2ft_block_fwd_mb / d2ft_block_bwd_mb: one op code per (subnet, micro-batch)
+(Alg. 1, T_opt[k][x_i]), weight gradients added over the micro-batches, against the oracle."""
+import numpy as np
+import pytest
+
+import d2ft_inputs as di
+from helpers import FLAG_GATE_FFN, TOL, rel_inf
+
+pytestmark = pytest.mark.gpu
+
+FULL, FWD, SKIP = di.OP_FULL, di.OP_FWD, di.OP_SKIP
+
+
+def gpu_block_mb(w, weights, ops_mb, mb, x, dy, flags=0, grads_init=None):
+    import torch
+    import paper_2504_12471_amd as P
+    desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype, w.lora_rank, w.lora_scale,
+                       w.ln_eps, w.head_dim, flags)
+    dw = {k: P.to_device(v, w.dtype) for k, v in weights.items()}
+    xd, dyd = P.to_device(x, w.dtype), P.to_device(dy, w.dtype)
+    y, dx = torch.empty_like(xd), torch.empty_like(xd)
+    saved = torch.empty(P.d2ft_block_saved_bytes_mb(desc, mb), dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(P.d2ft_block_scratch_bytes(desc), dtype=torch.uint8, device="cuda")
+    grads = {k: (None if v is None else (torch.full_like(v, float("nan")) if grads_init is None
+                                         else P.to_device(grads_init[k], w.dtype))) for k, v in dw.items()}
+    P.d2ft_block_fwd_mb(desc, dw, mb, ops_mb, xd, y, saved, scratch)
+    P.d2ft_block_bwd_mb(desc, dw, mb, ops_mb, xd, dyd, dx, grads, saved, scratch)
+    torch.cuda.synchronize()
+    host = lambda t: None if t is None else t.float().cpu().numpy()
+    return host(y), host(dx), {k: host(v) for k, v in grads.items()}
+
+
+def run_mb(w, ops_mb, mb, seed, gate=False):
+    from oracle import d2ft_oracle as orc
+    rng = np.random.default_rng(seed)
+    x, wt, dy = di.draw_hidden(rng, w), di.draw_block_weights(rng, w), di.draw_hidden(rng, w)
+    y, dx, g = gpu_block_mb(w, wt, ops_mb, mb, x, dy, FLAG_GATE_FFN if gate else 0)
+    ry, caches = orc.block_fwd_mb(wt, ops_mb, mb, x, w.head_dim, w.ln_eps, w.lora_scale, gate_ffn=gate)
+    rdx, rg = orc.block_bwd_mb(wt, caches, mb, dy)
+    tol = TOL[w.dtype]
+    errs = {"y": rel_inf(y, ry), "dx": rel_inf(dx, rdx)}
+    for k, v in g.items():
+        if v is not None:
+            assert np.all(np.isfinite(v)), k
+            errs["d" + k] = rel_inf(v, rg[k])
+    print(f"[mb {w.name} mb={mb} gate={gate}] " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()), flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, bad
+    # a subnet that is p_f in no micro-batch: exact +0.0
+    dh = w.head_dim
+    for h in range(w.heads):
+        if all(ops[h] != FULL for ops in ops_mb):
+            for s in (g["w_qkv"][:, h], g["b_qkv"][:, h], g["w_o"][:, h * dh:(h + 1) * dh]):
+                assert np.all(s == 0.0) and not np.any(np.signbit(s))
+    return g, rg
+
+
+def test_fp32_three_micro_batches():
+    w = di.scaled(di.WORKLOADS["vit_tiny_fp32"], batch=6)
+    run_mb(w, [[FULL, FWD, SKIP], [SKIP, FULL, SKIP], [FWD, FWD, SKIP]], [1, 3, 2], seed=71)
+
+
+def test_fp32_gated_micro_batches():
+    w = di.scaled(di.WORKLOADS["vit_tiny_fp32"], batch=5)
+    run_mb(w, [[FULL, SKIP, SKIP], [SKIP, SKIP, SKIP], [FWD, FULL, SKIP]], [2, 1, 2], seed=72, gate=True)
+
+
+def test_single_micro_batch_equals_plain_call_bitwise():
+    from helpers import gpu_block
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    rng = np.random.default_rng(73)
+    x, wt, dy = di.draw_hidden(rng, w), di.draw_block_weights(rng, w), di.draw_hidden(rng, w)
+    ops = [FULL, FWD, SKIP]
+    a = gpu_block_mb(w, wt, [ops], [w.batch], x, dy)
+    b = gpu_block(w, wt, ops, x, dy)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    for k in a[2]:
+        if a[2][k] is not None:
+            assert np.array_equal(a[2][k], b[2][k]), k
+
+
+def test_bf16_five_micro_batches():
+    w = di.Workload("mb_bf16", 10, 197, 384, 6, 64, 1536, 1, "bf16")
+    rng = np.random.default_rng(74)
+    ops_mb = [list(rng.choice([FULL, FULL, FULL, FWD, SKIP], size=w.heads)) for _ in range(5)]
+    run_mb(w, ops_mb, [2, 2, 2, 2, 2], seed=75)
+    run_mb(w, ops_mb, [3, 1, 2, 2, 2], seed=76, gate=True)
+
+
+def test_bad_micro_batch_sizes_are_rejected():
+    import paper_2504_12471_amd as P
+    w = di.WORKLOADS["vit_tiny_fp32"]
+    desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype)
+    assert P.d2ft_block_saved_bytes_mb(desc, [1, 1]) == 0          # does not add up to the batch
+    assert P.d2ft_block_saved_bytes_mb(desc, [4, 0]) == 0
+    assert P.d2ft_block_saved_bytes_mb(desc, [2, 2]) > 0
