@@ -76,7 +76,7 @@ SavedLayout saved_layout(const Dims& s) {
     L.mean2 = take(s.M * 4);
     L.rstd2 = take(s.M * 4);
     L.v = take(s.M * s.D * s.es);
-    L.z = take(s.M * s.Dm * s.es);
+    L.z = take(s.M * s.Dm * s.es);   // GELU'(z) of the hidden units in use (what the backward needs of z)
     L.g = take(s.M * s.Dm * s.es);
     L.total = off;
     return L;

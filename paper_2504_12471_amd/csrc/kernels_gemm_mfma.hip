@@ -141,7 +141,9 @@ __device__ __forceinline__ bf16x8 read_fragment(const bf16* lds, int i_base, int
 // exponential and a polynomial).  Here Phi(z) = 0.5 + z * Q(z^2) with Q a degree-8 polynomial fitted
 // on |z| <= 4 (Chebyshev fit of (Phi(z) - 0.5) / z; max absolute error 3.3e-5 including the clamp
 // of |z| to 4), i.e. more than an order of magnitude below bf16 resolution: 11 FMA-class
-// instructions and no transcendental.  The density for the derivative keeps its one exponential.
+// instructions and no transcendental.  The forward epilogue also evaluates GELU'(z) = Phi(z) + z phi(z)
+// (one exponential for the density) and saves it in place of z, so the backward epilogue is one
+// multiplication per element.
 __device__ __forceinline__ float phi_poly(float z) {
     const float zc = fminf(fmaxf(z, -4.0f), 4.0f);
     const float u = zc * zc;
@@ -155,11 +157,6 @@ __device__ __forceinline__ float phi_poly(float z) {
     q = fmaf(q, u, -6.646679917e-02f);
     q = fmaf(q, u, 3.989401704e-01f);
     return fmaf(zc, q, 0.5f);
-}
-__device__ __forceinline__ float gelu_fast(float z) { return z * phi_poly(z); }
-__device__ __forceinline__ float gelu_grad_fast(float z) {
-    const float e = __builtin_amdgcn_exp2f(-0.72134752044448170368f * z * z);   // exp(-z^2/2)
-    return fmaf(z * 0.39894228040143267794f, e, phi_poly(z));
 }
 
 // ---- issue order of one MFMA group ----
@@ -423,15 +420,21 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                         for (int i = 0; i < 8; ++i) v[i] += b[i];
                     }
                     if (g.act == ACT_GELU) {
-                        bf16* zp = Z + (long)m * g.ldz + n;
-                        store8(zp, v);
+                        // Z <- GELU'(z), C <- GELU(z), both of the pre-activation rounded to bf16
+                        float gp[8];
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) v[i] = gelu_fast(static_cast<float>(static_cast<bf16>(v[i])));
+                        for (int i = 0; i < 8; ++i) {
+                            const float zr = static_cast<float>(static_cast<bf16>(v[i]));
+                            const float ph = phi_poly(zr);
+                            gp[i] = fmaf(zr * 0.39894228040143267794f, __builtin_amdgcn_exp2f(-0.72134752044448170368f * zr * zr), ph);
+                            v[i] = zr * ph;
+                        }
+                        store8(Z + (long)m * g.ldz + n, gp);
                     } else if (g.act == ACT_DGELU) {
-                        float z[8];
-                        load8(Z + (long)m * g.ldz + n, z);
+                        float gp[8];
+                        load8(Z + (long)m * g.ldz + n, gp);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast(z[i]);
+                        for (int i = 0; i < 8; ++i) v[i] *= gp[i];
                     }
                     if (R) {
                         float rr[8];

@@ -118,12 +118,13 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmArgs g) {
             float v = acc[i][j];
             if (bias) v += ld<T>(bias + (g.bias_remap ? g.tbl(n) : n));
             if (g.act == ACT_GELU) {
-                st<T>(Z + (long)m * g.ldz + n, v);
-                // the saved pre-activation is what the backward pass differentiates, so the
-                // activation is taken of the stored (rounded) value
-                v = gelu_f(ld<T>(Z + (long)m * g.ldz + n));
+                // the activation and its derivative are both taken of the pre-activation rounded to the
+                // storage type; the derivative is what the backward pass needs, so that is what is saved
+                const float zr = static_cast<float>(static_cast<T>(v));
+                st<T>(Z + (long)m * g.ldz + n, gelu_grad_f(zr));
+                v = gelu_f(zr);
             } else if (g.act == ACT_DGELU) {
-                v *= gelu_grad_f(ld<T>(Z + (long)m * g.ldz + n));
+                v *= ld<T>(Z + (long)m * g.ldz + n);
             }
             if (R) v += ld<T>(R + (long)m * g.ldr + n);
             st<T>(C + (long)m * g.ldc + n, v);
