@@ -105,7 +105,7 @@ struct GemmArgs {
     const void* bias;     // [N] or null
     const void* residual; // [M][ldr] or null, added in the epilogue
     long ldr;
-    int act;              // ACT_GELU: Z <- gelu'(z), C <- gelu(z), z = the rounded pre-activation; ACT_DGELU: C <- acc * Z
+    int act;              // ACT_GELU: Z <- gelu'(z), C <- gelu(z), z = the fp32 pre-activation; ACT_DGELU: C <- acc * Z
     void* Z;
     long ldz;
     float* partial;       // non-null: split-K mode, raw fp32 sums go to partial[split][M][N]

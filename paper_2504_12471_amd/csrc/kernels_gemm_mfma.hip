@@ -391,6 +391,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     const bf16* R = static_cast<const bf16*>(g.residual);
     bf16* Z = static_cast<bf16*>(g.Z);
     float* P = g.partial ? g.partial + (long)esplit * g.M * g.N : nullptr;
+    // a lane reads back the same 8 columns in every chunk (64 is a multiple of the chunks per row),
+    // so its bias values are fetched once per tile
+    static_assert(64 % CPR == 0, "a lane keeps its columns over the chunks of a band");
+    u32x4 braw = {0u, 0u, 0u, 0u};
+    {
+        const int nb = en0 + wn * WTN + (lane % CPR) * 8;
+        if (!P && bias && nb < g.N) braw = *reinterpret_cast<const u32x4*>(bias + (g.bias_remap ? g.tbl(nb) : nb));
+    }
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
 #pragma unroll
@@ -414,17 +422,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                     store8(P + (long)m * g.N + n, v);
                 } else {
                     if (bias) {
-                        float b[8];
-                        load8(bias + (g.bias_remap ? g.tbl(n) : n), b);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) v[i] += b[i];
+                        for (int i = 0; i < 4; ++i) {
+                            v[2 * i] += __uint_as_float(braw[i] << 16);
+                            v[2 * i + 1] += __uint_as_float(braw[i] & 0xffff0000u);
+                        }
                     }
                     if (g.act == ACT_GELU) {
-                        // Z <- GELU'(z), C <- GELU(z), both of the pre-activation rounded to bf16
+                        // Z <- GELU'(z), C <- GELU(z), both of the fp32 pre-activation
                         float gp[8];
 #pragma unroll
                         for (int i = 0; i < 8; ++i) {
-                            const float zr = static_cast<float>(static_cast<bf16>(v[i]));
+                            const float zr = v[i];
                             const float ph = phi_poly(zr);
                             gp[i] = fmaf(zr * 0.39894228040143267794f, __builtin_amdgcn_exp2f(-0.72134752044448170368f * zr * zr), ph);
                             v[i] = zr * ph;

@@ -118,9 +118,9 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(GemmArgs g) {
             float v = acc[i][j];
             if (bias) v += ld<T>(bias + (g.bias_remap ? g.tbl(n) : n));
             if (g.act == ACT_GELU) {
-                // the activation and its derivative are both taken of the pre-activation rounded to the
-                // storage type; the derivative is what the backward pass needs, so that is what is saved
-                const float zr = static_cast<float>(static_cast<T>(v));
+                // the activation and its derivative are both taken of the fp32 pre-activation; the
+                // derivative is what the backward pass needs, so that is what is saved
+                const float zr = v;
                 st<T>(Z + (long)m * g.ldz + n, gelu_grad_f(zr));
                 v = gelu_f(zr);
             } else if (g.act == ACT_DGELU) {
