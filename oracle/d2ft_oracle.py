@@ -44,6 +44,12 @@ design notes of the repository):
     (Alg. 1, T_opt[k][x_i]); a block call over several micro-batches applies
     each micro-batch's codes to its own images, and a weight gradient is the
     sum of the micro-batches' gradients (gradient accumulation).
+  * The optimizer is SGD with momentum (Sec. IV-A names it and gives no
+    hyper-parameters): v <- mu*v + (g + wd*w), w <- w - lr*v, the common
+    formulation without dampening or Nesterov look-ahead.  Slices that belong to
+    a subnet that was not p_f in the step are left untouched, momentum included
+    (a device that skipped its subnet does no work on it); tensors shared by all
+    subnets are always updated.
   * In DPSearching the item weight tested and subtracted in the fill phase is
     the operation's own weight (W_p), as the backtracking phase uses; the
     backtracking index decrements by one.
@@ -394,6 +400,51 @@ def subnet_scores(t: Dict[str, Optional[np.ndarray]], heads: int, head_dim: int,
                 parts.append(t["w2"][:, h * S:(h + 1) * S])
         out[h] = sum(f(a) for a in parts)
     return out
+
+
+# ----------------------------------------------------------------------------
+# SGD with momentum on the slices of the p_f subnets (Sec. IV-A: "SGD optimizer with momentum")
+# ----------------------------------------------------------------------------
+def _head_slices(name: str, a: np.ndarray, h: int, heads: int, head_dim: int, gate_ffn: bool):
+    """Index expression of head h's slice of tensor `name`, or None if the tensor is shared by all heads."""
+    if name in ("w_qkv", "b_qkv"):
+        return (slice(None), h)
+    if name == "w_o":
+        return (slice(None), slice(h * head_dim, (h + 1) * head_dim))
+    if name.startswith("lora_"):
+        return (h,)
+    if gate_ffn and name in ("w1", "b1"):
+        S = a.shape[0] // heads
+        return (slice(h * S, (h + 1) * S),)
+    if gate_ffn and name == "w2":
+        S = a.shape[1] // heads
+        return (slice(None), slice(h * S, (h + 1) * S))
+    return None
+
+
+def sgd_momentum_step(w: Dict[str, Optional[np.ndarray]], g: Dict[str, Optional[np.ndarray]],
+                      v: Dict[str, Optional[np.ndarray]], updated: Sequence[bool], head_dim: int,
+                      lr: float, momentum: float, weight_decay: float = 0.0, gate_ffn: bool = False):
+    """One optimizer step.  w, g, v: weights, gradients, momentum buffers in the weight layout
+    (fields that are None in g are not trained).  updated[h]: subnet h was p_f in this step.
+    Returns (w_new, v_new) as new float64 dicts; slices of subnets with updated[h] False are copied."""
+    heads = len(updated)
+    w_new = {k: (None if a is None else np.array(a, dtype=np.float64)) for k, a in w.items()}
+    v_new = {k: (None if a is None else np.array(a, dtype=np.float64)) for k, a in v.items()}
+    for k, grad in g.items():
+        if grad is None or w.get(k) is None:
+            continue
+        grad = _f64(grad)
+        regions = []
+        if _head_slices(k, grad, 0, heads, head_dim, gate_ffn) is None:
+            regions.append((slice(None),))
+        else:
+            regions = [_head_slices(k, grad, h, heads, head_dim, gate_ffn) for h in range(heads) if updated[h]]
+        for r in regions:
+            vv = momentum * v_new[k][r] + (grad[r] + weight_decay * w_new[k][r])
+            v_new[k][r] = vv
+            w_new[k][r] = w_new[k][r] - lr * vv
+    return w_new, v_new
 
 
 # ----------------------------------------------------------------------------
