@@ -169,6 +169,31 @@ def main() -> int:
     head_bytes = sum(t.numel() * t.element_size() for k, t in stack.grads[0].items()
                      if t is not None and (k in ("w_qkv", "b_qkv", "w_o") or k.startswith("lora")
                                            or (w.gate_ffn and k in ("w1", "b1", "w2"))))
+    # optimizer step (Sec. IV-A: SGD with momentum) on every block, slices of the p_f subnets only
+    mom = [{k: (None if t is None else torch.zeros(t.shape, dtype=torch.float32, device="cuda"))
+            for k, t in stack.grads[l].items()} for l in range(w.blocks)]
+    step_ops = ops if mb_images is None else np.where((ops == di.OP_FULL).any(axis=1), di.OP_FULL, di.OP_SKIP)
+    P.d2ft_timing_enable(True)
+    for l in range(w.blocks):
+        P.d2ft_sgd_step(desc, dws[l], stack.grads[l], mom[l], None, step_ops[l], 0.0, 0.9, 0.0)   # lr 0: weights keep their values
+    torch.cuda.synchronize()
+    sg = [k for k in P.d2ft_timing_read(8) if "sgd" in k["name"]]
+    P.d2ft_timing_enable(False)
+    sgd = None
+    if sg:
+        es = 2 if w.dtype == "bf16" else 4
+        elems = 0
+        for l in range(w.blocks):
+            for k, t in stack.grads[l].items():
+                if t is None:
+                    continue
+                per_head = k in ("w_qkv", "b_qkv", "w_o") or k.startswith("lora") or (w.gate_ffn and k in ("w1", "b1", "w2"))
+                frac = float((step_ops[l] == di.OP_FULL).mean()) if per_head else 1.0
+                elems += t.numel() * frac
+        sgd_ms = sum(k["ms"] for k in sg)
+        sgd = {"ms_per_step": round(sgd_ms, 4), "bytes_per_step": int(elems * (3 * es + 8)),
+               "GB_per_s": round(elems * (3 * es + 8) / (sgd_ms * 1e-3) / 1e9, 1)}
+    del mom
     scores = None
     if sc:
         us = sc[0]["ms"] / sc[0]["launches"] * 1e3
@@ -213,6 +238,7 @@ def main() -> int:
         "kernel_ms_per_step_sum": round(total_kernel_ms, 4),
         "roofline": roofline,
         "subnet_scores": scores,
+        "sgd_step": sgd,
         "kernels": kernels[:12],
     }
 

@@ -235,6 +235,33 @@ size_t d2ft_scores_workspace_bytes(const d2ft_block_desc *desc);
 d2ft_status d2ft_subnet_scores(const d2ft_block_desc *desc, const d2ft_block_weights *tensors, int32_t kind,
                                double *scores_out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* One optimizer step on a block: SGD with momentum, the optimizer Sec. IV-A names ("Computational
+ * cost analysis"; the paper gives no hyper-parameters), in the common form without dampening or
+ * Nesterov look-ahead, per element
+ *     v <- momentum * v + (g + weight_decay * w),     w <- w - lr * v.
+ * The slices that belong to one subnet alone (Q/K/V rows and biases, W_o columns, LoRA adapters and,
+ * with D2FT_FLAG_GATE_FFN, the feed-forward slice) are updated for the heads whose code in `ops`
+ * is p_f and left untouched - weights, momentum and master copy - for the others: a subnet that
+ * ran p_o or p_s in the step has no gradient and does no optimizer work.  Tensors shared by all
+ * subnets (LayerNorm parameters, b_o, b2, and the whole feed-forward network without the flag) are
+ * always updated.  A tensor takes part only if its pointers in `weights`, `grads` and `momentum`
+ * are all non-NULL.  Arithmetic is fp32.
+ *   weights   HOST struct of DEVICE pointers, storage dtype of desc, updated in place
+ *   grads     same layout and dtype, read only
+ *   momentum  same layout, fp32 buffers, updated in place
+ *   master    NULL, or a struct of fp32 copies of the weights: where a field is non-NULL the update
+ *             is applied to the fp32 copy and `weights` receives its rounded value
+ *   ops       HOST [heads]
+ * Errors: D2FT_EINVAL for NULL desc / weights / grads / momentum / ops / params, a code outside
+ * {1,2,3}, a misaligned pointer or non-finite hyper-parameters. */
+typedef struct d2ft_sgd_params {
+    float lr, momentum, weight_decay;
+} d2ft_sgd_params;
+d2ft_status d2ft_sgd_step(const d2ft_block_desc *desc, const d2ft_block_grads *weights,
+                          const d2ft_block_weights *grads, const d2ft_block_grads *momentum,
+                          const d2ft_block_grads *master, const uint8_t *ops,
+                          const d2ft_sgd_params *params, void *hip_stream);
+
 /* Diagnostics: per-kernel timing.  While enabled, every kernel launch the library makes is
  * bracketed by a pair of HIP events on the stream of the call (this adds host work per launch:
  * do not time whole steps while it is on).  d2ft_timing_enable(1) clears earlier records and

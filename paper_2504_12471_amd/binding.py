@@ -86,6 +86,15 @@ _lib.d2ft_subnet_scores.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.c_
 SCORE_FISHER, SCORE_MAGNITUDE = 0, 1
 
 
+class SgdParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+
+
+_lib.d2ft_sgd_step.restype = C.c_int
+_lib.d2ft_sgd_step.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.POINTER(_Ptrs), C.POINTER(_Ptrs),
+                               C.POINTER(_Ptrs), C.c_void_p, C.POINTER(SgdParams), C.c_void_p]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -263,9 +272,23 @@ def d2ft_subnet_scores(desc: BlockDesc, tensors: Dict[str, Optional[torch.Tensor
     return out
 
 
+def d2ft_sgd_step(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], grads: Dict[str, Optional[torch.Tensor]],
+                  momentum: Dict[str, Optional[torch.Tensor]], master: Optional[Dict[str, Optional[torch.Tensor]]],
+                  ops: Sequence[int], lr: float, mu: float, weight_decay: float = 0.0,
+                  stream: Optional[torch.cuda.Stream] = None) -> None:
+    """SGD with momentum on the slices of the p_f heads (and on the shared tensors), in place."""
+    a = _ops_array(ops)
+    w, g, v = _ptr_struct(weights), _ptr_struct(grads), _ptr_struct(momentum)
+    m = None if master is None else _ptr_struct(master)
+    prm = SgdParams(lr, mu, weight_decay)
+    st = _lib.d2ft_sgd_step(C.byref(desc), C.byref(w), C.byref(g), C.byref(v), None if m is None else C.byref(m),
+                            a.ctypes.data, C.byref(prm), _stream_ptr(stream))
+    _check(st, "d2ft_sgd_step")
+
+
 def exported_symbols():
     """Names this binding resolves in the shared library (used by the load test)."""
     return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
             "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_block_saved_bytes_mb", "d2ft_block_fwd_mb", "d2ft_block_bwd_mb",
             "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
-            "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_timing_enable", "d2ft_timing_read"]
+            "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_sgd_step", "d2ft_timing_enable", "d2ft_timing_read"]

@@ -182,6 +182,25 @@ hipError_t launch_zero_head_slices(int dtype, const HeadList& heads, int H, int 
 hipError_t launch_zero_ffn_slices(int dtype, const HeadList& heads, int slice, int D, int Dm, void* g_w1, void* g_b1,
                                   void* g_w2, hipStream_t s);
 
+// SGD with momentum over spans of tensors: for list entry y (blockIdx.y) the elements
+// first + heads.h[y]*head_stride + r*stride + c, r < rows, c < 8*cols8, of w (storage dtype), g (storage
+// dtype), v (fp32) and, if non-NULL, master (fp32)
+struct SgdSpan {
+    void* w;
+    const void* g;
+    float* v;
+    float* master;
+    long first, head_stride, stride;
+    int rows, cols8, chunk0, nchunks;
+};
+struct SgdArgs {
+    SgdSpan span[16];
+    int n, total_chunks;
+    float lr, momentum, weight_decay;
+};
+hipError_t launch_sgd(int dtype, const SgdArgs& a, const HeadList& heads, hipStream_t s);
+
+
 // W_eff rows for compacted heads: out[(j*3+p)*64 + d][:] = W[p][live[j]][d][:] (+ s * B A for p in {query, value})
 hipError_t launch_lora_merge(int dtype, const void* w_qkv, const void* la_q, const void* la_v, const void* lb_q,
                              const void* lb_v, void* out, const HeadList& live, int n_heads_used, int H, int D, int r,

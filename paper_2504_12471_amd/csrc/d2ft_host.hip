@@ -915,6 +915,74 @@ d2ft_status d2ft_subnet_scores(const d2ft_block_desc* desc, const d2ft_block_wei
     return D2FT_OK;
 }
 
+d2ft_status d2ft_sgd_step(const d2ft_block_desc* desc, const d2ft_block_grads* w, const d2ft_block_weights* g,
+                          const d2ft_block_grads* v, const d2ft_block_grads* master, const uint8_t* ops,
+                          const d2ft_sgd_params* prm, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!w || !g || !v || !ops || !prm) return D2FT_EINVAL;
+    if (!isfinite(prm->lr) || !isfinite(prm->momentum) || !isfinite(prm->weight_decay)) return D2FT_EINVAL;
+    const Dims s = dims_of(desc);
+    HeadList upd, one;
+    upd.n = 0;
+    one.n = 1; one.h[0] = 0;
+    for (int h = 0; h < s.H; ++h) {
+        if (ops[h] < D2FT_OP_FULL || ops[h] > D2FT_OP_SKIP) return D2FT_EINVAL;
+        if (ops[h] == D2FT_OP_FULL) upd.h[upd.n++] = (uint8_t)h;
+    }
+    const long D = s.D, H = s.H, r = s.r, Dm = s.Dm;
+    const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
+    const long S = gate ? Dm / H : 0;
+    SgdArgs per_head, shared;
+    memset(&per_head, 0, sizeof(per_head));
+    memset(&shared, 0, sizeof(shared));
+    per_head.lr = shared.lr = prm->lr;
+    per_head.momentum = shared.momentum = prm->momentum;
+    per_head.weight_decay = shared.weight_decay = prm->weight_decay;
+    bool bad = false;
+    auto add = [&](SgdArgs& a, void* wp, const void* gp, void* vp, void* mp, long first, long head_stride, long rows,
+                   long cols, long stride) {
+        if (!wp || !gp || !vp) return;
+        if (!aligned16(wp) || !aligned16(gp) || !aligned16(vp) || (mp && !aligned16(mp))) { bad = true; return; }
+        SgdSpan& sp = a.span[a.n++];
+        sp.w = wp; sp.g = gp; sp.v = static_cast<float*>(vp); sp.master = static_cast<float*>(mp);
+        sp.first = first; sp.head_stride = head_stride; sp.stride = stride;
+        sp.rows = (int)rows; sp.cols8 = (int)(cols / 8);
+        long n = (rows * cols / 8 + 511) / 512;   // about two 8-element pieces per thread
+        sp.nchunks = (int)(n < 1 ? 1 : (n > 256 ? 256 : n));
+        sp.chunk0 = a.total_chunks;
+        a.total_chunks += sp.nchunks;
+    };
+#define D2FT_M(f) (master ? master->f : nullptr)
+    for (long p = 0; p < 3; ++p) {
+        add(per_head, w->w_qkv, g->w_qkv, v->w_qkv, D2FT_M(w_qkv), p * H * 64 * D, 64 * D, 1, 64 * D, 64 * D);
+        add(per_head, w->b_qkv, g->b_qkv, v->b_qkv, D2FT_M(b_qkv), p * H * 64, 64, 1, 64, 64);
+    }
+    add(per_head, w->w_o, g->w_o, v->w_o, D2FT_M(w_o), 0, 64, D, 64, H * 64);
+    if (r > 0) {
+        add(per_head, w->lora_a_q, g->lora_a_q, v->lora_a_q, D2FT_M(lora_a_q), 0, r * D, 1, r * D, r * D);
+        add(per_head, w->lora_a_v, g->lora_a_v, v->lora_a_v, D2FT_M(lora_a_v), 0, r * D, 1, r * D, r * D);
+        add(per_head, w->lora_b_q, g->lora_b_q, v->lora_b_q, D2FT_M(lora_b_q), 0, 64 * r, 1, 64 * r, 64 * r);
+        add(per_head, w->lora_b_v, g->lora_b_v, v->lora_b_v, D2FT_M(lora_b_v), 0, 64 * r, 1, 64 * r, 64 * r);
+    }
+    SgdArgs& ffn = gate ? per_head : shared;
+    add(ffn, w->w1, g->w1, v->w1, D2FT_M(w1), 0, gate ? S * D : 0, 1, gate ? S * D : Dm * D, gate ? S * D : Dm * D);
+    add(ffn, w->b1, g->b1, v->b1, D2FT_M(b1), 0, gate ? S : 0, 1, gate ? S : Dm, gate ? S : Dm);
+    add(ffn, w->w2, g->w2, v->w2, D2FT_M(w2), 0, gate ? S : 0, gate ? D : 1, gate ? S : D * Dm, gate ? Dm : D * Dm);
+    add(shared, w->ln1_g, g->ln1_g, v->ln1_g, D2FT_M(ln1_g), 0, 0, 1, D, D);
+    add(shared, w->ln1_b, g->ln1_b, v->ln1_b, D2FT_M(ln1_b), 0, 0, 1, D, D);
+    add(shared, w->b_o, g->b_o, v->b_o, D2FT_M(b_o), 0, 0, 1, D, D);
+    add(shared, w->ln2_g, g->ln2_g, v->ln2_g, D2FT_M(ln2_g), 0, 0, 1, D, D);
+    add(shared, w->ln2_b, g->ln2_b, v->ln2_b, D2FT_M(ln2_b), 0, 0, 1, D, D);
+    add(shared, w->b2, g->b2, v->b2, D2FT_M(b2), 0, 0, 1, D, D);
+#undef D2FT_M
+    if (bad) return D2FT_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    D2FT_TRY(launch_sgd(s.dtype, per_head, upd, st));
+    D2FT_TRY(launch_sgd(s.dtype, shared, one, st));
+    return D2FT_OK;
+}
+
 size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const int32_t* cap_full,
                                      const int32_t* cap_fwd) {
     if (n_knapsacks < 1 || n_items < 1 || !cap_full || !cap_fwd) return 0;

@@ -546,6 +546,39 @@ __global__ void score_final_kernel(const double* __restrict__ partial, int chunk
     out[h] = s;
 }
 
+// ---------------------------------------------------------------------------
+// SGD with momentum: blockIdx.y = entry of the head list, blockIdx.x = chunk of one span; 8 elements per
+// thread and step.  v <- mu*v + (g + wd*w), w <- w - lr*v in fp32; with a master copy the update is
+// applied to it and the storage-type weight receives its rounded value.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void sgd_momentum_kernel(SgdArgs a, HeadList heads) {
+    const int cidx = blockIdx.x;
+    int si = 0;
+    for (int i = 1; i < a.n; ++i)
+        if (cidx >= a.span[i].chunk0) si = i;
+    const SgdSpan sp = a.span[si];
+    const long base = sp.first + (long)heads.h[blockIdx.y] * sp.head_stride;
+    const int n8 = sp.rows * sp.cols8;
+    for (int i8 = (cidx - sp.chunk0) * 256 + threadIdx.x; i8 < n8; i8 += sp.nchunks * 256) {
+        const int r = i8 / sp.cols8, c8 = i8 - r * sp.cols8;
+        const long off = base + (long)r * sp.stride + c8 * 8;
+        float w[8], g[8], v[8];
+        T* wp = static_cast<T*>(sp.w) + off;
+        if (sp.master) load8(sp.master + off, w); else load8(wp, w);
+        load8(static_cast<const T*>(sp.g) + off, g);
+        load8(sp.v + off, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v[j] = a.momentum * v[j] + (g[j] + a.weight_decay * w[j]);
+            w[j] = w[j] - a.lr * v[j];
+        }
+        store8(sp.v + off, v);
+        if (sp.master) store8(sp.master + off, w);
+        store8(wp, w);
+    }
+}
+
 hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean,
                          float* rstd, int rows, int width, float eps, hipStream_t s) {
     const dim3 grid((rows + 3) / 4), block(256);
@@ -601,6 +634,13 @@ hipError_t launch_subnet_scores(int dtype, const ScoreArgs& a, int kind, double*
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(score_final_kernel, dim3((a.H + 63) / 64), dim3(64), 0, s, partial, a.total_chunks, a.H, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_sgd(int dtype, const SgdArgs& a, const HeadList& heads, hipStream_t s) {
+    if (a.n <= 0 || heads.n <= 0) return hipSuccess;
+    const dim3 grid(a.total_chunks, heads.n), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(sgd_momentum_kernel<T>, grid, block, 0, s, a, heads);)
     return hipGetLastError();
 }
 
