@@ -169,3 +169,37 @@ def test_small_stack_against_oracle():
     for l in range(w.blocks):
         for k in ("w_qkv", "w_o", "w1", "w2", "b1"):
             assert rel_inf(st.grads[l][k].float().cpu().numpy(), rgrads[l][k]) < 2e-2, (l, k)
+
+
+# ---------------------------------------------------------------------------
+# limits of the supported shapes
+# ---------------------------------------------------------------------------
+def test_bf16_tokens_beyond_the_matrix_core_attention_limit():
+    """More than 256 tokens: the bf16 block takes the vector-ALU attention kernels, GEMMs stay on the matrix cores."""
+    w = di.Workload("long_bf16", 1, 300, 128, 2, 64, 256, 1, "bf16")
+    run_case(w, [FULL, FWD], seed=14)
+
+
+def test_bf16_exactly_256_tokens_and_one_token_tail():
+    run_case(di.Workload("t256_bf16", 2, 256, 128, 2, 64, 256, 1, "bf16"), [FULL, FULL], seed=15)
+    run_case(di.Workload("t225_bf16", 2, 225, 128, 2, 64, 256, 1, "bf16"), [FULL, SKIP], seed=16)   # 7 tiles + 1 token
+
+
+def test_maximum_head_count():
+    w = di.Workload("h64_f32", 1, 9, 64, 64, 64, 64, 1, "f32")
+    rng = np.random.default_rng(17)
+    ops = list(rng.choice([FULL, FWD, SKIP], size=64))
+    run_case(w, ops, seed=17)
+    wb = di.Workload("h64_bf16", 1, 40, 64, 64, 64, 64, 1, "bf16")
+    run_case(wb, ops, seed=18)
+
+
+def test_unsupported_shapes_are_rejected_without_a_launch():
+    import paper_2504_12471_amd as P
+    for kw in (dict(batch=0), dict(tokens=0), dict(tokens=1025), dict(width=12), dict(heads=65), dict(head_dim=32),
+               dict(mlp_hidden=4)):
+        base = dict(batch=1, tokens=8, width=64, heads=2, mlp_hidden=64, dtype="f32", head_dim=64)
+        base.update(kw)
+        desc = P.make_desc(base["batch"], base["tokens"], base["width"], base["heads"], base["mlp_hidden"], base["dtype"],
+                           0, 1.0, 1e-6, base["head_dim"])
+        assert P.d2ft_block_saved_bytes(desc) == 0 and P.d2ft_block_scratch_bytes(desc) == 0, kw
