@@ -421,15 +421,16 @@ __global__ __launch_bounds__(256) void lora_grad_a_kernel(const float* __restric
     __syncthreads();
     const int kl = threadIdx.x & 63, dq = threadIdx.x >> 6;   // column within the chunk, group of 16 rows
     const int k = blockIdx.y * 64 + kl;
+    // the 16 rows' split slices are added in slice order, 16 loads in flight at a time
     float gs[16];
 #pragma unroll
-    for (int dd = 0; dd < 16; ++dd) {
-        float v = 0.f;
-        if (k < D) {
-            const float* src = G + ((long)(j * 3 + p) * 64 + dq * 16 + dd) * D + k;
-            for (int s = 0; s < splits; ++s) v += src[s * slice_stride];
+    for (int dd = 0; dd < 16; ++dd) gs[dd] = 0.f;
+    if (k < D) {
+        const float* src = G + ((long)(j * 3 + p) * 64 + dq * 16) * D + k;
+        for (int s = 0; s < splits; ++s) {
+#pragma unroll
+            for (int dd = 0; dd < 16; ++dd) gs[dd] += src[(long)dd * D + s * slice_stride];
         }
-        gs[dd] = v;
     }
     gA += (long)h * r * D;
     for (int i = 0; i < r; ++i) {
@@ -461,22 +462,38 @@ __global__ __launch_bounds__(256) void lora_grad_b_kernel(const float* __restric
     const T* A = (plane == 0 ? la_q : la_v) + (long)h * r * D;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int d0 = blockIdx.y * 4;               // this workgroup's 4 rows of G_h
-    for (int i = 0; i < r; ++i) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int k = threadIdx.x; k < D; k += 256) {
-            const float a = ld<T>(A + (long)i * D + k);
+    // G_h's four rows are summed over the split slices once per group of 16 adapter rows
+    for (int i0 = 0; i0 < r; i0 += 16) {
+        float acc[4][16];
 #pragma unroll
-            for (int dd = 0; dd < 4; ++dd) {
-                const float* src = G + ((long)(j * 3 + p) * 64 + d0 + dd) * D + k;
-                float v = 0.f;
-                for (int s = 0; s < splits; ++s) v += src[s * slice_stride];
-                acc[dd] = fmaf(v, a, acc[dd]);
+        for (int dd = 0; dd < 4; ++dd)
+#pragma unroll
+            for (int ii = 0; ii < 16; ++ii) acc[dd][ii] = 0.f;
+        for (int k = threadIdx.x; k < D; k += 256) {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            const float* src = G + ((long)(j * 3 + p) * 64 + d0) * D + k;
+            for (int s = 0; s < splits; ++s) {
+#pragma unroll
+                for (int dd = 0; dd < 4; ++dd) v[dd] += src[(long)dd * D + s * slice_stride];
+            }
+#pragma unroll
+            for (int ii = 0; ii < 16; ++ii) {
+                if (i0 + ii < r) {
+                    const float a = ld<T>(A + (long)(i0 + ii) * D + k);
+#pragma unroll
+                    for (int dd = 0; dd < 4; ++dd) acc[dd][ii] = fmaf(v[dd], a, acc[dd][ii]);
+                }
             }
         }
 #pragma unroll
-        for (int dd = 0; dd < 4; ++dd) {
-            const float v = wave_sum(acc[dd]);
-            if (lane == 0) red[wave][dd][i] = v;
+        for (int ii = 0; ii < 16; ++ii) {
+            if (i0 + ii < r) {
+#pragma unroll
+                for (int dd = 0; dd < 4; ++dd) {
+                    const float v = wave_sum(acc[dd][ii]);
+                    if (lane == 0) red[wave][dd][i0 + ii] = v;
+                }
+            }
         }
     }
     __syncthreads();
