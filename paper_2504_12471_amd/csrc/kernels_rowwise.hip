@@ -372,6 +372,8 @@ __global__ __launch_bounds__(256) void zero_ffn_slices_kernel(HeadList heads, in
 //   out[(j*3+p)*64 + d][k] = W[p][h][d][k] + scale * sum_i B_p[h][d][i] * A_p[h][i][k],  h = live[j]
 // one block per output row
 // ---------------------------------------------------------------------------
+constexpr int kMaxLoraRank = D2FT_MAX_LORA_RANK;
+
 template <typename T>
 __global__ __launch_bounds__(256) void lora_merge_kernel(const T* __restrict__ w_qkv, const T* __restrict__ la_q,
                                                          const T* __restrict__ la_v, const T* __restrict__ lb_q,
@@ -384,11 +386,22 @@ __global__ __launch_bounds__(256) void lora_merge_kernel(const T* __restrict__ w
     const T* A = (p == 0) ? la_q : (p == 2 ? la_v : nullptr);
     const T* B = (p == 0) ? lb_q : (p == 2 ? lb_v : nullptr);
     T* orow = out + (long)row * D;
+    __shared__ float bs[kMaxLoraRank + 8];   // this row of B_h, zero padded to a multiple of 8
+    if (A) {
+        for (int i = threadIdx.x; i < ((r + 7) & ~7); i += 256) bs[i] = i < r ? (float)ld<T>(B + ((long)h * 64 + d) * r + i) : 0.f;
+        __syncthreads();
+    }
     for (int k = threadIdx.x; k < D; k += 256) {
         float v = ld<T>(wrow + k);
         if (A) {
             float acc = 0.f;
-            for (int i = 0; i < r; ++i) acc += ld<T>(B + ((long)h * 64 + d) * r + i) * ld<T>(A + ((long)h * r + i) * D + k);
+            for (int i0 = 0; i0 < r; i0 += 8) {   // eight rows of A in flight; terms are added in index order
+                float a[8];
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii) a[ii] = (i0 + ii < r) ? (float)ld<T>(A + ((long)h * r + i0 + ii) * D + k) : 0.f;
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii) acc += bs[i0 + ii] * a[ii];
+            }
             v += scale * acc;
         }
         st<T>(orow + k, v);
