@@ -50,6 +50,13 @@ design notes of the repository):
     a subnet that was not p_f in the step are left untouched, momentum included
     (a device that skipped its subnet does no work on it); tensors shared by all
     subnets are always updated.
+  * The two subnets outside the blocks (Sec. IV-A "Full fine-tuning partition
+    settings": the patch embedding layer, and the global pooling and
+    classification layer) are taken in the usual ViT form, which the paper does
+    not spell out: non-overlapping P x P patches flattened in (channel, row,
+    column) order and projected linearly, a class token in front, learned
+    position embeddings added; at the end LayerNorm of the class token (the
+    pooling), a linear layer and mean softmax cross-entropy.
   * In DPSearching the item weight tested and subtracted in the fill phase is
     the operation's own weight (W_p), as the backtracking phase uses; the
     backtracking index decrements by one.
@@ -445,6 +452,64 @@ def sgd_momentum_step(w: Dict[str, Optional[np.ndarray]], g: Dict[str, Optional[
             v_new[k][r] = vv
             w_new[k][r] = w_new[k][r] - lr * vv
     return w_new, v_new
+
+
+# ----------------------------------------------------------------------------
+# the two subnets outside the blocks (Sec. IV-A): patch embedding, pooling + classifier
+# ----------------------------------------------------------------------------
+def patch_embed_fwd(images: np.ndarray, w_pe: np.ndarray, b_pe: np.ndarray, cls: np.ndarray, pos: np.ndarray,
+                    patch: int):
+    """images [B, C, H, W] -> tokens [B, 1 + (H/P)(W/P), D].  w_pe [D, C*P*P] with k = (c*P + i)*P + j."""
+    images, w_pe, b_pe, cls, pos = map(_f64, (images, w_pe, b_pe, cls, pos))
+    B, C, H, W = images.shape
+    P = patch
+    ny, nx = H // P, W // P
+    patches = np.zeros((B, ny * nx, C * P * P))
+    for py in range(ny):
+        for px in range(nx):
+            blk = images[:, :, py * P:(py + 1) * P, px * P:(px + 1) * P]       # [B, C, P, P]
+            patches[:, py * nx + px] = blk.reshape(B, -1)
+    tokens = np.zeros((B, 1 + ny * nx, w_pe.shape[0]))
+    tokens[:, 0] = cls + pos[0]
+    tokens[:, 1:] = patches @ w_pe.T + b_pe + pos[1:]
+    return tokens, dict(patches=patches)
+
+
+def patch_embed_bwd(cache: dict, dtokens: np.ndarray):
+    """Gradients of the embedding's parameters (no gradient is taken with respect to the images)."""
+    dtokens = _f64(dtokens)
+    dp = dtokens[:, 1:]
+    D = dtokens.shape[-1]
+    return dict(w_pe=dp.reshape(-1, D).T @ cache["patches"].reshape(-1, cache["patches"].shape[-1]),
+                b_pe=dp.reshape(-1, D).sum(axis=0), cls=dtokens[:, 0].sum(axis=0), pos=dtokens.sum(axis=0))
+
+
+def classifier_fwd(tokens: np.ndarray, ln_g, ln_b, w_c, b_c, labels: Sequence[int], ln_eps: float = 1e-6):
+    """Class-token pooling, LayerNorm, linear layer, mean softmax cross-entropy.  Returns (loss, logits, cache)."""
+    tokens, ln_g, ln_b, w_c, b_c = map(_f64, (tokens, ln_g, ln_b, w_c, b_c))
+    h, xhat, rstd = layer_norm(tokens[:, 0], ln_g, ln_b, ln_eps)
+    logits = h @ w_c.T + b_c
+    zmax = logits.max(axis=-1, keepdims=True)
+    lse = zmax[:, 0] + np.log(np.exp(logits - zmax).sum(axis=-1))
+    labels = np.asarray(labels, dtype=np.int64)
+    loss = float((lse - logits[np.arange(len(labels)), labels]).mean())
+    return loss, logits, dict(h=h, xhat=xhat, rstd=rstd, logits=logits, lse=lse, labels=labels, shape=tokens.shape,
+                              ln_g=ln_g, w_c=w_c)
+
+
+def classifier_bwd(cache: dict):
+    """Returns (dtokens, grads): only the class-token rows of dtokens are non-zero."""
+    logits, labels = cache["logits"], cache["labels"]
+    Bn = logits.shape[0]
+    dl = np.exp(logits - cache["lse"][:, None])
+    dl[np.arange(Bn), labels] -= 1.0
+    dl /= Bn
+    g = dict(w_c=dl.T @ cache["h"], b_c=dl.sum(axis=0))
+    dh = dl @ cache["w_c"]
+    dcls, g["ln_g"], g["ln_b"] = layer_norm_bwd(dh, cache["xhat"], cache["rstd"], cache["ln_g"])
+    dtokens = np.zeros(cache["shape"])
+    dtokens[:, 0] = dcls
+    return dtokens, g
 
 
 # ----------------------------------------------------------------------------
