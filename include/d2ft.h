@@ -262,6 +262,58 @@ d2ft_status d2ft_sgd_step(const d2ft_block_desc *desc, const d2ft_block_grads *w
                           const d2ft_block_grads *master, const uint8_t *ops,
                           const d2ft_sgd_params *params, void *hip_stream);
 
+/* The two subnets outside the transformer blocks (Sec. IV-A, "Full fine-tuning partition settings":
+ * the patch embedding layer at the start, the global pooling and classification layer at the end).
+ * The paper does not spell them out; they are taken in the usual ViT form.
+ *
+ * Patch embedding: the image is cut into non-overlapping patch x patch squares, each flattened in
+ * (channel, row, column) order and projected, a class token goes in front, position embeddings are added:
+ *   tokens[b][0]     = cls + pos[0]
+ *   tokens[b][1 + p] = w_pe . patch(b, p) + b_pe + pos[1 + p],   p = py * (width_px / patch) + px
+ *   images  [B][C][H][W]            w_pe [D][C*patch*patch]      b_pe, cls [D]      pos [T][D]
+ *   tokens  [B][T][D], T = 1 + (H/patch)*(W/patch)
+ * patch must be a multiple of 8 and divide H and W; D a multiple of 8.  The backward call returns the
+ * parameter gradients (NULL pointers are skipped; D2FT_FLAG_ACCUM_GRADS in flags adds instead of
+ * overwriting); no gradient is taken with respect to the images.
+ *   saved    d2ft_embed_saved_bytes(desc) bytes, written by fwd, read by bwd
+ *   scratch  d2ft_embed_scratch_bytes(desc) bytes */
+typedef struct d2ft_embed_desc {
+    int32_t batch, channels, height, width_px, patch;
+    int32_t width;   /* D */
+    int32_t dtype;   /* d2ft_dtype */
+    uint32_t flags;  /* D2FT_FLAG_ACCUM_GRADS, D2FT_FLAG_NO_MFMA */
+} d2ft_embed_desc;
+size_t d2ft_embed_saved_bytes(const d2ft_embed_desc *desc);
+size_t d2ft_embed_scratch_bytes(const d2ft_embed_desc *desc);
+d2ft_status d2ft_patch_embed_fwd(const d2ft_embed_desc *desc, const void *images, const void *w_pe,
+                                 const void *b_pe, const void *cls, const void *pos, void *tokens,
+                                 void *saved, void *scratch, void *hip_stream);
+d2ft_status d2ft_patch_embed_bwd(const d2ft_embed_desc *desc, const void *dtokens, void *g_w_pe,
+                                 void *g_b_pe, void *g_cls, void *g_pos, const void *saved,
+                                 void *scratch, void *hip_stream);
+
+/* Pooling and classification with the loss, forward and backward in one call: LayerNorm of the class
+ * token (row 0 of each image), a linear layer, mean softmax cross-entropy over the batch, and the
+ * gradients: dtokens [B][T][D] is written in full (zero outside the class-token rows), parameter
+ * gradients where the pointers are non-NULL.  Arithmetic is fp32; images are added in index order.
+ * The call synchronises the stream to return the loss.
+ *   tokens [B][T][D]   ln_g, ln_b [D]   w_c [classes][D]   b_c [classes]
+ *   labels    HOST [B], each in [0, classes)  (else D2FT_EINVAL)
+ *   loss_out  HOST, one float
+ *   scratch   DEVICE, d2ft_head_scratch_bytes(desc) bytes, 256-byte aligned */
+typedef struct d2ft_head_desc {
+    int32_t batch, tokens, width, classes;
+    float ln_eps;
+    int32_t dtype;
+    uint32_t flags;   /* D2FT_FLAG_ACCUM_GRADS */
+} d2ft_head_desc;
+size_t d2ft_head_scratch_bytes(const d2ft_head_desc *desc);
+d2ft_status d2ft_classifier_fwd_bwd(const d2ft_head_desc *desc, const void *tokens, const void *ln_g,
+                                    const void *ln_b, const void *w_c, const void *b_c,
+                                    const int32_t *labels, float *loss_out, void *dtokens, void *g_ln_g,
+                                    void *g_ln_b, void *g_w_c, void *g_b_c, void *scratch,
+                                    void *hip_stream);
+
 /* Diagnostics: per-kernel timing.  While enabled, every kernel launch the library makes is
  * bracketed by a pair of HIP events on the stream of the call (this adds host work per launch:
  * do not time whole steps while it is on).  d2ft_timing_enable(1) clears earlier records and

@@ -286,9 +286,73 @@ def d2ft_sgd_step(desc: BlockDesc, weights: Dict[str, Optional[torch.Tensor]], g
     _check(st, "d2ft_sgd_step")
 
 
+class EmbedDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("channels", C.c_int32), ("height", C.c_int32), ("width_px", C.c_int32),
+                ("patch", C.c_int32), ("width", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+class HeadDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("tokens", C.c_int32), ("width", C.c_int32), ("classes", C.c_int32),
+                ("ln_eps", C.c_float), ("dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+_lib.d2ft_embed_saved_bytes.restype = C.c_size_t
+_lib.d2ft_embed_saved_bytes.argtypes = [C.POINTER(EmbedDesc)]
+_lib.d2ft_embed_scratch_bytes.restype = C.c_size_t
+_lib.d2ft_embed_scratch_bytes.argtypes = [C.POINTER(EmbedDesc)]
+_lib.d2ft_patch_embed_fwd.restype = C.c_int
+_lib.d2ft_patch_embed_fwd.argtypes = [C.POINTER(EmbedDesc)] + [C.c_void_p] * 9
+_lib.d2ft_patch_embed_bwd.restype = C.c_int
+_lib.d2ft_patch_embed_bwd.argtypes = [C.POINTER(EmbedDesc)] + [C.c_void_p] * 8
+_lib.d2ft_head_scratch_bytes.restype = C.c_size_t
+_lib.d2ft_head_scratch_bytes.argtypes = [C.POINTER(HeadDesc)]
+_lib.d2ft_classifier_fwd_bwd.restype = C.c_int
+_lib.d2ft_classifier_fwd_bwd.argtypes = [C.POINTER(HeadDesc)] + [C.c_void_p] * 14
+
+
+def d2ft_embed_saved_bytes(desc: EmbedDesc) -> int:
+    return int(_lib.d2ft_embed_saved_bytes(C.byref(desc)))
+
+
+def d2ft_embed_scratch_bytes(desc: EmbedDesc) -> int:
+    return int(_lib.d2ft_embed_scratch_bytes(C.byref(desc)))
+
+
+def d2ft_patch_embed_fwd(desc: EmbedDesc, images, w_pe, b_pe, cls, pos, tokens, saved, scratch, stream=None) -> None:
+    st = _lib.d2ft_patch_embed_fwd(C.byref(desc), _ptr(images), _ptr(w_pe), _ptr(b_pe), _ptr(cls), _ptr(pos), _ptr(tokens),
+                                   _ptr(saved), _ptr(scratch), _stream_ptr(stream))
+    _check(st, "d2ft_patch_embed_fwd")
+
+
+def d2ft_patch_embed_bwd(desc: EmbedDesc, dtokens, g_w_pe, g_b_pe, g_cls, g_pos, saved, scratch, stream=None) -> None:
+    st = _lib.d2ft_patch_embed_bwd(C.byref(desc), _ptr(dtokens), _ptr(g_w_pe), _ptr(g_b_pe), _ptr(g_cls), _ptr(g_pos),
+                                   _ptr(saved), _ptr(scratch), _stream_ptr(stream))
+    _check(st, "d2ft_patch_embed_bwd")
+
+
+def d2ft_head_scratch_bytes(desc: HeadDesc) -> int:
+    return int(_lib.d2ft_head_scratch_bytes(C.byref(desc)))
+
+
+def d2ft_classifier_fwd_bwd(desc: HeadDesc, tokens, ln_g, ln_b, w_c, b_c, labels, dtokens, g_ln_g, g_ln_b, g_w_c, g_b_c,
+                            scratch, stream=None) -> float:
+    """Returns the mean cross-entropy loss; dtokens and the non-None gradient tensors are written."""
+    lab = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    if lab.shape != (desc.batch,):
+        raise ValueError("one label per image")
+    loss = C.c_float(0.0)
+    st = _lib.d2ft_classifier_fwd_bwd(C.byref(desc), _ptr(tokens), _ptr(ln_g), _ptr(ln_b), _ptr(w_c), _ptr(b_c),
+                                      lab.ctypes.data, C.addressof(loss), _ptr(dtokens), _ptr(g_ln_g), _ptr(g_ln_b),
+                                      _ptr(g_w_c), _ptr(g_b_c), _ptr(scratch), _stream_ptr(stream))
+    _check(st, "d2ft_classifier_fwd_bwd")
+    return float(loss.value)
+
+
 def exported_symbols():
     """Names this binding resolves in the shared library (used by the load test)."""
     return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
             "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_block_saved_bytes_mb", "d2ft_block_fwd_mb", "d2ft_block_bwd_mb",
             "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
-            "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_sgd_step", "d2ft_timing_enable", "d2ft_timing_read"]
+            "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_sgd_step", "d2ft_embed_saved_bytes",
+            "d2ft_embed_scratch_bytes", "d2ft_patch_embed_fwd", "d2ft_patch_embed_bwd", "d2ft_head_scratch_bytes",
+            "d2ft_classifier_fwd_bwd", "d2ft_timing_enable", "d2ft_timing_read"]

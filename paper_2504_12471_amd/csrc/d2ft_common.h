@@ -155,6 +155,17 @@ struct ScoreArgs {
 };
 hipError_t launch_subnet_scores(int dtype, const ScoreArgs& a, int kind, double* partial, double* out, hipStream_t s);
 
+// the two subnets outside the blocks (kernels_head.hip)
+hipError_t launch_im2col(int dtype, const void* img, void* patches, int B, int C, int H, int W, int P, hipStream_t s);
+hipError_t launch_assemble_tokens(int dtype, const void* proj, const void* cls, const void* pos, void* tokens, int B, int Np,
+                                  int D, hipStream_t s);
+hipError_t launch_embed_bwd_gather(int dtype, const void* dtokens, void* dproj, void* g_pos, void* g_cls, int B, int Np, int D,
+                                   int accumulate, hipStream_t s);
+hipError_t launch_classifier(int dtype, const void* tokens, const void* ln_g, const void* ln_b, const void* w_c, const void* b_c,
+                             const int32_t* labels, int B, int Tn, int D, int n, float eps, float* xhat, float* h, float* rstd,
+                             float* logits, float* dl, float* loss_b, float* dh, void* dtokens, void* g_w_c, void* g_b_c,
+                             void* g_ln_g, void* g_ln_b, float* loss, int accumulate, hipStream_t s);
+
 // several independent column reductions out[c] = sum over chunks of partial[chunk][c] in one launch
 // (the bias gradients of one block); remap_cols = 1 or 2 sends column c to tbl_a(c) or tbl_b(c)
 struct ColReduceJob {

@@ -983,6 +983,168 @@ d2ft_status d2ft_sgd_step(const d2ft_block_desc* desc, const d2ft_block_grads* w
     return D2FT_OK;
 }
 
+// ---- the two subnets outside the blocks ----
+struct EmbedLayout {
+    long rows, K;          // B * patches per image, C * P * P
+    int Np;
+    size_t proj, dproj, part, colpart, total;
+};
+static bool embed_ok(const d2ft_embed_desc* d) {
+    if (!d) return false;
+    if (d->dtype != D2FT_F32 && d->dtype != D2FT_BF16) return false;
+    if (d->batch < 1 || d->channels < 1 || d->patch < 8 || d->patch % 8) return false;
+    if (d->height < d->patch || d->width_px < d->patch || d->height % d->patch || d->width_px % d->patch) return false;
+    if (d->width < 8 || d->width % 8) return false;
+    const long np = (long)(d->height / d->patch) * (d->width_px / d->patch);
+    if (np > 4096 || (long)d->batch * np > (1L << 24)) return false;
+    if ((long)d->channels * d->patch * d->patch > 65536) return false;
+    return true;
+}
+static EmbedLayout embed_layout(const d2ft_embed_desc* d) {
+    EmbedLayout L;
+    L.Np = (d->height / d->patch) * (d->width_px / d->patch);
+    L.rows = (long)d->batch * L.Np;
+    L.K = (long)d->channels * d->patch * d->patch;
+    const size_t es = elem_size(d->dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
+    L.proj = take((size_t)L.rows * d->width * es);
+    L.dproj = take((size_t)L.rows * d->width * es);
+    L.part = take((size_t)kMaxSplits * d->width * L.K * 4);
+    L.colpart = take((size_t)kColChunks * d->width * 4);
+    L.total = off;
+    return L;
+}
+// a block descriptor that carries dtype and flags to the GEMM helpers
+static d2ft_block_desc helper_desc(int dtype, uint32_t flags) {
+    d2ft_block_desc b;
+    memset(&b, 0, sizeof(b));
+    b.dtype = dtype;
+    b.flags = flags;
+    return b;
+}
+
+size_t d2ft_embed_saved_bytes(const d2ft_embed_desc* d) {
+    if (!embed_ok(d)) return 0;
+    const EmbedLayout L = embed_layout(d);
+    return align256((size_t)L.rows * L.K * elem_size(d->dtype));
+}
+size_t d2ft_embed_scratch_bytes(const d2ft_embed_desc* d) {
+    if (!embed_ok(d)) return 0;
+    return embed_layout(d).total;
+}
+
+d2ft_status d2ft_patch_embed_fwd(const d2ft_embed_desc* d, const void* images, const void* w_pe, const void* b_pe,
+                                 const void* cls, const void* pos, void* tokens, void* saved, void* scratch,
+                                 void* hip_stream) {
+    if (!d) return D2FT_EINVAL;
+    if (!embed_ok(d)) return D2FT_ESHAPE;
+    if (!images || !w_pe || !b_pe || !cls || !pos || !tokens || !saved || !scratch) return D2FT_EINVAL;
+    const void* ps[] = {images, w_pe, b_pe, cls, pos, tokens};
+    for (const void* p : ps)
+        if (!aligned16(p)) return D2FT_EINVAL;
+    if (((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
+    const EmbedLayout L = embed_layout(d);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(scratch);
+    D2FT_TRY(launch_im2col(d->dtype, images, saved, d->batch, d->channels, d->height, d->width_px, d->patch, st));
+    const d2ft_block_desc hd = helper_desc(d->dtype, d->flags);
+    GemmArgs g = gemm_base();
+    g.A = saved; g.a_rs = L.K; g.a_cs = 1;
+    g.B = w_pe; g.b_rs = 1; g.b_cs = L.K;
+    g.M = (int)L.rows; g.N = d->width; g.K = (int)L.K;
+    g.C = ws + L.proj; g.ldc = d->width;
+    g.bias = b_pe;
+    D2FT_TRY_UNTIMED(run_gemm(g, &hd, st));
+    D2FT_TRY(launch_assemble_tokens(d->dtype, ws + L.proj, cls, pos, tokens, d->batch, L.Np, d->width, st));
+    return D2FT_OK;
+}
+
+d2ft_status d2ft_patch_embed_bwd(const d2ft_embed_desc* d, const void* dtokens, void* g_w_pe, void* g_b_pe, void* g_cls,
+                                 void* g_pos, const void* saved, void* scratch, void* hip_stream) {
+    if (!d) return D2FT_EINVAL;
+    if (!embed_ok(d)) return D2FT_ESHAPE;
+    if (!dtokens || !saved || !scratch || !aligned16(dtokens)) return D2FT_EINVAL;
+    const void* ps[] = {g_w_pe, g_b_pe, g_cls, g_pos};
+    for (const void* p : ps)
+        if (p && !aligned16(p)) return D2FT_EINVAL;
+    if (((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
+    const EmbedLayout L = embed_layout(d);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(scratch);
+    const int accum = (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
+    D2FT_TRY(launch_embed_bwd_gather(d->dtype, dtokens, ws + L.dproj, g_pos, g_cls, d->batch, L.Np, d->width, accum, st));
+    const d2ft_block_desc hd = helper_desc(d->dtype, d->flags);
+    Dims s;
+    memset(&s, 0, sizeof(s));
+    s.M = L.rows; s.dtype = d->dtype; s.es = elem_size(d->dtype); s.D = d->width;
+    Remap64 none;
+    memset(&none, 0, sizeof(none));
+    if (g_w_pe) {   // dW_pe = dproj^T patches
+        const d2ft_status rc = weight_grad(&hd, s, ws + L.dproj, d->width, saved, L.K, d->width, (int)L.K,
+                                           (float*)(ws + L.part), g_w_pe, L.K, RED_REMAP_NONE, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    if (g_b_pe) {
+        ColReduceBatch batch;
+        memset(&batch, 0, sizeof(batch));
+        d2ft_status rc = bias_grad(s, ws + L.dproj, d->width, d->width, (float*)(ws + L.colpart), g_b_pe, 0, &batch, st);
+        if (rc != D2FT_OK) return rc;
+        rc = flush_bias_grads(&hd, s, &batch, none, none, st);
+        if (rc != D2FT_OK) return rc;
+    }
+    return D2FT_OK;
+}
+
+struct HeadLayout {
+    size_t xhat, h, dh, rstd, logits, dl, loss_b, loss, labels, total;
+};
+static bool head_ok(const d2ft_head_desc* d) {
+    if (!d) return false;
+    if (d->dtype != D2FT_F32 && d->dtype != D2FT_BF16) return false;
+    if (d->batch < 1 || d->batch > 65536 || d->tokens < 1 || d->tokens > 4097) return false;
+    if (d->width < 8 || d->width % 8 || d->width > 16384) return false;
+    if (d->classes < 1 || d->classes > 65536) return false;
+    if (!(d->ln_eps > 0.0f) || !isfinite(d->ln_eps)) return false;
+    return true;
+}
+static HeadLayout head_layout(const d2ft_head_desc* d) {
+    HeadLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
+    const size_t B = d->batch, D = d->width, n = d->classes;
+    L.xhat = take(B * D * 4); L.h = take(B * D * 4); L.dh = take(B * D * 4); L.rstd = take(B * 4);
+    L.logits = take(B * n * 4); L.dl = take(B * n * 4); L.loss_b = take(B * 4); L.loss = take(4);
+    L.labels = take(B * 4);
+    L.total = off;
+    return L;
+}
+size_t d2ft_head_scratch_bytes(const d2ft_head_desc* d) { return head_ok(d) ? head_layout(d).total : 0; }
+
+d2ft_status d2ft_classifier_fwd_bwd(const d2ft_head_desc* d, const void* tokens, const void* ln_g, const void* ln_b,
+                                    const void* w_c, const void* b_c, const int32_t* labels, float* loss_out, void* dtokens,
+                                    void* g_ln_g, void* g_ln_b, void* g_w_c, void* g_b_c, void* scratch, void* hip_stream) {
+    if (!d) return D2FT_EINVAL;
+    if (!head_ok(d)) return D2FT_ESHAPE;
+    if (!tokens || !ln_g || !ln_b || !w_c || !b_c || !labels || !loss_out || !dtokens || !scratch) return D2FT_EINVAL;
+    if (((uintptr_t)scratch & 255) || tokens == dtokens) return D2FT_EINVAL;
+    for (int b = 0; b < d->batch; ++b)
+        if (labels[b] < 0 || labels[b] >= d->classes) return D2FT_EINVAL;
+    const HeadLayout L = head_layout(d);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(scratch);
+    if (hipMemcpyAsync(ws + L.labels, labels, (size_t)d->batch * 4, hipMemcpyHostToDevice, st) != hipSuccess)
+        return D2FT_EDEVICE;
+    D2FT_TRY(launch_classifier(d->dtype, tokens, ln_g, ln_b, w_c, b_c, (const int32_t*)(ws + L.labels), d->batch, d->tokens,
+                               d->width, d->classes, d->ln_eps, (float*)(ws + L.xhat), (float*)(ws + L.h),
+                               (float*)(ws + L.rstd), (float*)(ws + L.logits), (float*)(ws + L.dl), (float*)(ws + L.loss_b),
+                               (float*)(ws + L.dh), dtokens, g_w_c, g_b_c, g_ln_g, g_ln_b, (float*)(ws + L.loss),
+                               (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+    if (hipMemcpyAsync(loss_out, ws + L.loss, 4, hipMemcpyDeviceToHost, st) != hipSuccess) return D2FT_EDEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return D2FT_EDEVICE;
+    return D2FT_OK;
+}
+
 size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const int32_t* cap_full,
                                      const int32_t* cap_fwd) {
     if (n_knapsacks < 1 || n_items < 1 || !cap_full || !cap_fwd) return 0;
