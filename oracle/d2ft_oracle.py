@@ -60,7 +60,9 @@ design notes of the repository):
   * In DPSearching the item weight tested and subtracted in the fill phase is
     the operation's own weight (W_p), as the backtracking phase uses; the
     backtracking index decrements by one.
-  * An item is taken only where it strictly changes the table value.
+  * An item is taken only where it strictly changes the table value.  What the
+    selection does on exactly tied scores rests on that rule alone: parity
+    unpinned for ties (every other part of this file has a pin in tests/).
   * The two DP calls use separate capacities, as Alg. 1's inputs state; an
     item chosen by both is p_f.
 
