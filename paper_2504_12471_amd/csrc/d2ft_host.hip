@@ -447,12 +447,26 @@ d2ft_status d2ft_compact_heads(const uint8_t* ops, int32_t heads, int32_t* live,
     return compact(ops, heads, live, n_full, n_live);
 }
 
-d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
-                           const void* x, void* y, void* saved, void* scratch, void* hip_stream) {
-    d2ft_status why;
-    if (!desc_ok(desc, &why)) return why;
-    if (!weights_ok(desc, w) || !ops || !x || !y || !saved || !scratch || x == y) return D2FT_EINVAL;
-    if (!aligned16(x) || !aligned16(y) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
+static bool grads_aligned(const d2ft_block_grads* grads) {
+    const void* gp[] = {grads->ln1_g, grads->ln1_b, grads->w_qkv, grads->b_qkv, grads->w_o, grads->b_o,
+                        grads->ln2_g, grads->ln2_b, grads->w1, grads->b1, grads->w2, grads->b2,
+                        grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v};
+    for (const void* p : gp)
+        if (p && !aligned16(p)) return false;
+    return true;
+}
+
+// Which half of a block a call works on.  The public block calls run both; the micro-batched calls run
+// the attention half per micro-batch (its op codes differ) and, when the feed-forward network is not
+// gated, the feed-forward half once for the whole batch.
+enum { PART_BOTH = 0, PART_ATTN = 1, PART_MLP = 2 };
+
+// Forward of a block or of one half of it.  Arguments are validated by the callers.
+//   PART_ATTN: y receives x1 = x + attention residual;   PART_MLP: x is x1.
+//   sva / svm: where the attention-side / feed-forward-side fields of SavedLayout live (both are the
+//   start of the one saved buffer for PART_BOTH)
+static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
+                                  const void* x, void* y, char* sva, char* svm, void* scratch, hipStream_t st, int part) {
     int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
     d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
     if (cs != D2FT_OK) return cs;
@@ -460,13 +474,14 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
     const Dims s = dims_of(desc);
     const SavedLayout SL = saved_layout(s);
     const ScratchLayout WL = scratch_layout(s);
-    char* sv = static_cast<char*>(saved);
     char* ws = static_cast<char*>(scratch);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int M = (int)s.M;
+    const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
+    if (part != PART_BOTH && gate) return D2FT_EINVAL;   // a gated feed-forward slice goes with its head
+    char* sv = sva;
 
     const void* x1 = x;   // all heads shortcut: the attention residual is x itself
-    if (nl > 0) {
+    if (part != PART_MLP && nl > 0) {
         void* u = sv + SL.u;
         D2FT_TRY(launch_ln_fwd(s.dtype, x, w->ln1_g, w->ln1_b, u, (float*)(sv + SL.mean1), (float*)(sv + SL.rstd1), M,
                                s.D, desc->ln_eps, st));
@@ -496,13 +511,22 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
         p.A = sv + SL.o; p.a_rs = nl * 64; p.a_cs = 1;
         p.B = w->w_o; p.b_rs = 1; p.b_cs = (long)s.H * 64; p.remap = REMAP_B_K;
         p.M = M; p.N = s.D; p.K = nl * 64;
-        p.C = sv + SL.x1; p.ldc = s.D;
+        p.C = (part == PART_ATTN) ? y : (void*)(sv + SL.x1); p.ldc = s.D;
         p.bias = w->b_o;
         p.residual = x; p.ldr = s.D;
         D2FT_TRY_UNTIMED(run_gemm(p, desc, st));
-        x1 = sv + SL.x1;
+        x1 = p.C;
     }
-    const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
+    if (part == PART_ATTN) {
+        if (nl == 0) {   // x1 is x: the caller wants it in y
+            timing_begin(st, "copy");
+            const hipError_t e = hipMemcpyAsync(y, x, (size_t)s.M * s.D * s.es, hipMemcpyDeviceToDevice, st);
+            timing_end(st);
+            if (e != hipSuccess) return D2FT_EDEVICE;
+        }
+        return D2FT_OK;
+    }
+    sv = svm;
     if (gate && nl == 0) {   // no live subnet: the block is the identity (neither bias is applied)
         timing_begin(st, "copy");
         const hipError_t e = hipMemcpyAsync(y, x, (size_t)s.M * s.D * s.es, hipMemcpyDeviceToDevice, st);
@@ -543,22 +567,22 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
     return D2FT_OK;
 }
 
-d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
-                           const void* x, const void* dy, void* dx, const d2ft_block_grads* grads, const void* saved,
-                           void* scratch, void* hip_stream) {
+d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
+                           const void* x, void* y, void* saved, void* scratch, void* hip_stream) {
     d2ft_status why;
     if (!desc_ok(desc, &why)) return why;
-    if (!weights_ok(desc, w) || !ops || !x || !dy || !dx || !grads || !saved || !scratch || dy == dx)
-        return D2FT_EINVAL;
-    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255))
-        return D2FT_EINVAL;
-    {
-        const void* gp[] = {grads->ln1_g, grads->ln1_b, grads->w_qkv, grads->b_qkv, grads->w_o, grads->b_o,
-                            grads->ln2_g, grads->ln2_b, grads->w1, grads->b1, grads->w2, grads->b2,
-                            grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v};
-        for (const void* p : gp)
-            if (p && !aligned16(p)) return D2FT_EINVAL;
-    }
+    if (!weights_ok(desc, w) || !ops || !x || !y || !saved || !scratch || x == y) return D2FT_EINVAL;
+    if (!aligned16(x) || !aligned16(y) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
+    return block_fwd_impl(desc, w, ops, x, y, static_cast<char*>(saved), static_cast<char*>(saved), scratch,
+                          static_cast<hipStream_t>(hip_stream), PART_BOTH);
+}
+
+// Backward of a block or of one half of it.  Arguments are validated by the callers.
+//   PART_MLP:  x is x1, dy the gradient of the block output, dx receives dx1 (the gradient of x1)
+//   PART_ATTN: dy is dx1 and may be the same buffer as dx (rows are rewritten in place)
+static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
+                                  const void* x, const void* dy, void* dx, const d2ft_block_grads* grads,
+                                  const char* sva, const char* svm, void* scratch, hipStream_t st, int half) {
     int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
     d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
     if (cs != D2FT_OK) return cs;
@@ -566,9 +590,8 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     const Dims s = dims_of(desc);
     const SavedLayout SL = saved_layout(s);
     const ScratchLayout WL = scratch_layout(s);
-    const char* sv = static_cast<const char*>(saved);
+    const char* sv = svm;
     char* ws = static_cast<char*>(scratch);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int M = (int)s.M;
     const int accum = (desc->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
     float* part = (float*)(ws + WL.part);
@@ -578,11 +601,12 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     memset(&bias_batch, 0, sizeof(bias_batch));
     Remap64 none;
     memset(&none, 0, sizeof(none));
-    const void* x1 = nl > 0 ? (const void*)(sv + SL.x1) : x;
+    const void* x1 = (half != PART_MLP && nl > 0) ? (const void*)(sva + SL.x1) : x;
     d2ft_status rc;
 
     // ---- feed-forward network: all of it, or (gated) the slices of the p_f heads, a prefix of the compacted layout ----
     const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
+    if (half != PART_BOTH && gate) return D2FT_EINVAL;   // a gated feed-forward slice goes with its head
     const int slice = gate ? s.Dm / s.H : 0;
     const int ld_hid = gate ? nl * slice : s.Dm;      // row stride of the saved z and g
     const int n_hid = gate ? nf * slice : s.Dm;       // hidden units that take part in backward
@@ -601,13 +625,14 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
             if (grads->ln2_b) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, 0, st));
         }
     }
-    if (grads->b2 && w->b2 && (!gate || nl > 0)) {
+    if (half != PART_ATTN && grads->b2 && w->b2 && (!gate || nl > 0)) {
         rc = bias_grad(s, dy, s.D, s.D, colpart + 0 * WL.colpart_stride, grads->b2, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
-    const void* dx1_in = dy;   // gated with no p_f subnet: the residual route alone, dx1 = dy
-    void* dx1 = nullptr;
-    if (n_hid > 0) {
+    // gradient of x1.  It is dy when the feed-forward half is not run here: handed over by the caller
+    // (PART_ATTN), or gated with no p_f subnet (the residual route alone).
+    const void* dx1 = dy;
+    if (half != PART_ATTN && n_hid > 0) {
         if (grads->w2) {   // dW2[:, hidden] = dy^T g
             rc = weight_grad(desc, s, dy, s.D, sv + SL.g, ld_hid, s.D, n_hid, part, grads->w2, s.Dm,
                              gate ? RED_REMAP_COLS : RED_REMAP_NONE, ffn_tbl, st);
@@ -655,15 +680,17 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
                 D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, accum, st));
         }
         // dx1 = dy + LN2bwd(dv); with no p_f head this already is dx (residual route only)
-        dx1 = (nf > 0) ? (void*)(ws + WL.dx1) : dx;
+        void* out = (half == PART_BOTH && nf > 0) ? (void*)(ws + WL.dx1) : dx;
         D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2), (const float*)(sv + SL.rstd2),
-                               w->ln2_g, dy, dx1, M, s.D, st));
-        dx1_in = dx1;
+                               w->ln2_g, dy, out, M, s.D, st));
+        dx1 = out;
     }
+    if (half == PART_MLP) return flush_bias_grads(desc, s, &bias_batch, none, ffn_tbl, st);
 
     // ---- attention side ----
+    sv = sva;
     if (grads->b_o && w->b_o && nl > 0) {
-        rc = bias_grad(s, dx1_in, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
+        rc = bias_grad(s, dx1, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     // heads that are not p_f: gradient slices are +0.0 in overwrite mode, untouched in accumulate mode
@@ -683,9 +710,9 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
         }
     }
     if (nf == 0) {
-        if (!dx1) {   // gated, no p_f subnet: the gradient passes by the residual route unchanged
+        if (dx1 != dx) {   // the gradient passes by the residual route unchanged
             timing_begin(st, "copy");
-            const hipError_t e = hipMemcpyAsync(dx, dy, (size_t)s.M * s.D * s.es, hipMemcpyDeviceToDevice, st);
+            const hipError_t e = hipMemcpyAsync(dx, dx1, (size_t)s.M * s.D * s.es, hipMemcpyDeviceToDevice, st);
             timing_end(st);
             if (e != hipSuccess) return D2FT_EDEVICE;
         }
@@ -769,6 +796,20 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights
     return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st);
 }
 
+d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
+                           const void* x, const void* dy, void* dx, const d2ft_block_grads* grads, const void* saved,
+                           void* scratch, void* hip_stream) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!weights_ok(desc, w) || !ops || !x || !dy || !dx || !grads || !saved || !scratch || dy == dx)
+        return D2FT_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255))
+        return D2FT_EINVAL;
+    if (!grads_aligned(grads)) return D2FT_EINVAL;
+    return block_bwd_impl(desc, w, ops, x, dy, dx, grads, static_cast<const char*>(saved), static_cast<const char*>(saved),
+                          scratch, static_cast<hipStream_t>(hip_stream), PART_BOTH);
+}
+
 // ---- micro-batches: the block calls applied to consecutive image ranges ----
 static bool micro_ok(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
     if (n_micro < 1 || n_micro > D2FT_MAX_MICRO || !mb_images) return false;
@@ -780,16 +821,42 @@ static bool micro_ok(const d2ft_block_desc* desc, int32_t n_micro, const int32_t
     return sum == desc->batch;
 }
 
-size_t d2ft_block_saved_bytes_mb(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
-    d2ft_status why;
-    if (!desc_ok(desc, &why) || !micro_ok(desc, n_micro, mb_images)) return 0;
-    size_t total = 0;
+// Saved-activation layout of the micro-batched calls.
+//   gated feed-forward: one whole SavedLayout per micro-batch (each micro-batch is a block call of its own)
+//   otherwise: the attention-side fields per micro-batch, then x1 of the whole batch, then the
+//   feed-forward fields of the whole batch (that half does not depend on the op codes, so it runs once)
+struct MicroPlan {
+    bool shared_mlp;
+    size_t at[D2FT_MAX_MICRO];   // start of micro-batch i's fields
+    size_t x1, mlp, total;       // shared_mlp only: whole-batch x1; feed-forward fields begin at mlp
+};
+static MicroPlan micro_plan(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
+    MicroPlan P;
+    memset(&P, 0, sizeof(P));
+    P.shared_mlp = (desc->flags & D2FT_FLAG_GATE_FFN) == 0;
+    size_t off = 0;
     for (int i = 0; i < n_micro; ++i) {
         d2ft_block_desc d = *desc;
         d.batch = mb_images[i];
-        total += saved_layout(dims_of(&d)).total;
+        const SavedLayout L = saved_layout(dims_of(&d));
+        P.at[i] = off;
+        off += P.shared_mlp ? L.x1 : L.total;
     }
-    return total;
+    if (P.shared_mlp) {
+        const SavedLayout L = saved_layout(dims_of(desc));
+        P.x1 = off;
+        off += L.mean2 - L.x1;
+        P.mlp = off;
+        off += L.total - L.mean2;
+    }
+    P.total = off;
+    return P;
+}
+
+size_t d2ft_block_saved_bytes_mb(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
+    d2ft_status why;
+    if (!desc_ok(desc, &why) || !micro_ok(desc, n_micro, mb_images)) return 0;
+    return micro_plan(desc, n_micro, mb_images).total;
 }
 
 d2ft_status d2ft_block_fwd_mb(const d2ft_block_desc* desc, const d2ft_block_weights* w, int32_t n_micro,
@@ -798,20 +865,31 @@ d2ft_status d2ft_block_fwd_mb(const d2ft_block_desc* desc, const d2ft_block_weig
     d2ft_status why;
     if (!desc_ok(desc, &why)) return why;
     if (!micro_ok(desc, n_micro, mb_images)) return mb_images ? D2FT_ESHAPE : D2FT_EINVAL;
-    if (!ops || !x || !y || !saved) return D2FT_EINVAL;
+    if (!weights_ok(desc, w) || !ops || !x || !y || !saved || !scratch || x == y) return D2FT_EINVAL;
+    if (!aligned16(x) || !aligned16(y) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
     for (int i = 0; i < n_micro * desc->heads; ++i)   // validate every code before the first launch
         if (ops[i] < D2FT_OP_FULL || ops[i] > D2FT_OP_SKIP) return D2FT_EINVAL;
+    const MicroPlan P = micro_plan(desc, n_micro, mb_images);
     const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
-    size_t img0 = 0, sv0 = 0;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* sv = static_cast<char*>(saved);
+    size_t img0 = 0;
     for (int i = 0; i < n_micro; ++i) {
         d2ft_block_desc d = *desc;
         d.batch = mb_images[i];
-        const d2ft_status rc = d2ft_block_fwd(&d, w, ops + (size_t)i * desc->heads, static_cast<const char*>(x) + img0 * row_bytes,
-                                              static_cast<char*>(y) + img0 * row_bytes, static_cast<char*>(saved) + sv0,
-                                              scratch, hip_stream);
+        const char* xi = static_cast<const char*>(x) + img0 * row_bytes;
+        // attention half alone: x1 of these images goes into the whole-batch x1
+        void* out = P.shared_mlp ? (void*)(sv + P.x1 + img0 * row_bytes) : (void*)(static_cast<char*>(y) + img0 * row_bytes);
+        const d2ft_status rc = block_fwd_impl(&d, w, ops + (size_t)i * desc->heads, xi, out, sv + P.at[i], sv + P.at[i],
+                                              scratch, st, P.shared_mlp ? PART_ATTN : PART_BOTH);
         if (rc != D2FT_OK) return rc;
         img0 += mb_images[i];
-        sv0 += saved_layout(dims_of(&d)).total;
+    }
+    if (P.shared_mlp) {
+        const SavedLayout L = saved_layout(dims_of(desc));
+        uint8_t any[D2FT_MAX_HEADS];   // op codes play no part in the ungated feed-forward half
+        for (int h = 0; h < desc->heads; ++h) any[h] = D2FT_OP_FULL;
+        return block_fwd_impl(desc, w, any, sv + P.x1, y, nullptr, sv + P.mlp - L.mean2, scratch, st, PART_MLP);
     }
     return D2FT_OK;
 }
@@ -822,22 +900,37 @@ d2ft_status d2ft_block_bwd_mb(const d2ft_block_desc* desc, const d2ft_block_weig
     d2ft_status why;
     if (!desc_ok(desc, &why)) return why;
     if (!micro_ok(desc, n_micro, mb_images)) return mb_images ? D2FT_ESHAPE : D2FT_EINVAL;
-    if (!ops || !x || !dy || !dx || !saved || !grads) return D2FT_EINVAL;
+    if (!weights_ok(desc, w) || !ops || !x || !dy || !dx || !saved || !grads || !scratch || dy == dx) return D2FT_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || ((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255))
+        return D2FT_EINVAL;
+    if (!grads_aligned(grads)) return D2FT_EINVAL;
     for (int i = 0; i < n_micro * desc->heads; ++i)
         if (ops[i] < D2FT_OP_FULL || ops[i] > D2FT_OP_SKIP) return D2FT_EINVAL;
+    const MicroPlan P = micro_plan(desc, n_micro, mb_images);
     const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
-    size_t img0 = 0, sv0 = 0;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const char* sv = static_cast<const char*>(saved);
+    if (P.shared_mlp) {   // feed-forward half over the whole batch: dx <- dx1, with the caller's flags
+        const SavedLayout L = saved_layout(dims_of(desc));
+        uint8_t any[D2FT_MAX_HEADS];
+        for (int h = 0; h < desc->heads; ++h) any[h] = D2FT_OP_FULL;
+        const d2ft_status rc = block_bwd_impl(desc, w, any, sv + P.x1, dy, dx, grads, nullptr, sv + P.mlp - L.mean2,
+                                              scratch, st, PART_MLP);
+        if (rc != D2FT_OK) return rc;
+    }
+    size_t img0 = 0;
     for (int i = 0; i < n_micro; ++i) {
         d2ft_block_desc d = *desc;
         d.batch = mb_images[i];
         if (i > 0) d.flags |= D2FT_FLAG_ACCUM_GRADS;   // later micro-batches add to the first one's result
-        const d2ft_status rc = d2ft_block_bwd(&d, w, ops + (size_t)i * desc->heads, static_cast<const char*>(x) + img0 * row_bytes,
-                                              static_cast<const char*>(dy) + img0 * row_bytes,
-                                              static_cast<char*>(dx) + img0 * row_bytes, grads,
-                                              static_cast<const char*>(saved) + sv0, scratch, hip_stream);
+        const char* xi = static_cast<const char*>(x) + img0 * row_bytes;
+        char* dxi = static_cast<char*>(dx) + img0 * row_bytes;
+        // attention half alone: dx1 of these images sits in dx and is rewritten in place
+        const char* dyi = P.shared_mlp ? dxi : static_cast<const char*>(dy) + img0 * row_bytes;
+        const d2ft_status rc = block_bwd_impl(&d, w, ops + (size_t)i * desc->heads, xi, dyi, dxi, grads, sv + P.at[i],
+                                              sv + P.at[i], scratch, st, P.shared_mlp ? PART_ATTN : PART_BOTH);
         if (rc != D2FT_OK) return rc;
         img0 += mb_images[i];
-        sv0 += saved_layout(dims_of(&d)).total;
     }
     return D2FT_OK;
 }

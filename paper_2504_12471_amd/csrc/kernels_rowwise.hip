@@ -104,8 +104,9 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ d, const T* __restrict__ x,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                     const T* __restrict__ gamma, const T* __restrict__ res,
-                                                     T* __restrict__ dx, int rows, int width) {
+                                                     const T* __restrict__ gamma, const T* res, T* dx, int rows,
+                                                     int width) {
+    // res and dx may be the same buffer: every lane reads its res elements before it writes them
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;

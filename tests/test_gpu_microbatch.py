@@ -60,6 +60,13 @@ def test_fp32_three_micro_batches():
     run_mb(w, [[FULL, FWD, SKIP], [SKIP, FULL, SKIP], [FWD, FWD, SKIP]], [1, 3, 2], seed=71)
 
 
+def test_fp32_micro_batches_without_a_live_or_full_subnet():
+    """First micro-batch all-shortcut (x1 = x, b_o not applied), second forward-only, third mixed."""
+    w = di.scaled(di.WORKLOADS["vit_tiny_fp32"], batch=6)
+    run_mb(w, [[SKIP, SKIP, SKIP], [FWD, SKIP, FWD], [FULL, FWD, SKIP]], [2, 1, 3], seed=77)
+    run_mb(w, [[FWD, FWD, FWD], [SKIP, SKIP, SKIP]], [4, 2], seed=78)      # nothing is p_f anywhere
+
+
 def test_fp32_gated_micro_batches():
     w = di.scaled(di.WORKLOADS["vit_tiny_fp32"], batch=5)
     run_mb(w, [[FULL, SKIP, SKIP], [SKIP, SKIP, SKIP], [FWD, FULL, SKIP]], [2, 1, 2], seed=72, gate=True)
