@@ -50,6 +50,10 @@ template <int BI, int BK, bool COL> constexpr int slab_elems() {
 // branch and no select in the loop.  The part of the address that does not change from slab to
 // slab (the index part) is computed once.
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+// LDS is addressed through pointers that carry the LDS address space: their arithmetic is 32-bit and
+// constant offsets fold into the instructions' offset fields (generic pointers cost a null check and a
+// 64-bit select per use)
+typedef __attribute__((address_space(3))) bf16 lds_bf16;
 constexpr uint32_t kBufBytes = 0x80000000u;   // declared buffer size; operands are checked to be smaller
 constexpr uint32_t kOutside = 0x80000000u;    // any offset >= kBufBytes reads as zero
 
@@ -83,47 +87,55 @@ struct SlabLoader {
         }
     }
 
-    // slab starting at k0 (a multiple of 64 counted from 0), valid k < k_end
+    // slab starting at k0 (a multiple of 64 counted from 0), valid k < k_end; chunk c alone, or all chunks
     template <bool REMAP_K>
-    __device__ __forceinline__ void load(int k0, int k_end, const Remap64& tbl) {
+    __device__ __forceinline__ void load_one(int c, int k0, int k_end, const Remap64& tbl) {
         const uint32_t kstart = REMAP_K ? (uint32_t)tbl.start[k0 >> 6] : (uint32_t)k0;
         const uint32_t koff = kstart * sk_bytes;   // uniform over the workgroup
-        const int left = k_end - k0;
+        const uint32_t off = (k_local(c) < k_end - k0) ? base[c] : kOutside;
+        v[c] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, koff, 0);
+    }
+    template <bool REMAP_K>
+    __device__ __forceinline__ void load(int k0, int k_end, const Remap64& tbl) {
 #pragma unroll
-        for (int c = 0; c < kPerThread; ++c) {
-            const uint32_t off = (k_local(c) < left) ? base[c] : kOutside;
-            v[c] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, koff, 0);
-        }
+        for (int c = 0; c < kPerThread; ++c) load_one<REMAP_K>(c, k0, k_end, tbl);
     }
 
-    __device__ __forceinline__ void store(bf16* lds) const {
-#pragma unroll
-        for (int c = 0; c < kPerThread; ++c) {
-            const int id = threadIdx.x + c * kThreads;
-            int off;
-            if (COL) {
-                off = (id / (BI / 8)) * col_form_stride<BI>() + (id % (BI / 8)) * 8;
-            } else {
-                off = (id / (BK / 8)) * row_form_stride<BK>() + (id % (BK / 8)) * 8;
-            }
-            *reinterpret_cast<u32x4*>(lds + off) = v[c];
+    __device__ __forceinline__ void store_one(int c, lds_bf16* lds) const {
+        const int id = threadIdx.x + c * kThreads;
+        int off;
+        if (COL) {
+            off = (id / (BI / 8)) * col_form_stride<BI>() + (id % (BI / 8)) * 8;
+        } else {
+            off = (id / (BK / 8)) * row_form_stride<BK>() + (id % (BK / 8)) * 8;
         }
+        *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(lds + off) = v[c];
+    }
+    __device__ __forceinline__ void store(lds_bf16* lds) const {
+#pragma unroll
+        for (int c = 0; c < kPerThread; ++c) store_one(c, lds);
     }
 };
 
 // ---- LDS -> MFMA operand fragment: rows i_base + lane%32, k = kk + 8*(lane/32) .. +7 ----
+// The address is split into a part that depends on the lane and the wavefront (computed once per
+// kernel, one register) and a compile-time part (buffer, MFMA tile, k step) that goes into the
+// instruction's offset field.
 template <int BI, int BK, bool COL>
-__device__ __forceinline__ bf16x8 read_fragment(const bf16* lds, int i_base, int kk, int lane) {
+__device__ __forceinline__ int fragment_lane_offset(int i_wave, int lane) {
+    if (!COL) return (i_wave + (lane & 31)) * row_form_stride<BK>() + 8 * (lane >> 5);
+    // transposing read: a group of 16 lanes turns a 4 (k) x 16 (index) block into 4 consecutive k per lane;
+    // lane j of the group supplies the address of row k = j/4, columns 4*(j%4) .. +3
+    const int j = lane & 15;
+    return (8 * (lane >> 5) + (j >> 2)) * col_form_stride<BI>() + i_wave + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+}
+template <int BI, int BK, bool COL>
+__device__ __forceinline__ bf16x8 read_fragment(const lds_bf16* lane_base, int i_tile, int kk) {
     if (!COL) {
-        const bf16* p = lds + (i_base + (lane & 31)) * row_form_stride<BK>() + kk + 8 * (lane >> 5);
-        return *reinterpret_cast<const bf16x8*>(p);
+        const lds_bf16* p = lane_base + (i_tile * row_form_stride<BK>() + kk);
+        return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(p);
     } else {
-        // transposing read: a group of 16 lanes turns a 4 (k) x 16 (index) block into 4 consecutive k per lane;
-        // lane j of the group supplies the address of row k = j/4, columns 4*(j%4) .. +3
-        const int j = lane & 15;
-        const int i_blk = i_base + 16 * ((lane >> 4) & 1);
-        const int k_blk = kk + 8 * (lane >> 5);
-        const bf16* p = lds + (k_blk + (j >> 2)) * col_form_stride<BI>() + i_blk + 4 * (j & 3);
+        const lds_bf16* p = lane_base + (kk * col_form_stride<BI>() + i_tile);
         typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * col_form_stride<BI>()));
@@ -160,41 +172,29 @@ __device__ __forceinline__ float phi_poly(float z) {
 }
 
 // ---- issue order of one MFMA group ----
-// NM MFMAs with NR LDS reads (and optionally NW LDS stores and NW global loads) spread evenly
-// between them, expressed as scheduling-group barriers for the compiler's instruction scheduler.
-template <int NM, int NR, int NW, bool READS, bool STORES, bool LOADS, int I = 0>
+// A group is NM MFMAs with, between them, the NR LDS reads of the next group's fragments and NS LDS
+// stores of the next slab, each store followed by the global load that refills its registers.  The
+// reads ride on the first MFMAs of the group so that every fragment has at least two MFMAs of time to
+// arrive before the next group starts; the stores follow (LDS reads cannot be moved across LDS
+// stores: the compiler must assume the buffers alias).  Expressed as scheduling-group barriers.
+template <int NM, int NR, int NS, int I = 0>
 __device__ __forceinline__ void pace_group() {
+    constexpr int RA0 = NS > 0 ? NM / 2 : NM - 2;
+    constexpr int RA = RA0 > 0 ? RA0 : 1;   // MFMAs that carry the reads
     if constexpr (I < NM) {
-        constexpr int nw = (I + 1) * NW / NM - I * NW / NM;
-        constexpr int nr = (I + 1) * NR / NM - I * NR / NM;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   // MFMA
-        if constexpr (READS && nr > 0) __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);   // LDS read
-        if constexpr (STORES && nw > 0) __builtin_amdgcn_sched_group_barrier(0x200, nw, 0);  // LDS store
-        if constexpr (LOADS && nw > 0) __builtin_amdgcn_sched_group_barrier(0x020, nw, 0);   // global load
-        pace_group<NM, NR, NW, READS, STORES, LOADS, I + 1>();
-    }
-}
-
-// First MFMA group of a slab: LDS reads cannot be moved across LDS stores (the compiler must assume
-// the two buffers alias), so the group's reads all go behind its first quarter of MFMAs and the
-// stores of the next slab, each followed by the global load that refills its registers, behind the rest.
-template <int NM, int NR, int NW, int I = 0>
-__device__ __forceinline__ void pace_first_group() {
-    constexpr int RA = NM / 4 > 0 ? NM / 4 : 1;   // MFMAs that carry the reads
-    if constexpr (I < NM) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
         if constexpr (I < RA) {
             constexpr int nr = (I + 1) * NR / RA - I * NR / RA;
-            if constexpr (nr > 0) __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);
-        } else {
+            if constexpr (nr > 0) __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);   // LDS read
+        } else if constexpr (NS > 0) {
             constexpr int J = I - RA, NB = NM - RA;
-            constexpr int nw = (J + 1) * NW / NB - J * NW / NB;
+            constexpr int nw = (J + 1) * NS / NB - J * NS / NB;
             if constexpr (nw > 0) {
-                __builtin_amdgcn_sched_group_barrier(0x200, nw, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, nw, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, nw, 0);   // LDS store
+                __builtin_amdgcn_sched_group_barrier(0x020, nw, 0);   // global load
             }
         }
-        pace_first_group<NM, NR, NW, I + 1>();
+        pace_group<NM, NR, NS, I + 1>();
     }
 }
 
@@ -231,11 +231,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     constexpr int A_ELEMS = slab_elems<BM, BK, A_COL>();
     constexpr int B_ELEMS = slab_elems<BN, BK, B_COL>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-    bf16* const As0 = smem;
-    bf16* const Bs0 = smem + A_ELEMS;
-    bf16* const As1 = smem + A_ELEMS + B_ELEMS;
-    bf16* const Bs1 = smem + 2 * A_ELEMS + B_ELEMS;
+    lds_bf16* const smem = (lds_bf16*)smem_raw;
+    constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;   // LDS buffer p: A slab at p * STAGE_ELEMS, B slab behind it
 
     const bf16* __restrict__ A = static_cast<const bf16*>(g.A);
     const bf16* __restrict__ B = static_cast<const bf16*>(g.B);
@@ -281,14 +278,24 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     // slab s + 1, fetched one slab ahead; operand fragments are double-buffered too, so every LDS
     // read is issued one MFMA group (16 k) before it is used.  The single barrier of a slab sits
     // before its last MFMA group: by then all fragment reads of the slab are done (its buffer may be
-    // refilled from the next slab on) and the stores of slab s + 1, issued at the top, have had three
-    // MFMA groups to land, so the first fragments of slab s + 1 are fetched behind that last group.
+    // refilled from the next slab on) and the stores of slab s + 1 have landed, so the first
+    // fragments of slab s + 1 are fetched behind that last group.  The stores of slab s + 1 (and
+    // behind each the load of slab s + 2 into the registers it frees) are spread over the first three
+    // groups: all eight wavefronts store at the same time, and a whole slab in one group keeps the LDS
+    // busy for longer than the group's MFMAs last.  A slab's LDS addresses are one add per base
+    // register (buffer offset, chosen by the slab's parity) plus compile-time instruction offsets.
     bf16x8 af[2][MT], bfg[2][NT];
-    auto read_frags = [&](int buf, const bf16* as, const bf16* bs, int kk) {
+    const lds_bf16* const a_lane = smem + fragment_lane_offset<BM, BK, A_COL>(wm * WTM, lane);
+    const lds_bf16* const b_lane = smem + A_ELEMS + fragment_lane_offset<BN, BK, B_COL>(wn * WTN, lane);
+    auto read_frags = [&](int buf, int stage, int kk) {   // stage: LDS buffer 0 / 1, a constant at every call
+        const lds_bf16* as = a_lane + stage * STAGE_ELEMS;
+        const lds_bf16* bs = b_lane + stage * STAGE_ELEMS;
+        // in the order the MFMAs of the group need them
+        af[buf][0] = read_fragment<BM, BK, A_COL>(as, 0, kk);
 #pragma unroll
-        for (int t = 0; t < MT; ++t) af[buf][t] = read_fragment<BM, BK, A_COL>(as, wm * WTM + t * 32, kk, lane);
+        for (int u = 0; u < NT; ++u) bfg[buf][u] = read_fragment<BN, BK, B_COL>(bs, u * 32, kk);
 #pragma unroll
-        for (int u = 0; u < NT; ++u) bfg[buf][u] = read_fragment<BN, BK, B_COL>(bs, wn * WTN + u * 32, kk, lane);
+        for (int t = 1; t < MT; ++t) af[buf][t] = read_fragment<BM, BK, A_COL>(as, t * 32, kk);
     };
     auto mfma_group = [&](int buf) {
 #pragma unroll
@@ -297,12 +304,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
             for (int u = 0; u < NT; ++u)
                 acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][t], bfg[buf][u], acc[t][u], 0, 0, 0);
     };
-    // Issue order of one MFMA group: the compiler is told to spread the group's LDS reads (and, in the
-    // first group of a slab, the LDS stores of the next slab and the global loads of the one after)
-    // evenly between the MFMAs instead of clumping them in front with a wait behind each.
     constexpr int NM = MT * NT;
-    constexpr int NR = MT * (A_COL ? 2 : 1) + NT * (B_COL ? 2 : 1);                                  // LDS reads per group
-    constexpr int NW = SlabLoader<BM, BK, A_COL, kThreads>::kPerThread + SlabLoader<BN, BK, B_COL, kThreads>::kPerThread;   // stores = loads per slab
+    constexpr int NR = MT * (A_COL ? 2 : 1) + NT * (B_COL ? 2 : 1);   // LDS reads per group
+    constexpr int KA = SlabLoader<BM, BK, A_COL, kThreads>::kPerThread;
+    constexpr int NW = KA + SlabLoader<BN, BK, B_COL, kThreads>::kPerThread;   // stores = loads per slab
     static_assert(BK == 64, "the pipeline below is written for four MFMA groups per slab");
 
     setup_tile(blockIdx.x);
@@ -314,63 +319,68 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[t][u][e] = 0.f;
     if (nslabs > 0) {
-        la.store(As0);
-        lb.store(Bs0);
+        la.store(smem);
+        lb.store(smem + A_ELEMS);
         if (nslabs > 1) {
             la.template load<false>(kb + BK, ke, g.tbl);
             lb.template load<REMAP == REMAP_B_K>(kb + BK, ke, g.tbl);
         }
     }
     __syncthreads();
-    if (nslabs > 0) read_frags(0, As0, Bs0, 0);
+    if (nslabs > 0) read_frags(0, 0, 0);
 
     // one slab; STORE: slab s+1 is in the loader registers and goes to the other buffer,
     // LOAD: slab s+2 exists and is fetched into the loader registers
     auto slab = [&](int s, auto store_tag, auto load_tag) {
         constexpr bool STORE = decltype(store_tag)::value, LOAD = decltype(load_tag)::value;
-        const bool odd = s & 1;
-        const bf16* as = odd ? As1 : As0;
-        const bf16* bs = odd ? Bs1 : Bs0;
-        bf16* as_next = odd ? As0 : As1;
-        bf16* bs_next = odd ? Bs0 : Bs1;
-        read_frags(1, as, bs, 16);   // ahead of the stores: LDS reads are not moved across LDS stores
-        if (STORE) {
-            la.store(as_next);
-            lb.store(bs_next);
-        }
-        if (LOAD) {
-            const int k0 = kb + (s + 2) * BK;
-            la.template load<false>(k0, ke, g.tbl);
-            lb.template load<REMAP == REMAP_B_K>(k0, ke, g.tbl);
-        }
+        const int CUR = s & 1;
+        lds_bf16* as_next = smem + (1 - CUR) * STAGE_ELEMS;
+        lds_bf16* bs_next = as_next + A_ELEMS;
+        const int k_next = kb + (s + 2) * BK;
+        auto move_third = [&](auto third_tag) {   // a third of the slab's chunks: store, then reload
+            constexpr int P = decltype(third_tag)::value;
+#pragma unroll
+            for (int c = P * NW / 3; c < (P + 1) * NW / 3; ++c) {
+                if (c < KA) {
+                    if (STORE) la.store_one(c, as_next);
+                    if (LOAD) la.template load_one<false>(c, k_next, ke, g.tbl);
+                } else {
+                    if (STORE) lb.store_one(c - KA, bs_next);
+                    if (LOAD) lb.template load_one<REMAP == REMAP_B_K>(c - KA, k_next, ke, g.tbl);
+                }
+            }
+        };
+        read_frags(1, CUR, 16);   // ahead of the stores: LDS reads are not moved across LDS stores
+        move_third(std::integral_constant<int, 0>{});
         mfma_group(0);
-        if constexpr (STORE && LOAD)
-            pace_first_group<NM, NR, NW>();
-        else
-            pace_group<NM, NR, NW, true, false, false>();
+        pace_group<NM, NR, STORE ? NW / 3 : 0>();
         __builtin_amdgcn_sched_barrier(0);   // groups are scheduled one by one
-        read_frags(0, as, bs, 32);
+        read_frags(0, CUR, 32);
+        move_third(std::integral_constant<int, 1>{});
         mfma_group(1);
-        pace_group<NM, NR, NW, true, false, false>();
+        pace_group<NM, NR, STORE ? 2 * NW / 3 - NW / 3 : 0>();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, as, bs, 48);
+        read_frags(1, CUR, 48);
+        move_third(std::integral_constant<int, 2>{});
         mfma_group(0);
-        pace_group<NM, NR, NW, true, false, false>();
+        pace_group<NM, NR, STORE ? NW - 2 * NW / 3 : 0>();
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        if (STORE) read_frags(0, as_next, bs_next, 0);
+        if (STORE) read_frags(0, 1 - CUR, 0);
         mfma_group(1);
-        pace_group<NM, NR, NW, STORE, false, false>();
+        pace_group<NM, STORE ? NR : 0, 0>();
         __builtin_amdgcn_sched_barrier(0);
     };
     {
+        constexpr std::true_type yes{};
+        constexpr std::false_type no{};
         int s = 0;
-        for (; s + 2 < nslabs; ++s) slab(s, std::true_type{}, std::true_type{});
+        for (; s + 2 < nslabs; ++s) slab(s, yes, yes);
         if (s + 1 < nslabs) {
-            slab(s, std::true_type{}, std::false_type{});
+            slab(s, yes, no);
             ++s;
         }
-        if (s < nslabs) slab(s, std::false_type{}, std::false_type{});
+        if (s < nslabs) slab(s, no, no);
     }
     __syncthreads();   // the epilogue reuses the operand buffers
     const int em0 = m0, en0 = n0, esplit = split;
