@@ -233,7 +233,33 @@ hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, long ldq, const vo
                                   int tokens, int n_full, hipStream_t s);
 
 // MFMA attention (bf16, head dimension 64, up to 256 tokens); same argument meaning as the simple launchers
+// Which (micro-batch, compacted head position) pairs take part when one launch covers several
+// micro-batches with their own op codes: bit p of live[i] / full[i] says whether the head at position p
+// is computed / is p_f in micro-batch i, which holds the images [img_end[i-1], img_end[i]).
+struct MicroMask {
+    int n;
+    int img_end[D2FT_MAX_MICRO];
+    uint64_t live[D2FT_MAX_MICRO];
+    uint64_t full[D2FT_MAX_MICRO];
+    __host__ __device__ int micro_of(int image) const {
+        int i = 0;
+        while (i + 1 < n && image >= img_end[i]) ++i;
+        return i;
+    }
+};
+
 bool attn_mfma_supported(int tokens, long ldq, long ldo);
+// with a mask: pairs that are not live get a zero O block (forward), pairs that are not p_f a zero dQKV
+// block (backward); the log-sum-exp is saved for p_f pairs
+hipError_t launch_attn_fwd_mfma_masked(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
+                                       int n_live, const MicroMask& mask, hipStream_t s);
+hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
+                                       const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
+                                       int n_full, const MicroMask& mask, hipStream_t s);
+// zero the [tokens][width] blocks (column offset position * width, row stride ld) of the pairs that are live
+// but not p_f, positions 0 .. n_pos-1
+hipError_t launch_zero_forward_only_pairs(int dtype, void* x, long ld, int batch, int tokens, int n_pos, int width,
+                                          const MicroMask& mask, hipStream_t s);
 hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
                                 int n_live, int n_full, hipStream_t s);
 hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse,

@@ -278,9 +278,18 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
     return e;
 }
 
+// bf16, head dimension 64, up to 256 tokens: the matrix-core attention kernels
+static bool attn_on_mfma(const d2ft_block_desc* d) {
+    return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && d->tokens <= 256;
+}
+
 hipError_t run_attn_fwd(const d2ft_block_desc* d, const void* qkv, long ldq, void* o, long ldo, float* lse, int batch,
-                        int tokens, int n_live, int n_full, hipStream_t s) {
+                        int tokens, int n_live, int n_full, hipStream_t s, const MicroMask* mask = nullptr) {
     g_timing.flops = 4.0 * batch * n_live * (double)tokens * tokens * 64;
+    if (mask) {   // callers pass a mask only where attn_on_mfma() holds
+        g_timing.label = "attn_fwd_mfma";
+        return launch_attn_fwd_mfma_masked(qkv, ldq, o, ldo, lse, batch, tokens, n_live, *mask, s);
+    }
     if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && attn_mfma_supported(tokens, ldq, ldo)) {
         g_timing.label = "attn_fwd_mfma";
         return launch_attn_fwd_mfma(qkv, ldq, o, ldo, lse, batch, tokens, n_live, n_full, s);
@@ -291,8 +300,13 @@ hipError_t run_attn_fwd(const d2ft_block_desc* d, const void* qkv, long ldq, voi
 
 hipError_t run_attn_bwd(const d2ft_block_desc* d, const void* qkv, long ldq, const void* o, long ldo, const float* lse,
                         const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, int batch, int tokens,
-                        int n_full, hipStream_t s) {
+                        int n_full, hipStream_t s, const MicroMask* mask = nullptr) {
     g_timing.flops = 8.0 * batch * n_full * (double)tokens * tokens * 64;
+    if (mask) {
+        g_timing.label = "attn_bwd_mfma";
+        return launch_attn_bwd_mfma_masked(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, *mask,
+                                           s);
+    }
     if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && attn_mfma_supported(tokens, ldq, ldo) &&
         (ld_do % 8) == 0 && (ld_dqkv % 8) == 0) {
         g_timing.label = "attn_bwd_mfma";
@@ -465,8 +479,10 @@ enum { PART_BOTH = 0, PART_ATTN = 1, PART_MLP = 2 };
 //   PART_ATTN: y receives x1 = x + attention residual;   PART_MLP: x is x1.
 //   sva / svm: where the attention-side / feed-forward-side fields of SavedLayout live (both are the
 //   start of the one saved buffer for PART_BOTH)
+//   mask: NULL, or the micro-batches' own codes when ops is their union (see micro_union below)
 static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
-                                  const void* x, void* y, char* sva, char* svm, void* scratch, hipStream_t st, int part) {
+                                  const void* x, void* y, char* sva, char* svm, void* scratch, hipStream_t st, int part,
+                                  const MicroMask* mask = nullptr) {
     int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
     d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
     if (cs != D2FT_OK) return cs;
@@ -504,7 +520,7 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
         // softmax attention per (image, live head); log-sum-exp kept for p_f heads only
         D2FT_TRY(run_attn_fwd(desc, sv + SL.qkv, nl * 192, sv + SL.o, nl * 64, (float*)(sv + SL.lse), s.B, s.T, nl, nf,
-                              st));
+                              st, mask));
         // x1 = x + O Wo_live^T + b_o
         GemmArgs p = gemm_base();
         fill_head_table(p.tbl, live, nl);
@@ -516,6 +532,9 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         p.residual = x; p.ldr = s.D;
         D2FT_TRY_UNTIMED(run_gemm(p, desc, st));
         x1 = p.C;
+        // the backward multiplies the saved O of the p_f positions over the whole batch: a pair that
+        // was forward-only in its micro-batch must not reach the gradient of W_o
+        if (mask) D2FT_TRY(launch_zero_forward_only_pairs(s.dtype, sv + SL.o, nl * 64, s.B, s.T, nf, 64, *mask, st));
     }
     if (part == PART_ATTN) {
         if (nl == 0) {   // x1 is x: the caller wants it in y
@@ -582,7 +601,8 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc* desc, const d2ft_block_weights
 //   PART_ATTN: dy is dx1 and may be the same buffer as dx (rows are rewritten in place)
 static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,
                                   const void* x, const void* dy, void* dx, const d2ft_block_grads* grads,
-                                  const char* sva, const char* svm, void* scratch, hipStream_t st, int half) {
+                                  const char* sva, const char* svm, void* scratch, hipStream_t st, int half,
+                                  const MicroMask* mask = nullptr) {
     int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
     d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
     if (cs != D2FT_OK) return cs;
@@ -741,7 +761,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         if (rc != D2FT_OK) return rc;
     }
     D2FT_TRY(run_attn_bwd(desc, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o, ld_do,
-                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), s.B, s.T, nf, st));
+                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), s.B, s.T, nf, st, mask));
     const void* u = sv + SL.u;
     const bool want_lora = s.r > 0 && (grads->lora_a_q || grads->lora_a_v || grads->lora_b_q || grads->lora_b_v);
     if (grads->w_qkv || want_lora) {   // G = dQKV^T u, rows in compacted order
@@ -825,6 +845,7 @@ static bool micro_ok(const d2ft_block_desc* desc, int32_t n_micro, const int32_t
 //   gated feed-forward: one whole SavedLayout per micro-batch (each micro-batch is a block call of its own)
 //   otherwise: the attention-side fields per micro-batch, then x1 of the whole batch, then the
 //   feed-forward fields of the whole batch (that half does not depend on the op codes, so it runs once)
+//   union mode (micro_union below): the plain SavedLayout of the whole batch
 struct MicroPlan {
     bool shared_mlp;
     size_t at[D2FT_MAX_MICRO];   // start of micro-batch i's fields
@@ -842,15 +863,56 @@ static MicroPlan micro_plan(const d2ft_block_desc* desc, int32_t n_micro, const 
         P.at[i] = off;
         off += P.shared_mlp ? L.x1 : L.total;
     }
+    const SavedLayout L = saved_layout(dims_of(desc));
     if (P.shared_mlp) {
-        const SavedLayout L = saved_layout(dims_of(desc));
         P.x1 = off;
         off += L.mean2 - L.x1;
         P.mlp = off;
         off += L.total - L.mean2;
     }
-    P.total = off;
+    P.total = off > L.total ? off : L.total;   // either mode fits
     return P;
+}
+
+// Union mode.  With several micro-batches on the matrix-core attention path and every micro-batch
+// keeping at least one head live, the block runs ONCE over the whole batch under the union of the
+// codes (a head is p_f if it is p_f in any micro-batch, else forward-only if it is live in any):
+// the projections then have the whole batch's rows (full tiles, one launch each) instead of a
+// fifth of them per launch.  The attention kernels take the micro-batches' own codes as a mask: a
+// pair (micro-batch, head) that is skipped gets a zero O block, a pair that is not p_f a zero dQKV
+// block and, after the output projection, a zero saved O block, so that every product over the whole
+// batch sums exactly the terms the micro-batches' own calls would (plus zeros).  The price is
+// projection FLOPs on the zero blocks.
+static bool micro_union(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images, const uint8_t* ops,
+                        uint8_t* ops_union, MicroMask* mask) {
+    if (n_micro < 2 || (desc->flags & D2FT_FLAG_GATE_FFN) || !attn_on_mfma(desc)) return false;
+    const int H = desc->heads;
+    for (int h = 0; h < H; ++h) ops_union[h] = D2FT_OP_SKIP;
+    for (int i = 0; i < n_micro; ++i) {
+        int live_i = 0;
+        for (int h = 0; h < H; ++h) {
+            const uint8_t o = ops[(size_t)i * H + h];
+            if (o != D2FT_OP_SKIP) ++live_i;
+            if (o == D2FT_OP_FULL) ops_union[h] = D2FT_OP_FULL;
+            else if (o == D2FT_OP_FWD && ops_union[h] == D2FT_OP_SKIP) ops_union[h] = D2FT_OP_FWD;
+        }
+        if (live_i == 0) return false;   // that micro-batch's rows take no projection bias: per-micro-batch calls
+    }
+    int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
+    if (compact(ops_union, H, live, &nf, &nl) != D2FT_OK) return false;
+    memset(mask, 0, sizeof(*mask));
+    mask->n = n_micro;
+    int end = 0;
+    for (int i = 0; i < n_micro; ++i) {
+        end += mb_images[i];
+        mask->img_end[i] = end;
+        for (int p = 0; p < nl; ++p) {
+            const uint8_t o = ops[(size_t)i * H + live[p]];
+            if (o != D2FT_OP_SKIP) mask->live[i] |= 1ull << p;
+            if (o == D2FT_OP_FULL) mask->full[i] |= 1ull << p;
+        }
+    }
+    return true;
 }
 
 size_t d2ft_block_saved_bytes_mb(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images) {
@@ -873,6 +935,12 @@ d2ft_status d2ft_block_fwd_mb(const d2ft_block_desc* desc, const d2ft_block_weig
     const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* sv = static_cast<char*>(saved);
+    {
+        uint8_t ops_union[D2FT_MAX_HEADS];
+        MicroMask mask;
+        if (micro_union(desc, n_micro, mb_images, ops, ops_union, &mask))
+            return block_fwd_impl(desc, w, ops_union, x, y, sv, sv, scratch, st, PART_BOTH, &mask);
+    }
     size_t img0 = 0;
     for (int i = 0; i < n_micro; ++i) {
         d2ft_block_desc d = *desc;
@@ -910,6 +978,12 @@ d2ft_status d2ft_block_bwd_mb(const d2ft_block_desc* desc, const d2ft_block_weig
     const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const char* sv = static_cast<const char*>(saved);
+    {
+        uint8_t ops_union[D2FT_MAX_HEADS];
+        MicroMask mask;
+        if (micro_union(desc, n_micro, mb_images, ops, ops_union, &mask))
+            return block_bwd_impl(desc, w, ops_union, x, dy, dx, grads, sv, sv, scratch, st, PART_BOTH, &mask);
+    }
     if (P.shared_mlp) {   // feed-forward half over the whole batch: dx <- dx1, with the caller's flags
         const SavedLayout L = saved_layout(dims_of(desc));
         uint8_t any[D2FT_MAX_HEADS];

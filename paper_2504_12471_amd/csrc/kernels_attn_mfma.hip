@@ -13,6 +13,8 @@
 // MFMA 32x32x16 bf16 layouts used throughout (h = lane / 32, c = lane % 32):
 //   operand:  row-or-column c, k-slots 8h .. 8h+7
 //   result :  column c, element e <-> row 8*(e/4) + 4h + e%4
+#include <type_traits>
+
 #include "d2ft_common.h"
 
 namespace d2ft {
@@ -116,10 +118,13 @@ constexpr int kVS = 96;   // V rows in LDS: 192 bytes (transposing reads)
 // ---------------------------------------------------------------------------
 // forward: O = softmax(Q K^T / 8) V per (image, live head); log-sum-exp saved for p_f heads
 // ---------------------------------------------------------------------------
-template <int KT>   // number of 32-token tiles
+struct WholeBatch {};   // no mask: every (image, head) pair is live, the first n_full positions are p_f
+
+template <int KT, typename Mask>   // KT: number of 32-token tiles
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
                                                             bf16* __restrict__ o, long ldo, float* __restrict__ lse,
-                                                            int tokens, int n_live, int n_full, long rows_total) {
+                                                            int tokens, int n_live, int n_full, long rows_total,
+                                                            Mask mask) {
     constexpr int TP = KT * 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* Ks = reinterpret_cast<bf16*>(smem_raw);
@@ -128,6 +133,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     const int c = lane & 31, h = lane >> 5;
     const int b = blockIdx.x / n_live, j = blockIdx.x % n_live;
     const long row0 = (long)b * tokens;
+    bool save_lse = j < n_full;
+    if constexpr (std::is_same<Mask, MicroMask>::value) {
+        const int mb = mask.micro_of(b);
+        save_lse = (mask.full[mb] >> j) & 1;
+        if (!((mask.live[mb] >> j) & 1)) {   // the head is skipped in this image's micro-batch: O = 0
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int i = threadIdx.x; i < tokens * 8; i += 256)
+                *reinterpret_cast<u32x4*>(o + (row0 + (i >> 3)) * ldo + j * 64 + (i & 7) * 8) = z;
+            return;
+        }
+    }
     const bf16* Qb = qkv + row0 * ldq + j * 192;
     load_two_tiles64<TP>(Qb + 64, Qb + 128, ldq, tokens, Ks, kKS, Vs, kVS);
     __syncthreads();
@@ -246,16 +262,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
                     pk.y = pack_bf16x2(ot[dt][4 * eg + 2] * inv, ot[dt][4 * eg + 3] * inv);
                     *reinterpret_cast<uint2*>(orow + dt * 32 + 8 * eg + 4 * h) = pk;
                 }
-            if (h == 0 && j < n_full) lse[(long)j * rows_total + row0 + q] = m * kScale + __logf(sum);
+            if (h == 0 && save_lse) lse[(long)j * rows_total + row0 + q] = m * kScale + __logf(sum);
         }
     }
 }
 
-template <int KT>
+template <int KT, typename Mask>
 hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* lse, int batch, int tokens, int n_live,
-                         int n_full, hipStream_t s) {
+                         int n_full, const Mask& mask, hipStream_t s) {
     constexpr size_t lds = (size_t)KT * 32 * (kKS + kVS) * sizeof(bf16);
-    auto kern = attn_fwd_mfma_kernel<KT>;
+    auto kern = attn_fwd_mfma_kernel<KT, Mask>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -263,7 +279,7 @@ hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* ls
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(batch * n_live), dim3(256), lds, s, qkv, ldq, o, ldo, lse, tokens, n_live, n_full,
-                       (long)batch * tokens);
+                       (long)batch * tokens, mask);
     return hipGetLastError();
 }
 
@@ -285,13 +301,14 @@ hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* ls
 constexpr int kTS = 104;   // rows that are read both ways (row-form and transposing): 208 bytes
 constexpr int kBwdWaves = 8;
 
-template <int KT>
+template <int KT, typename Mask>
 __global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
                                                                           const bf16* __restrict__ o, long ldo,
                                                                           const float* __restrict__ lse,
                                                                           const bf16* __restrict__ d_o, long ld_do,
                                                                           bf16* __restrict__ dqkv, long ld_dqkv,
-                                                                          int tokens, int n_full, long rows_total) {
+                                                                          int tokens, int n_full, long rows_total,
+                                                                          Mask mask) {
     static_assert(KT <= kBwdWaves, "one key tile per wavefront");
     constexpr int TP = KT * 32;
     constexpr int NTHR = 64 * kBwdWaves;
@@ -313,6 +330,14 @@ __global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const 
     const bf16* dOb = d_o + row0 * ld_do + j * 64;
     const bf16* Ob = o + row0 * ldo + j * 64;
     bf16* dQb = dqkv + row0 * ld_dqkv + j * 192;
+    if constexpr (std::is_same<Mask, MicroMask>::value) {
+        if (!((mask.full[mask.micro_of(b)] >> j) & 1)) {   // not p_f in this image's micro-batch: dQ = dK = dV = 0
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int i = threadIdx.x; i < tokens * 24; i += NTHR)
+                *reinterpret_cast<u32x4*>(dQb + (long)(i / 24) * ld_dqkv + (i % 24) * 8) = z;
+            return;
+        }
+    }
 
     load_two_tiles64<TP, NTHR>(Qb + 64, Qb + 128, ldq, tokens, Ks, kTS, Vs, kKS);
     for (int q = threadIdx.x; q < TP; q += NTHR) {
@@ -479,13 +504,13 @@ __global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const 
     }
 }
 
-template <int KT>
+template <int KT, typename Mask>
 hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, const float* lse, const bf16* d_o, long ld_do,
-                         bf16* dqkv, long ld_dqkv, int batch, int tokens, int n_full, hipStream_t s) {
+                         bf16* dqkv, long ld_dqkv, int batch, int tokens, int n_full, const Mask& mask, hipStream_t s) {
     constexpr int TP = KT * 32;
     constexpr size_t lds = (size_t)(TP * kTS + TP * kKS + 2 * 32 * kTS + kBwdWaves * 32 * 32) * sizeof(bf16) +
                            (size_t)(2 * TP + 4 * 64 * 32) * sizeof(float);
-    auto kern = attn_bwd_mfma_kernel<KT>;
+    auto kern = attn_bwd_mfma_kernel<KT, Mask>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -493,7 +518,7 @@ hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, con
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * kBwdWaves), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv,
-                       ld_dqkv, tokens, n_full, (long)batch * tokens);
+                       ld_dqkv, tokens, n_full, (long)batch * tokens, mask);
     return hipGetLastError();
 }
 
@@ -503,44 +528,65 @@ bool attn_mfma_supported(int tokens, long ldq, long ldo) {
     return tokens >= 1 && tokens <= 256 && (ldq % 8) == 0 && (ldo % 8) == 0;
 }
 
-hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
-                                int n_live, int n_full, hipStream_t s) {
+template <typename Mask>
+static hipError_t attn_fwd_dispatch(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
+                                    int n_live, int n_full, const Mask& mask, hipStream_t s) {
     if (n_live <= 0) return hipSuccess;
     const bf16* q = static_cast<const bf16*>(qkv);
     bf16* op = static_cast<bf16*>(o);
+#define D2FT_FWD_CASE(KT) \
+    case KT: return launch_fwd_kt<KT, Mask>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, mask, s);
     switch ((tokens + 31) / 32) {
-        case 1: return launch_fwd_kt<1>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 2: return launch_fwd_kt<2>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 3: return launch_fwd_kt<3>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 4: return launch_fwd_kt<4>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 5: return launch_fwd_kt<5>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 6: return launch_fwd_kt<6>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 7: return launch_fwd_kt<7>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
-        case 8: return launch_fwd_kt<8>(q, ldq, op, ldo, lse, batch, tokens, n_live, n_full, s);
+        D2FT_FWD_CASE(1) D2FT_FWD_CASE(2) D2FT_FWD_CASE(3) D2FT_FWD_CASE(4)
+        D2FT_FWD_CASE(5) D2FT_FWD_CASE(6) D2FT_FWD_CASE(7) D2FT_FWD_CASE(8)
         default: return hipErrorNotSupported;
     }
+#undef D2FT_FWD_CASE
+}
+
+hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
+                                int n_live, int n_full, hipStream_t s) {
+    return attn_fwd_dispatch(qkv, ldq, o, ldo, lse, batch, tokens, n_live, n_full, WholeBatch{}, s);
+}
+
+hipError_t launch_attn_fwd_mfma_masked(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
+                                       int n_live, const MicroMask& mask, hipStream_t s) {
+    return attn_fwd_dispatch(qkv, ldq, o, ldo, lse, batch, tokens, n_live, 0, mask, s);
 }
 
 }  // namespace d2ft
 
 namespace d2ft {
 
-hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse, const void* d_o,
-                                long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens, int n_full,
-                                hipStream_t s) {
+template <typename Mask>
+static hipError_t attn_bwd_dispatch(const void* qkv, long ldq, const void* o, long ldo, const float* lse, const void* d_o,
+                                    long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens, int n_full,
+                                    const Mask& mask, hipStream_t s) {
     if (n_full <= 0) return hipSuccess;
     const bf16* q = static_cast<const bf16*>(qkv);
     const bf16* op = static_cast<const bf16*>(o);
     const bf16* dop = static_cast<const bf16*>(d_o);
     bf16* dq = static_cast<bf16*>(dqkv);
 #define D2FT_BWD_CASE(KT) \
-    case KT: return launch_bwd_kt<KT>(q, ldq, op, ldo, lse, dop, ld_do, dq, ld_dqkv, batch, tokens, n_full, s);
+    case KT: return launch_bwd_kt<KT, Mask>(q, ldq, op, ldo, lse, dop, ld_do, dq, ld_dqkv, batch, tokens, n_full, mask, s);
     switch ((tokens + 31) / 32) {
         D2FT_BWD_CASE(1) D2FT_BWD_CASE(2) D2FT_BWD_CASE(3) D2FT_BWD_CASE(4)
         D2FT_BWD_CASE(5) D2FT_BWD_CASE(6) D2FT_BWD_CASE(7) D2FT_BWD_CASE(8)
         default: return hipErrorNotSupported;
     }
 #undef D2FT_BWD_CASE
+}
+
+hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse, const void* d_o,
+                                long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens, int n_full,
+                                hipStream_t s) {
+    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, WholeBatch{}, s);
+}
+
+hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
+                                       const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
+                                       int n_full, const MicroMask& mask, hipStream_t s) {
+    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, mask, s);
 }
 
 }  // namespace d2ft

@@ -353,6 +353,22 @@ __global__ __launch_bounds__(256) void zero_head_slices_kernel(HeadList heads, i
     }
 }
 
+// zero the [tokens][width] block of every (image, position) pair that is live but not p_f in the image's
+// micro-batch (width * sizeof(T) is a multiple of 16 bytes)
+template <typename T>
+__global__ __launch_bounds__(256) void zero_forward_only_pairs_kernel(T* x, long ld, int tokens, int n_pos, int width,
+                                                                      MicroMask mask) {
+    const int b = blockIdx.x / n_pos, p = blockIdx.x % n_pos;
+    const int mb = mask.micro_of(b);
+    if (!(((mask.live[mb] & ~mask.full[mb]) >> p) & 1)) return;
+    constexpr int per = 16 / sizeof(T);
+    const int chunks = width / per;
+    T* base = x + (long)b * tokens * ld + (long)p * width;
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = threadIdx.x; i < tokens * chunks; i += 256)
+        *reinterpret_cast<float4*>(base + (long)(i / chunks) * ld + (i % chunks) * per) = z;
+}
+
 // ---------------------------------------------------------------------------
 // +0.0 into the feed-forward gradient slices of the listed heads: rows [h*S, (h+1)*S) of w1 [Dm][D]
 // and of b1, columns [h*S, (h+1)*S) of w2 [D][Dm]
@@ -691,6 +707,15 @@ hipError_t launch_zero_ffn_slices(int dtype, const HeadList& heads, int slice, i
     const dim3 grid(32, heads.n), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL(zero_ffn_slices_kernel<T>, grid, block, 0, s, heads, slice, D, Dm, (T*)g_w1,
                                             (T*)g_b1, (T*)g_w2);)
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_forward_only_pairs(int dtype, void* x, long ld, int batch, int tokens, int n_pos, int width,
+                                          const MicroMask& mask, hipStream_t s) {
+    if (n_pos <= 0 || batch <= 0) return hipSuccess;
+    const dim3 grid(batch * n_pos), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(zero_forward_only_pairs_kernel<T>, grid, block, 0, s, (T*)x, ld, tokens, n_pos,
+                                            width, mask);)
     return hipGetLastError();
 }
 

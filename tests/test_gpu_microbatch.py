@@ -94,6 +94,50 @@ def test_bf16_five_micro_batches():
     run_mb(w, ops_mb, [3, 1, 2, 2, 2], seed=76, gate=True)
 
 
+# bf16 with several micro-batches, each with a live head: the block runs once under the union of the codes
+# and the attention kernels take the micro-batches' own codes as a mask.
+def test_bf16_union_of_codes_mixed():
+    w = di.Workload("mb_union", 7, 197, 384, 6, 64, 1536, 1, "bf16")
+    ops_mb = [[FULL, FWD, SKIP, FULL, FWD, SKIP],
+              [FWD, FWD, FWD, SKIP, SKIP, SKIP],       # nothing p_f in this micro-batch
+              [SKIP, FULL, FULL, FWD, SKIP, SKIP]]     # head 1: forward-only, forward-only, p_f; head 5 never live
+    g, rg = run_mb(w, ops_mb, [3, 1, 3], seed=81)
+    assert np.all(g["w_qkv"][:, 5] == 0.0) and np.all(g["w_qkv"][:, 4] == 0.0)     # never p_f
+
+
+def test_bf16_union_of_codes_without_a_full_head():
+    w = di.Workload("mb_union_fwd", 4, 100, 256, 4, 64, 512, 1, "bf16")
+    g, rg = run_mb(w, [[FWD, SKIP, SKIP, FWD], [SKIP, FWD, SKIP, SKIP]], [1, 3], seed=82)
+    for k in ("w_qkv", "b_qkv", "w_o"):
+        assert np.all(g[k] == 0.0), k
+
+
+def test_bf16_union_of_codes_ragged_tokens_and_single_images():
+    w = di.Workload("mb_union_ragged", 5, 33, 128, 2, 64, 256, 1, "bf16")
+    run_mb(w, [[FULL, SKIP], [SKIP, FULL], [FWD, FULL], [FULL, FULL], [FULL, FWD]], [1, 1, 1, 1, 1], seed=83)
+
+
+def test_bf16_union_of_codes_with_lora():
+    w = di.Workload("mb_union_lora", 6, 64, 256, 4, 64, 512, 1, "bf16", lora_rank=8, lora_scale=2.0, lora_b_zero=False)
+    run_mb(w, [[FULL, FWD, SKIP, FULL], [SKIP, FULL, FULL, FWD]], [2, 4], seed=84)
+
+
+def test_bf16_union_accumulates_into_existing_gradients():
+    from oracle import d2ft_oracle as orc
+    w = di.Workload("mb_union_acc", 4, 64, 128, 2, 64, 256, 1, "bf16")
+    rng = np.random.default_rng(85)
+    x, wt, dy = di.draw_hidden(rng, w), di.draw_block_weights(rng, w), di.draw_hidden(rng, w)
+    ops_mb, mb = [[FULL, SKIP], [FWD, FULL]], [2, 2]
+    init = {k: (None if v is None else np.asarray(rng.standard_normal(v.shape), np.float32)) for k, v in wt.items()}
+    _, _, g = gpu_block_mb(w, wt, ops_mb, mb, x, dy, 1, grads_init=init)   # D2FT_FLAG_ACCUM_GRADS
+    _, caches = orc.block_fwd_mb(wt, ops_mb, mb, x, w.head_dim, w.ln_eps, w.lora_scale)
+    _, rg = orc.block_bwd_mb(wt, caches, mb, dy)
+    for k, v in g.items():
+        if v is not None:
+            ref = np.asarray(init[k], np.float64) + rg[k]
+            assert rel_inf(v, ref) <= 2 * TOL[w.dtype], k
+
+
 def test_bad_micro_batch_sizes_are_rejected():
     import paper_2504_12471_amd as P
     w = di.WORKLOADS["vit_tiny_fp32"]
