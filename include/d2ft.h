@@ -176,13 +176,13 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc *desc, const d2ft_block_weights
  * and a subnet that is p_f in no micro-batch gets +0.0; with it set everything is added to what
  * the buffers hold.  How the work is laid out on the stream is the library's choice and does not change
  * what is computed beyond rounding order:
- *   - with D2FT_FLAG_GATE_FFN every micro-batch is a block call of its own, one after the other;
- *   - without it the feed-forward half of the block does not depend on the op codes and runs once over the
- *     whole batch; the attention half runs per micro-batch, or, when the matrix-core attention kernels
- *     apply (bf16, at most 256 tokens) and every micro-batch keeps a head live, once over the whole batch
- *     under the union of the codes, with the attention kernels masking per (micro-batch, head): skipped
- *     pairs contribute exact zeros to the projections, pairs that are not p_f exact zeros to the weight
- *     gradients.
+ *   - when the matrix-core attention kernels apply (bf16, at most 256 tokens) and every micro-batch keeps a
+ *     head live, the block runs once over the whole batch under the union of the codes, with the attention
+ *     kernels masking per (micro-batch, head): skipped pairs contribute exact zeros to the projections, pairs
+ *     that are not p_f exact zeros to the weight gradients (gated feed-forward slices likewise);
+ *   - otherwise, without D2FT_FLAG_GATE_FFN, the feed-forward half (which does not depend on the op codes)
+ *     runs once over the whole batch and the attention half per micro-batch, one after the other;
+ *   - otherwise every micro-batch is a block call of its own.
  *   n_micro    1 .. D2FT_MAX_MICRO
  *   mb_images  HOST [n_micro], each >= 1, summing to desc->batch
  *   ops        HOST [n_micro][heads]

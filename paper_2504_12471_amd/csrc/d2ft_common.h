@@ -256,10 +256,11 @@ hipError_t launch_attn_fwd_mfma_masked(const void* qkv, long ldq, void* o, long 
 hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
                                        const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
                                        int n_full, const MicroMask& mask, hipStream_t s);
-// zero the [tokens][width] blocks (column offset position * width, row stride ld) of the pairs that are live
-// but not p_f, positions 0 .. n_pos-1
-hipError_t launch_zero_forward_only_pairs(int dtype, void* x, long ld, int batch, int tokens, int n_pos, int width,
-                                          const MicroMask& mask, hipStream_t s);
+// zero the [tokens][width] blocks (column offset position * width, row stride ld; in x and, if given, x2) of
+// the pairs at positions 0 .. n_pos-1 that are skipped, or that are live but not p_f
+enum { PAIRS_SKIPPED = 0, PAIRS_FORWARD_ONLY = 1 };
+hipError_t launch_zero_pairs(int dtype, void* x, void* x2, long ld, int batch, int tokens, int n_pos, int width, int which,
+                             const MicroMask& mask, hipStream_t s);
 hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
                                 int n_live, int n_full, hipStream_t s);
 hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse,

@@ -534,7 +534,7 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         x1 = p.C;
         // the backward multiplies the saved O of the p_f positions over the whole batch: a pair that
         // was forward-only in its micro-batch must not reach the gradient of W_o
-        if (mask) D2FT_TRY(launch_zero_forward_only_pairs(s.dtype, sv + SL.o, nl * 64, s.B, s.T, nf, 64, *mask, st));
+        if (mask) D2FT_TRY(launch_zero_pairs(s.dtype, sv + SL.o, nullptr, nl * 64, s.B, s.T, nf, 64, PAIRS_FORWARD_ONLY, *mask, st));
     }
     if (part == PART_ATTN) {
         if (nl == 0) {   // x1 is x: the caller wants it in y
@@ -571,6 +571,8 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         g.bias = w->b1; g.bias_remap = gate ? 1 : 0;
         g.act = ACT_GELU; g.Z = sv + SL.z; g.ldz = n_hid;
         D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        // a subnet skipped in a micro-batch adds nothing to that micro-batch's rows
+        if (gate && mask) D2FT_TRY(launch_zero_pairs(s.dtype, sv + SL.g, sv + SL.z, n_hid, s.B, s.T, nl, slice, PAIRS_SKIPPED, *mask, st));
     }
     {   // y = x1 + g W2^T + b2
         GemmArgs g = gemm_base();
@@ -582,6 +584,9 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         g.bias = w->b2;
         g.residual = x1; g.ldr = s.D;
         D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        // the backward multiplies the saved g and GELU' of the p_f slices over the whole batch: zero what
+        // was forward-only in its micro-batch (dz = (dy W2) * GELU' is then zero there too)
+        if (gate && mask) D2FT_TRY(launch_zero_pairs(s.dtype, sv + SL.g, sv + SL.z, n_hid, s.B, s.T, nf, slice, PAIRS_FORWARD_ONLY, *mask, st));
     }
     return D2FT_OK;
 }
@@ -881,11 +886,12 @@ static MicroPlan micro_plan(const d2ft_block_desc* desc, int32_t n_micro, const 
 // fifth of them per launch.  The attention kernels take the micro-batches' own codes as a mask: a
 // pair (micro-batch, head) that is skipped gets a zero O block, a pair that is not p_f a zero dQKV
 // block and, after the output projection, a zero saved O block, so that every product over the whole
-// batch sums exactly the terms the micro-batches' own calls would (plus zeros).  The price is
-// projection FLOPs on the zero blocks.
+// batch sums exactly the terms the micro-batches' own calls would (plus zeros).  Gated feed-forward
+// slices are handled the same way: g and GELU' blocks of skipped pairs are zeroed behind FC1, those of
+// forward-only pairs behind FC2.  The price is projection FLOPs on the zero blocks.
 static bool micro_union(const d2ft_block_desc* desc, int32_t n_micro, const int32_t* mb_images, const uint8_t* ops,
                         uint8_t* ops_union, MicroMask* mask) {
-    if (n_micro < 2 || (desc->flags & D2FT_FLAG_GATE_FFN) || !attn_on_mfma(desc)) return false;
+    if (n_micro < 2 || !attn_on_mfma(desc)) return false;
     const int H = desc->heads;
     for (int h = 0; h < H; ++h) ops_union[h] = D2FT_OP_SKIP;
     for (int i = 0; i < n_micro; ++i) {

@@ -353,20 +353,25 @@ __global__ __launch_bounds__(256) void zero_head_slices_kernel(HeadList heads, i
     }
 }
 
-// zero the [tokens][width] block of every (image, position) pair that is live but not p_f in the image's
-// micro-batch (width * sizeof(T) is a multiple of 16 bytes)
+// zero the [tokens][width] block (in x, and in x2 if given) of every (image, position) pair that is
+// skipped (which = PAIRS_SKIPPED) or live but not p_f (PAIRS_FORWARD_ONLY) in the image's micro-batch;
+// width * sizeof(T) is a multiple of 16 bytes
 template <typename T>
-__global__ __launch_bounds__(256) void zero_forward_only_pairs_kernel(T* x, long ld, int tokens, int n_pos, int width,
-                                                                      MicroMask mask) {
+__global__ __launch_bounds__(256) void zero_pairs_kernel(T* x, T* x2, long ld, int tokens, int n_pos, int width, int which,
+                                                         MicroMask mask) {
     const int b = blockIdx.x / n_pos, p = blockIdx.x % n_pos;
     const int mb = mask.micro_of(b);
-    if (!(((mask.live[mb] & ~mask.full[mb]) >> p) & 1)) return;
+    const uint64_t sel = (which == PAIRS_SKIPPED) ? ~mask.live[mb] : (mask.live[mb] & ~mask.full[mb]);
+    if (!((sel >> p) & 1)) return;
     constexpr int per = 16 / sizeof(T);
     const int chunks = width / per;
-    T* base = x + (long)b * tokens * ld + (long)p * width;
+    const long base = (long)b * tokens * ld + (long)p * width;
     const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i = threadIdx.x; i < tokens * chunks; i += 256)
-        *reinterpret_cast<float4*>(base + (long)(i / chunks) * ld + (i % chunks) * per) = z;
+    for (int i = threadIdx.x; i < tokens * chunks; i += 256) {
+        const long off = base + (long)(i / chunks) * ld + (i % chunks) * per;
+        *reinterpret_cast<float4*>(x + off) = z;
+        if (x2) *reinterpret_cast<float4*>(x2 + off) = z;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -710,12 +715,12 @@ hipError_t launch_zero_ffn_slices(int dtype, const HeadList& heads, int slice, i
     return hipGetLastError();
 }
 
-hipError_t launch_zero_forward_only_pairs(int dtype, void* x, long ld, int batch, int tokens, int n_pos, int width,
-                                          const MicroMask& mask, hipStream_t s) {
+hipError_t launch_zero_pairs(int dtype, void* x, void* x2, long ld, int batch, int tokens, int n_pos, int width, int which,
+                             const MicroMask& mask, hipStream_t s) {
     if (n_pos <= 0 || batch <= 0) return hipSuccess;
     const dim3 grid(batch * n_pos), block(256);
-    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(zero_forward_only_pairs_kernel<T>, grid, block, 0, s, (T*)x, ld, tokens, n_pos,
-                                            width, mask);)
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(zero_pairs_kernel<T>, grid, block, 0, s, (T*)x, (T*)x2, ld, tokens, n_pos, width,
+                                            which, mask);)
     return hipGetLastError();
 }
 

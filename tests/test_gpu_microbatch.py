@@ -105,6 +105,17 @@ def test_bf16_union_of_codes_mixed():
     assert np.all(g["w_qkv"][:, 5] == 0.0) and np.all(g["w_qkv"][:, 4] == 0.0)     # never p_f
 
 
+def test_bf16_union_of_codes_gated_feed_forward():
+    w = di.Workload("mb_union_gate", 6, 100, 384, 6, 64, 1536, 1, "bf16")
+    ops_mb = [[FULL, FWD, SKIP, FULL, FWD, SKIP],
+              [FWD, SKIP, FWD, SKIP, SKIP, SKIP],
+              [SKIP, FULL, FULL, FWD, SKIP, SKIP]]
+    g, rg = run_mb(w, ops_mb, [2, 1, 3], seed=86, gate=True)
+    S = w.mlp_hidden // w.heads
+    for h in (4, 5):   # never p_f: exact zeros in the slice's gradients
+        assert np.all(g["w1"][h * S:(h + 1) * S] == 0.0) and np.all(g["w2"][:, h * S:(h + 1) * S] == 0.0)
+
+
 def test_bf16_union_of_codes_without_a_full_head():
     w = di.Workload("mb_union_fwd", 4, 100, 256, 4, 64, 512, 1, "bf16")
     g, rg = run_mb(w, [[FWD, SKIP, SKIP, FWD], [SKIP, FWD, SKIP, SKIP]], [1, 3], seed=82)
