@@ -63,8 +63,14 @@ struct SlabLoader {
     static constexpr int kPerThread = kChunks / kThreads;
     static_assert(kChunks % kThreads == 0, "slab must divide over the workgroup");
     static_assert(BK == 64, "the k remap is resolved once per slab, which needs 64-aligned slabs");
+    // COL form with the thread count a multiple of the chunks per k row: a thread's chunks all have the
+    // same index part and k rows a fixed distance apart, so one offset register serves them all and the
+    // distance goes into the load's scalar offset
+    static constexpr bool kOneBase = COL && (kThreads % (BI / 8) == 0);
+    static constexpr int kBases = kOneBase ? 1 : kPerThread;
+    static constexpr int kRowStep = kThreads / (BI / 8);   // kOneBase: k rows between a thread's consecutive chunks
     u32x4 v[kPerThread];
-    uint32_t base[kPerThread];   // byte offset of the chunk within slab 0, kOutside if its index is outside
+    uint32_t base[kBases];   // byte offset of the chunk within slab 0, kOutside if its index is outside
     __amdgpu_buffer_rsrc_t rsrc;
     uint32_t sk_bytes;
 
@@ -78,7 +84,7 @@ struct SlabLoader {
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(p), 0, kBufBytes, 0x00020000);
         sk_bytes = (uint32_t)s_k * 2u;
 #pragma unroll
-        for (int c = 0; c < kPerThread; ++c) {
+        for (int c = 0; c < kBases; ++c) {
             const int id = threadIdx.x + c * kThreads;
             const int i = i0 + (COL ? (id % (BI / 8)) * 8 : id / (BK / 8));
             const int is = REMAP_I ? tbl(min(i, I - 1)) : i;
@@ -88,17 +94,20 @@ struct SlabLoader {
     }
 
     // slab starting at k0 (a multiple of 64 counted from 0), valid k < k_end; chunk c alone, or all chunks
-    template <bool REMAP_K>
+    // TAIL: the slab may reach beyond k_end (K is not a multiple of 64), so every chunk checks its k
+    template <bool REMAP_K, bool TAIL>
     __device__ __forceinline__ void load_one(int c, int k0, int k_end, const Remap64& tbl) {
         const uint32_t kstart = REMAP_K ? (uint32_t)tbl.start[k0 >> 6] : (uint32_t)k0;
-        const uint32_t koff = kstart * sk_bytes;   // uniform over the workgroup
-        const uint32_t off = (k_local(c) < k_end - k0) ? base[c] : kOutside;
+        uint32_t koff = kstart * sk_bytes;   // uniform over the workgroup
+        if constexpr (kOneBase) koff += (uint32_t)(c * kRowStep) * sk_bytes;
+        const uint32_t mine = base[kOneBase ? 0 : c];
+        const uint32_t off = (!TAIL || k_local(c) < k_end - k0) ? mine : kOutside;
         v[c] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, koff, 0);
     }
-    template <bool REMAP_K>
+    template <bool REMAP_K, bool TAIL>
     __device__ __forceinline__ void load(int k0, int k_end, const Remap64& tbl) {
 #pragma unroll
-        for (int c = 0; c < kPerThread; ++c) load_one<REMAP_K>(c, k0, k_end, tbl);
+        for (int c = 0; c < kPerThread; ++c) load_one<REMAP_K, TAIL>(c, k0, k_end, tbl);
     }
 
     __device__ __forceinline__ void store_one(int c, lds_bf16* lds) const {
@@ -223,7 +232,7 @@ __device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, i
     tn = in_group / gsize;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
@@ -269,8 +278,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         lb.template init<REMAP == REMAP_B_N>(B, g.b_cs, g.b_rs, n0, g.N, g.tbl);
         nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
         if (nslabs > 0) {
-            la.template load<false>(kb, ke, g.tbl);
-            lb.template load<REMAP == REMAP_B_K>(kb, ke, g.tbl);
+            la.template load<false, KTAIL>(kb, ke, g.tbl);
+            lb.template load<REMAP == REMAP_B_K, KTAIL>(kb, ke, g.tbl);
         }
     };
 
@@ -322,8 +331,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         la.store(smem);
         lb.store(smem + A_ELEMS);
         if (nslabs > 1) {
-            la.template load<false>(kb + BK, ke, g.tbl);
-            lb.template load<REMAP == REMAP_B_K>(kb + BK, ke, g.tbl);
+            la.template load<false, KTAIL>(kb + BK, ke, g.tbl);
+            lb.template load<REMAP == REMAP_B_K, KTAIL>(kb + BK, ke, g.tbl);
         }
     }
     __syncthreads();
@@ -343,10 +352,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
             for (int c = P * NW / 3; c < (P + 1) * NW / 3; ++c) {
                 if (c < KA) {
                     if (STORE) la.store_one(c, as_next);
-                    if (LOAD) la.template load_one<false>(c, k_next, ke, g.tbl);
+                    if (LOAD) la.template load_one<false, KTAIL>(c, k_next, ke, g.tbl);
                 } else {
                     if (STORE) lb.store_one(c - KA, bs_next);
-                    if (LOAD) lb.template load_one<REMAP == REMAP_B_K>(c - KA, k_next, ke, g.tbl);
+                    if (LOAD) lb.template load_one<REMAP == REMAP_B_K, KTAIL>(c - KA, k_next, ke, g.tbl);
                 }
             }
         };
@@ -478,10 +487,10 @@ constexpr size_t lds_bytes() {
     return slabs > stage ? slabs : stage;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, A_COL, B_COL>();
-    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP>;
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, KTAIL>;
     static int resident = 0;   // per instantiation: workgroups the chip holds at once, a multiple of 8
     if (resident == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -502,12 +511,19 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+// K a multiple of 64 (every shape of the model): the slab loads carry no per-chunk k check
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
+hipError_t launch_tail(const GemmArgs& g, hipStream_t s) {
+    if (g.K % BK) return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, true>(g, s);
+    return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, false>(g, s);
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 hipError_t launch_remap(const GemmArgs& g, hipStream_t s) {
     switch (g.remap) {
-        case REMAP_B_N: return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N>(g, s);
-        case REMAP_B_K: return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_K>(g, s);
-        default: return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE>(g, s);
+        case REMAP_B_N: return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N>(g, s);
+        case REMAP_B_K: return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_K>(g, s);
+        default: return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE>(g, s);
     }
 }
 
@@ -580,13 +596,14 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
     // the instantiation's name as a profiler prints it, so timing records and kernel traces can be matched
     const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
     const int tile = pick_tile(g);
-    static char names[4][3][3][64];
-    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)];
+    const bool tail = (g.K % 64) != 0;
+    static char names[4][3][3][2][72];
+    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail];
     if (!name[0]) {
         const int bm = tile == 0 ? 128 : (tile == 3 ? 192 : 256), bn = tile == 0 ? 128 : 256;
-        snprintf(name, sizeof(names[0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d>", bm, bn, tile == 0 ? 2 : 4,
-                 a_col ? "true" : "false", b_col ? "true" : "false",
-                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0));
+        snprintf(name, sizeof(names[0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s>", bm, bn,
+                 tile == 0 ? 2 : 4, a_col ? "true" : "false", b_col ? "true" : "false",
+                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false");
     }
     return name;
 }
