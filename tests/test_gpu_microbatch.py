@@ -149,6 +149,17 @@ def test_bf16_union_accumulates_into_existing_gradients():
             assert rel_inf(v, ref) <= 2 * TOL[w.dtype], k
 
 
+def test_bf16_union_of_codes_maximum_heads_and_micro_batches():
+    """64 heads (bit 63 of the per-micro-batch masks) and one image per micro-batch at 256 tokens."""
+    w = di.Workload("mb_union_h64", 3, 40, 64, 64, 64, 64, 1, "bf16")
+    rng = np.random.default_rng(87)
+    ops_mb = [list(rng.choice([FULL, FWD, SKIP], size=64)) for _ in range(3)]
+    ops_mb[0][63], ops_mb[1][63], ops_mb[2][63] = FULL, SKIP, FWD
+    run_mb(w, ops_mb, [1, 1, 1], seed=87)
+    w2 = di.Workload("mb_union_t256", 2, 256, 128, 2, 64, 256, 1, "bf16")
+    run_mb(w2, [[FULL, SKIP], [FWD, FULL]], [1, 1], seed=88)
+
+
 def test_bad_micro_batch_sizes_are_rejected():
     import paper_2504_12471_amd as P
     w = di.WORKLOADS["vit_tiny_fp32"]
