@@ -85,7 +85,7 @@ def main() -> int:
                     help="also run one plain 256 MiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (one device's head share, no collectives); --gpus must be 1",
+        print("bench.py: the library runs on ONE GPU (one device's head share, no collectives); --gpus must be 1",
               file=sys.stderr)
         return 2
 
