@@ -238,6 +238,7 @@ hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, long ldq, const vo
 // is computed / is p_f in micro-batch i, which holds the images [img_end[i-1], img_end[i]).
 struct MicroMask {
     int n;
+    int n_live_pos, n_full_pos;   // positions of the union layout: live ones, and its p_f prefix
     int img_end[D2FT_MAX_MICRO];
     uint64_t live[D2FT_MAX_MICRO];
     uint64_t full[D2FT_MAX_MICRO];
@@ -250,7 +251,10 @@ struct MicroMask {
 
 bool attn_mfma_supported(int tokens, long ldq, long ldo);
 // with a mask: pairs that are not live get a zero O block (forward), pairs that are not p_f a zero dQKV
-// block (backward); the log-sum-exp is saved for p_f pairs
+// block (backward); the log-sum-exp is saved for p_f pairs.  The grid has one workgroup per image and
+// "slot" (as many slots as the busiest micro-batch has pairs that take part): slot s of an image works
+// on its micro-batch's s-th such pair, and the zero blocks are dealt round-robin over the slots, so no
+// workgroup exists only to write zeros.
 hipError_t launch_attn_fwd_mfma_masked(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
                                        int n_live, const MicroMask& mask, hipStream_t s);
 hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,

@@ -908,6 +908,8 @@ static bool micro_union(const d2ft_block_desc* desc, int32_t n_micro, const int3
     if (compact(ops_union, H, live, &nf, &nl) != D2FT_OK) return false;
     memset(mask, 0, sizeof(*mask));
     mask->n = n_micro;
+    mask->n_live_pos = nl;
+    mask->n_full_pos = nf;
     int end = 0;
     for (int i = 0; i < n_micro; ++i) {
         end += mb_images[i];

@@ -131,18 +131,27 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     bf16* Vs = Ks + TP * kKS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
-    const int b = blockIdx.x / n_live, j = blockIdx.x % n_live;
+    const int b = blockIdx.x / n_live;   // with a mask n_live is the number of slots per image
+    int j = blockIdx.x % n_live;
     const long row0 = (long)b * tokens;
     bool save_lse = j < n_full;
     if constexpr (std::is_same<Mask, MicroMask>::value) {
-        const int mb = mask.micro_of(b);
+        const int mb = mask.micro_of(b), slot = j;
+        const uint64_t live = mask.live[mb];
+        const uint64_t skipped = ~live & (mask.n_live_pos >= 64 ? ~0ull : ((1ull << mask.n_live_pos) - 1ull));
+        int r = 0;
+        for (uint64_t m = skipped; m; m &= m - 1, ++r)   // heads skipped in this image's micro-batch: O = 0
+            if (r % n_live == slot) {
+                const int p = __builtin_ctzll(m);
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                for (int i = threadIdx.x; i < tokens * 8; i += 256)
+                    *reinterpret_cast<u32x4*>(o + (row0 + (i >> 3)) * ldo + p * 64 + (i & 7) * 8) = z;
+            }
+        if (slot >= __builtin_popcountll(live)) return;
+        uint64_t m = live;
+        for (int t = 0; t < slot; ++t) m &= m - 1;
+        j = __builtin_ctzll(m);   // this slot's live head
         save_lse = (mask.full[mb] >> j) & 1;
-        if (!((mask.live[mb] >> j) & 1)) {   // the head is skipped in this image's micro-batch: O = 0
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = threadIdx.x; i < tokens * 8; i += 256)
-                *reinterpret_cast<u32x4*>(o + (row0 + (i >> 3)) * ldo + j * 64 + (i & 7) * 8) = z;
-            return;
-        }
     }
     const bf16* Qb = qkv + row0 * ldq + j * 192;
     load_two_tiles64<TP>(Qb + 64, Qb + 128, ldq, tokens, Ks, kKS, Vs, kVS);
@@ -324,20 +333,30 @@ __global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
     bf16* dSs = dSs_all + wave * 32 * 32;
-    const int b = blockIdx.x / n_full, j = blockIdx.x % n_full;
+    const int b = blockIdx.x / n_full;   // with a mask n_full is the number of slots per image
+    int j = blockIdx.x % n_full;
     const long row0 = (long)b * tokens;
+    if constexpr (std::is_same<Mask, MicroMask>::value) {
+        const int mb = mask.micro_of(b), slot = j;
+        const uint64_t full = mask.full[mb];
+        const uint64_t rest = ~full & (mask.n_full_pos >= 64 ? ~0ull : ((1ull << mask.n_full_pos) - 1ull));
+        int r = 0;
+        for (uint64_t m = rest; m; m &= m - 1, ++r)   // not p_f in this image's micro-batch: dQ = dK = dV = 0
+            if (r % n_full == slot) {
+                bf16* zb = dqkv + row0 * ld_dqkv + __builtin_ctzll(m) * 192;
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                for (int i = threadIdx.x; i < tokens * 24; i += NTHR)
+                    *reinterpret_cast<u32x4*>(zb + (long)(i / 24) * ld_dqkv + (i % 24) * 8) = z;
+            }
+        if (slot >= __builtin_popcountll(full)) return;
+        uint64_t m = full;
+        for (int t = 0; t < slot; ++t) m &= m - 1;
+        j = __builtin_ctzll(m);   // this slot's p_f head
+    }
     const bf16* Qb = qkv + row0 * ldq + j * 192;
     const bf16* dOb = d_o + row0 * ld_do + j * 64;
     const bf16* Ob = o + row0 * ldo + j * 64;
     bf16* dQb = dqkv + row0 * ld_dqkv + j * 192;
-    if constexpr (std::is_same<Mask, MicroMask>::value) {
-        if (!((mask.full[mask.micro_of(b)] >> j) & 1)) {   // not p_f in this image's micro-batch: dQ = dK = dV = 0
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = threadIdx.x; i < tokens * 24; i += NTHR)
-                *reinterpret_cast<u32x4*>(dQb + (long)(i / 24) * ld_dqkv + (i % 24) * 8) = z;
-            return;
-        }
-    }
 
     load_two_tiles64<TP, NTHR>(Qb + 64, Qb + 128, ldq, tokens, Ks, kTS, Vs, kKS);
     for (int q = threadIdx.x; q < TP; q += NTHR) {
@@ -549,9 +568,20 @@ hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, fl
     return attn_fwd_dispatch(qkv, ldq, o, ldo, lse, batch, tokens, n_live, n_full, WholeBatch{}, s);
 }
 
+static int busiest(const uint64_t* sel, int n) {   // most pairs that take part in one micro-batch
+    int slots = 0;
+    for (int i = 0; i < n; ++i) {
+        const int c = __builtin_popcountll(sel[i]);
+        slots = c > slots ? c : slots;
+    }
+    return slots;
+}
+
 hipError_t launch_attn_fwd_mfma_masked(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
                                        int n_live, const MicroMask& mask, hipStream_t s) {
-    return attn_fwd_dispatch(qkv, ldq, o, ldo, lse, batch, tokens, n_live, 0, mask, s);
+    if (n_live != mask.n_live_pos) return hipErrorInvalidValue;
+    const int slots = busiest(mask.live, mask.n);
+    return attn_fwd_dispatch(qkv, ldq, o, ldo, lse, batch, tokens, slots > 0 ? slots : 1, 0, mask, s);
 }
 
 }  // namespace d2ft
@@ -586,7 +616,10 @@ hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long l
 hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
                                        const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
                                        int n_full, const MicroMask& mask, hipStream_t s) {
-    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, mask, s);
+    if (n_full != mask.n_full_pos) return hipErrorInvalidValue;
+    if (n_full <= 0) return hipSuccess;
+    const int slots = busiest(mask.full, mask.n);
+    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, slots > 0 ? slots : 1, mask, s);
 }
 
 }  // namespace d2ft
