@@ -91,3 +91,26 @@ def test_two_block_stack_full_size():
             errs[f"d{k}[{l}]"] = rel_inf(st.grads[l][k].float().cpu().numpy(), rgrads[l][k])
     print("[two-block stack full size] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
     assert all(v <= 2e-2 for v in errs.values()), errs
+
+
+@pytest.mark.parametrize("workload", ["vit_b16", "vit_b16_ffn"])
+def test_micro_batched_block_full_size(workload):
+    """The benchmark's --micro 5 configuration (13/13/13/13/12 images, one code per (subnet, micro-batch))."""
+    from oracle import d2ft_oracle as orc
+    from test_gpu_microbatch import gpu_block_mb
+    from helpers import FLAG_GATE_FFN
+    w = di.WORKLOADS[workload]
+    wb, x, wt, dy = one_block(w, seed=5)
+    mb = [13, 13, 13, 13, 12]
+    ops_mb = di.exact_count_masks(np.random.default_rng(6), 5, w.heads, 0.6, 0.2, 0.2)
+    assert all((o != di.OP_SKIP).any() for o in ops_mb)
+    ops_mb = [list(o) for o in ops_mb]
+    y, dx, g = gpu_block_mb(wb, wt, ops_mb, mb, x, dy, FLAG_GATE_FFN if w.gate_ffn else 0)
+    ry, caches = orc.block_fwd_mb(wt, ops_mb, mb, x, w.head_dim, w.ln_eps, w.lora_scale, gate_ffn=w.gate_ffn)
+    rdx, rg = orc.block_bwd_mb(wt, caches, mb, dy)
+    errs = {"y": rel_inf(y, ry), "dx": rel_inf(dx, rdx)}
+    for k in BASE_FIELDS:
+        if g.get(k) is not None:
+            errs["d" + k] = rel_inf(g[k], rg[k])
+    print(f"[{w.name} full size, 5 micro-batches] " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= TOL[w.dtype] for v in errs.values()), errs
