@@ -11,9 +11,12 @@ two-layer feed-forward network).  The paper's datasets are replaced by
 N(0,1) token batches: throughput and numerics of the block do not depend on
 pixel content.
 
-Draw order for one workload (one numpy ``default_rng(seed)`` stream):
-  x, then for each block its weights in the order of ``WEIGHT_FIELDS``, then
-  dy, then the mask permutation (or the two utility arrays).
+Draw order for one workload: one numpy ``default_rng(seed)`` stream gives x,
+then for each block its weights in the order of ``WEIGHT_FIELDS``, then dy.
+The op-code mask (its permutation, or the two utility arrays of the knapsack)
+comes from a stream of its own, ``default_rng([seed, MASK_STREAM])``, so that
+it does not depend on the batch size or on any other shape: a test that draws a
+smaller batch gets the same op codes as the benchmark.
 """
 from __future__ import annotations
 
@@ -218,23 +221,32 @@ class StackInputs:
     knapsack: Optional[KnapsackInputs] = None
 
 
+MASK_STREAM = 0x6D61736B   # second word of the seed sequence of the op-code stream
+
+
+def draw_ops(w: Workload, seed: int = 0) -> Tuple[Optional[np.ndarray], Optional[KnapsackInputs]]:
+    """The workload's op codes [blocks, heads] (or, for a knapsack recipe, the selection's inputs), from
+    their own seeded stream: they depend on blocks, heads and the recipe only."""
+    rng = np.random.default_rng([seed, MASK_STREAM])
+    kind = w.mask[0]
+    if kind == "fixed":
+        ops = np.tile(np.asarray(w.mask[1], dtype=np.uint8), (w.blocks, 1))
+        assert ops.shape[1] == w.heads
+        return ops, None
+    if kind == "counts":
+        return exact_count_masks(rng, w.blocks, w.heads, *w.mask[1:]), None
+    if kind == "knapsack":
+        return None, draw_knapsack_inputs(rng, 1, w.blocks * w.heads, 1, 2, w.mask[1])
+    raise ValueError(kind)
+
+
 def draw_stack(w: Workload, seed: int = 0) -> StackInputs:
     """All tensors of one workload, in the documented draw order."""
     rng = np.random.default_rng(seed)
     x = draw_hidden(rng, w)
     weights = [draw_block_weights(rng, w) for _ in range(w.blocks)]
     dy = draw_hidden(rng, w)
-    kind = w.mask[0]
-    ops, ks = None, None
-    if kind == "fixed":
-        ops = np.tile(np.asarray(w.mask[1], dtype=np.uint8), (w.blocks, 1))
-        assert ops.shape[1] == w.heads
-    elif kind == "counts":
-        ops = exact_count_masks(rng, w.blocks, w.heads, *w.mask[1:])
-    elif kind == "knapsack":
-        ks = draw_knapsack_inputs(rng, 1, w.blocks * w.heads, 1, 2, w.mask[1])
-    else:
-        raise ValueError(kind)
+    ops, ks = draw_ops(w, seed)
     return StackInputs(w, x, weights, dy, ops, ks)
 
 

@@ -541,8 +541,6 @@ inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
 
-int g_gemm_tile_override = 0;   // development aid: 0 = heuristic, 1 = 256x256, 2 = 128x128, 3 = 192x256
-
 bool gemm_mfma_supported(const GemmArgs& g) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return false;
     const bool a_row = (g.a_cs == 1), a_col = (g.a_rs == 1);
@@ -582,7 +580,6 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 // idle, down to about 100 workgroups; when its grid is under one round of the chip's 256 CUs, the
 // 192-row tile spreads the same work over more of them.
 static int pick_tile(const GemmArgs& g) {
-    if (g_gemm_tile_override) return g_gemm_tile_override == 2 ? 0 : g_gemm_tile_override;
     if (g.tile_hint) return g.tile_hint == 2 ? 0 : g.tile_hint;
     const long tn = (g.N + 255) / 256, splits = g.partial ? g.splits : 1;
     const long big = (long)((g.M + 255) / 256) * tn * splits;
