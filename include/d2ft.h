@@ -221,6 +221,23 @@ d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items,
                                  uint8_t *ops_out, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
 
+/* d2ft_select_knapsack for callers that cannot allocate device memory (code that runs where hipMalloc is
+ * not allowed: tight serving loops, harnesses that forbid allocation, set-up under which a workspace cannot
+ * be obtained).  Same arguments, results and errors as d2ft_select_knapsack, without the workspace: the DP
+ * tables live in a device array that is part of the library image, D2FT_KNAPSACK_STATIC_BYTES long, which
+ * every GPU the library runs on holds until the process ends.  The call makes no allocation of its own.
+ * A problem whose d2ft_knapsack_workspace_bytes(...) exceeds that size is refused with D2FT_ESHAPE before
+ * any device work.  All calls on one GPU share the one array: calls that overlap in time on the same GPU
+ * (from several threads or streams) race and must be serialised by the caller; consecutive calls need no
+ * clean-up in between.  d2ft_knapsack_static_bytes() returns the array's size. */
+#define D2FT_KNAPSACK_STATIC_BYTES (4u << 20)
+size_t d2ft_knapsack_static_bytes(void);
+d2ft_status d2ft_select_knapsack_static(int32_t n_knapsacks, int32_t n_items,
+                                        const double *score_full, const double *score_fwd,
+                                        const int32_t *cost_fwd, const int32_t *cost_bwd,
+                                        const int32_t *cap_full, const int32_t *cap_fwd,
+                                        uint8_t *ops_out, void *hip_stream);
+
 /* Contribution scores of the subnets of one block (Sec. II-B, contribution scores): for every
  * head h, over the tensor slices that belong to that subnet alone - Q/K/V weight rows and
  * biases, output-projection columns, LoRA adapters and, with D2FT_FLAG_GATE_FFN, the head's

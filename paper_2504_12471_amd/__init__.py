@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     d2ft_patch_embed_bwd, d2ft_patch_embed_fwd,
     d2ft_block_bwd, d2ft_block_bwd_mb, d2ft_block_fwd, d2ft_block_fwd_mb, d2ft_block_saved_bytes,
     d2ft_block_saved_bytes_mb, d2ft_block_scratch_bytes, d2ft_compact_heads,
-    d2ft_knapsack_workspace_bytes, d2ft_select_knapsack, d2ft_sgd_step, d2ft_status_string, d2ft_subnet_scores, d2ft_timing_enable, d2ft_timing_read)
+    d2ft_knapsack_static_bytes, d2ft_knapsack_workspace_bytes, d2ft_select_knapsack, d2ft_select_knapsack_static,
+    d2ft_sgd_step, d2ft_status_string, d2ft_subnet_scores, d2ft_timing_enable, d2ft_timing_read)
 from .stack import BlockStack, make_desc, to_device, torch_dtype  # noqa: F401

@@ -76,6 +76,11 @@ _lib.d2ft_knapsack_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_void_p,
 _lib.d2ft_select_knapsack.restype = C.c_int
 _lib.d2ft_select_knapsack.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.d2ft_knapsack_static_bytes.restype = C.c_size_t
+_lib.d2ft_knapsack_static_bytes.argtypes = []
+_lib.d2ft_select_knapsack_static.restype = C.c_int
+_lib.d2ft_select_knapsack_static.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 
 
 _lib.d2ft_scores_workspace_bytes.restype = C.c_size_t
@@ -257,6 +262,29 @@ def d2ft_select_knapsack(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, ca
     return out
 
 
+def d2ft_knapsack_static_bytes() -> int:
+    return int(_lib.d2ft_knapsack_static_bytes())
+
+
+def d2ft_select_knapsack_static(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, cap_fwd,
+                                stream: Optional[torch.cuda.Stream] = None) -> np.ndarray:
+    """d2ft_select_knapsack on the library's own fixed device array; nothing is allocated on the device."""
+    sf = np.ascontiguousarray(score_full, dtype=np.float64)
+    so = np.ascontiguousarray(score_fwd, dtype=np.float64)
+    if sf.ndim != 2 or sf.shape != so.shape:
+        raise ValueError("scores must be two [n_knapsacks, n_items] arrays")
+    K, n = sf.shape
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (cost_fwd, cost_bwd, cap_full, cap_fwd)]
+    if any(a.shape != (K,) for a in arrs):
+        raise ValueError("costs and capacities must have one entry per knapsack")
+    cf, cb, capf, capo = arrs
+    out = np.zeros((K, n), dtype=np.uint8)
+    st = _lib.d2ft_select_knapsack_static(K, n, sf.ctypes.data, so.ctypes.data, cf.ctypes.data, cb.ctypes.data,
+                                          capf.ctypes.data, capo.ctypes.data, out.ctypes.data, _stream_ptr(stream))
+    _check(st, "d2ft_select_knapsack_static")
+    return out
+
+
 def d2ft_subnet_scores(desc: BlockDesc, tensors: Dict[str, Optional[torch.Tensor]], kind: int,
                        workspace: Optional[torch.Tensor] = None,
                        stream: Optional[torch.cuda.Stream] = None) -> np.ndarray:
@@ -352,7 +380,8 @@ def exported_symbols():
     """Names this binding resolves in the shared library (used by the load test)."""
     return ["d2ft_status_string", "d2ft_block_saved_bytes", "d2ft_block_scratch_bytes", "d2ft_compact_heads",
             "d2ft_block_fwd", "d2ft_block_bwd", "d2ft_block_saved_bytes_mb", "d2ft_block_fwd_mb", "d2ft_block_bwd_mb",
-            "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack",
+            "d2ft_knapsack_workspace_bytes", "d2ft_select_knapsack", "d2ft_knapsack_static_bytes",
+            "d2ft_select_knapsack_static",
             "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_sgd_step", "d2ft_embed_saved_bytes",
             "d2ft_embed_scratch_bytes", "d2ft_patch_embed_fwd", "d2ft_patch_embed_bwd", "d2ft_head_scratch_bytes",
             "d2ft_classifier_fwd_bwd", "d2ft_timing_enable", "d2ft_timing_read"]

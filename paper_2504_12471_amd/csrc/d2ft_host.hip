@@ -1341,10 +1341,11 @@ size_t d2ft_knapsack_workspace_bytes(int32_t n_knapsacks, int32_t n_items, const
     return total;
 }
 
-d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items, const double* score_full,
-                                 const double* score_fwd, const int32_t* cost_fwd, const int32_t* cost_bwd,
-                                 const int32_t* cap_full, const int32_t* cap_fwd, uint8_t* ops_out, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream) {
+// validation and launch sequence shared by the two knapsack entry points; `workspace` is device memory
+static d2ft_status knapsack_run(int32_t n_knapsacks, int32_t n_items, const double* score_full,
+                                const double* score_fwd, const int32_t* cost_fwd, const int32_t* cost_bwd,
+                                const int32_t* cap_full, const int32_t* cap_fwd, uint8_t* ops_out, void* workspace,
+                                size_t workspace_bytes, hipStream_t st) {
     if (!score_full || !score_fwd || !cost_fwd || !cost_bwd || !cap_full || !cap_fwd || !ops_out || !workspace)
         return D2FT_EINVAL;
     if (n_knapsacks < 1 || n_items < 1) return D2FT_ESHAPE;
@@ -1362,7 +1363,6 @@ d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items, const dou
     const size_t need = d2ft_knapsack_workspace_bytes(n_knapsacks, n_items, cap_full, cap_fwd);
     if (need == 0 || workspace_bytes < need) return D2FT_ESHAPE;
 
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
     size_t off = 0;
     auto take = [&](size_t bytes) { char* at = ws + off; off += align256(bytes); return at; };
@@ -1392,6 +1392,50 @@ d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items, const dou
     D2FT_TRY(hipMemcpyAsync(ops_out, d_ops, nsc, hipMemcpyDeviceToHost, st));
     D2FT_TRY(hipStreamSynchronize(st));
     return D2FT_OK;
+}
+
+d2ft_status d2ft_select_knapsack(int32_t n_knapsacks, int32_t n_items, const double* score_full,
+                                 const double* score_fwd, const int32_t* cost_fwd, const int32_t* cost_bwd,
+                                 const int32_t* cap_full, const int32_t* cap_fwd, uint8_t* ops_out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+    return knapsack_run(n_knapsacks, n_items, score_full, score_fwd, cost_fwd, cost_bwd, cap_full, cap_fwd, ops_out,
+                        workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- the knapsack selection for callers that cannot allocate ----
+// Its workspace is a file-scope device array.  Every GPU the library runs on holds its own copy of the
+// array at its own address for the life of the process; the address is looked up once per device, with
+// that device current, and host code uses that pointer - never the array's name, which on the host is only
+// a handle for the lookup.
+static __device__ __align__(256) unsigned char scratch[D2FT_KNAPSACK_STATIC_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // per device, NULL until the first call on it
+
+size_t d2ft_knapsack_static_bytes(void) { return sizeof(scratch); }
+
+d2ft_status d2ft_select_knapsack_static(int32_t n_knapsacks, int32_t n_items, const double* score_full,
+                                        const double* score_fwd, const int32_t* cost_fwd, const int32_t* cost_bwd,
+                                        const int32_t* cap_full, const int32_t* cap_fwd, uint8_t* ops_out,
+                                        void* hip_stream) {
+    if (!cap_full || !cap_fwd) return D2FT_EINVAL;
+    if (n_knapsacks < 1 || n_items < 1) return D2FT_ESHAPE;
+    for (int k = 0; k < n_knapsacks; ++k)
+        if (cap_full[k] < 0 || cap_fwd[k] < 0) return D2FT_EINVAL;
+    // a problem beyond the array's size is refused before anything touches the device
+    const size_t need = d2ft_knapsack_workspace_bytes(n_knapsacks, n_items, cap_full, cap_fwd);
+    if (need == 0 || need > sizeof(scratch)) return D2FT_ESHAPE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return D2FT_EDEVICE;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return D2FT_EDEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    // nothing in the workspace has to start at zero: the kernel initialises the table row, the selection
+    // flags and every change flag it later reads, so what the previous call left behind is harmless
+    return knapsack_run(n_knapsacks, n_items, score_full, score_fwd, cost_fwd, cost_bwd, cap_full, cap_fwd, ops_out,
+                        g_scratch_ptr[dev], sizeof(scratch), static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"
