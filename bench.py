@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# the metric as the baseline record names it; the headline line is the ViT-B/16 stack with 60 % p_f / 20 % p_o /
+# 20 % p_s heads, and the literal "40 % of the heads skipped" mask is the sub-record "vit_b16_skip40"
+METRIC = "fine-tune step images/sec, ViT-B/16 block stack, 40% heads skipped; MFMA util %"
 
 
 def algorithmic_flops(w, ops, rows=None) -> float:
@@ -70,6 +73,63 @@ def recorded_traffic(kernel: str, workload: str):
         return None
 
 
+def sub_records(args, w, s, dws, x, dy, grad_fields):
+    """The ViT-B/16 stack under the other masks and modes, same weights and token batch, timed in the same run:
+    the metric's literal mask (40 % of the heads skipped, none forward-only), whole subnets gated (a head
+    with its 1/H slice of the feed-forward network, Sec. II-A.1), and one op code per (subnet, micro-batch)
+    with 5 micro-batches (Alg. 1's table; Sec. III-A), each with its all-p_f time and FLOP ratio."""
+    import numpy as np
+    import torch
+
+    import d2ft_inputs as di
+    import paper_2504_12471_amd as P
+
+    steps, warmup = max(10, args.steps // 2), max(3, args.warmup // 4)
+
+    def timed(stack, mask):
+        for _ in range(warmup):
+            stack.step(x, dy, mask)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            stack.step(x, dy, mask)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def record(name, wl, ops, mb_images):
+        desc = P.make_desc(wl.batch, wl.tokens, wl.width, wl.heads, wl.mlp_hidden, wl.dtype, wl.lora_rank, wl.lora_scale,
+                           wl.ln_eps, wl.head_dim, P.FLAG_GATE_FFN if wl.gate_ffn else 0)
+        stack = P.BlockStack(desc, dws, wl.dtype, grad_fields, mb_images)
+        ms = timed(stack, ops)
+        ms_full = timed(stack, np.full_like(ops, di.OP_FULL))
+        if mb_images is None:
+            fl = algorithmic_flops(wl, ops)
+            fl_full = algorithmic_flops(wl, np.full_like(ops, di.OP_FULL))
+        else:
+            fl = sum(algorithmic_flops(wl, ops[:, i], mb_images[i] * wl.tokens) for i in range(len(mb_images)))
+            fl_full = algorithmic_flops(wl, np.full_like(ops[:, 0], di.OP_FULL))
+        del stack
+        torch.cuda.empty_cache()
+        return {"workload": name, "ms_per_step": round(ms, 4), "images_per_s": round(wl.batch / (ms * 1e-3), 1),
+                "all_full_ms_per_step": round(ms_full, 4), "time_ratio": round(ms / ms_full, 4),
+                "flop_ratio": round(fl / fl_full, 4), "step_mfma_frac": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                "heads_full": int((ops == di.OP_FULL).sum()), "heads_fwd_only": int((ops == di.OP_FWD).sum()),
+                "heads_skipped": int((ops == di.OP_SKIP).sum()), "micro_batches": mb_images, "steps": steps}
+
+    out = []
+    for name in ("vit_b16_skip40", "vit_b16_ffn", "vit_b16_ffn_skip40"):
+        wl = di.WORKLOADS[name]
+        out.append(record(name, wl, di.draw_ops(wl, args.seed)[0], None))
+    base, extra = divmod(w.batch, 5)
+    mb = [base + (1 if i < extra else 0) for i in range(5)]
+    for name in ("vit_b16", "vit_b16_ffn"):
+        wl = di.WORKLOADS[name]
+        rng = np.random.default_rng(args.seed + 1000)
+        ops = di.exact_count_masks(rng, wl.blocks * 5, wl.heads, *wl.mask[1:]).reshape(wl.blocks, 5, wl.heads)
+        out.append(record(name + " --micro 5", wl, ops, mb))
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +141,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--micro", type=int, default=0,
                     help="split the batch into this many micro-batches, each with its own op codes (0: one code per head)")
+    ap.add_argument("--no-sub-records", action="store_true",
+                    help="skip the extra workloads timed beside the headline one (skip40 mask, gated FFN, 5 micro-batches)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -216,13 +278,21 @@ def main() -> int:
     kernels = [{"name": k["name"], "launches_per_step": k["launches"] // n_prof,
                 "ms_per_step": round(k["ms"] / n_prof, 4),
                 "tflops": round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 1) if k["flops"] > 0 else None} for k in kern]
+    # bandwidth-bound kernels: algorithmic bytes (every operand read once, every result written once) over the
+    # HIP-event time; operands of up to 78 MB can sit in the 256 MB last-level cache
+    hbm_kernels = [{"name": k["name"], "launches_per_step": k["launches"] // n_prof,
+                    "us_per_launch": round(k["ms"] / k["launches"] * 1e3, 2),
+                    "MB_per_launch": round(k["bytes"] / k["launches"] / 1e6, 2),
+                    "GB_per_s": round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1),
+                    "frac_of_hbm_peak": round(k["bytes"] / (k["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
+                   for k in kern if k["bytes"] > 0]
 
     if mb_images is None:
         flops = algorithmic_flops(w, ops)
     else:
         flops = sum(algorithmic_flops(w, ops[:, i], mb_images[i] * w.tokens) for i in range(args.micro))
     out = {
-        "metric": "fine-tune step images/sec, ViT block stack with per-head op codes",
+        "metric": METRIC,
         "value": round(w.batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic (seeded N(0,1) tokens, N(0,0.02^2) weights)",
@@ -239,8 +309,13 @@ def main() -> int:
         "roofline": roofline,
         "subnet_scores": scores,
         "sgd_step": sgd,
-        "kernels": kernels[:12],
+        "hbm_kernels": hbm_kernels,
+        "kernels": kernels,
     }
+    if args.workload == "vit_b16" and args.micro == 0 and not args.no_sub_records:
+        del stack   # its saved-activation buffers
+        torch.cuda.empty_cache()
+        out["sub_records"] = sub_records(args, w, s, dws, x, dy, grad_fields)
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host cores: block 0 of the same workload, forward + backward

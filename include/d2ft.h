@@ -176,7 +176,7 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc *desc, const d2ft_block_weights
  * and a subnet that is p_f in no micro-batch gets +0.0; with it set everything is added to what
  * the buffers hold.  How the work is laid out on the stream is the library's choice and does not change
  * what is computed beyond rounding order:
- *   - when the matrix-core attention kernels apply (bf16, at most 256 tokens) and every micro-batch keeps a
+ *   - when the matrix-core attention kernels apply (bf16, at most 224 tokens) and every micro-batch keeps a
  *     head live, the block runs once over the whole batch under the union of the codes, with the attention
  *     kernels masking per (micro-batch, head): skipped pairs contribute exact zeros to the projections, pairs
  *     that are not p_f exact zeros to the weight gradients (gated feed-forward slices likewise);

@@ -111,6 +111,9 @@ struct GemmArgs {
     float* partial;       // non-null: split-K mode, raw fp32 sums go to partial[split][M][N]
     int splits;
     int tile_hint;        // 0: kernel chooses its tile, 1: 256x256, 2: 128x128, 3: 192x256
+    float* colsum;        // non-null (MFMA path only): column sums of C's values over bands of rows, fp32
+                          // [bands][N]; band = colsum_row0 + 2 * (row tile) + (upper / lower half of the tile)
+    int colsum_row0;
     Remap64 tbl;
 };
 
@@ -119,6 +122,8 @@ hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
+// rows of the output tile launch_gemm_mfma would pick (a tile makes two bands of g.colsum)
+int gemm_mfma_tile_rows(const GemmArgs& g);
 // static string naming the kernel instantiation launch_gemm_mfma would pick (for timing records)
 const char* gemm_mfma_config_name(const GemmArgs& g);
 
@@ -127,6 +132,13 @@ hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void
 // dx = LNbwd(d) + res
 hipError_t launch_ln_bwd(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
                          const void* gamma, const void* res, void* dx, int rows, int width, hipStream_t s);
+// the same, also writing column sums of res (sum_res) and of dx (sum_out) over bands of rows:
+// [ln_bwd_sums_bands(rows)][width] fp32 each; either may be null.  res must be given; width <= 2048.
+bool ln_bwd_sums_supported(int width);
+int ln_bwd_sums_bands(int rows);
+hipError_t launch_ln_bwd_sums(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
+                              const void* gamma, const void* res, void* dx, int rows, int width, float* sum_res,
+                              float* sum_out, hipStream_t s);
 // partial_g/partial_b: [chunks][width] fp32 sums of d*xhat and d over row chunks
 hipError_t launch_ln_param_grad(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
                                 float* partial_g, float* partial_b, int rows, int width, int chunks, hipStream_t s);
@@ -232,7 +244,7 @@ hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, long ldq, const vo
                                   const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, int batch,
                                   int tokens, int n_full, hipStream_t s);
 
-// MFMA attention (bf16, head dimension 64, up to 256 tokens); same argument meaning as the simple launchers
+// MFMA attention (bf16, head dimension 64, up to 256 tokens forward, 224 backward); same argument meaning as the simple launchers
 // Which (micro-batch, compacted head position) pairs take part when one launch covers several
 // micro-batches with their own op codes: bit p of live[i] / full[i] says whether the head at position p
 // is computed / is p_f in micro-batch i, which holds the images [img_end[i-1], img_end[i]).
@@ -249,7 +261,8 @@ struct MicroMask {
     }
 };
 
-bool attn_mfma_supported(int tokens, long ldq, long ldo);
+bool attn_mfma_supported(int tokens, long ldq, long ldo);       // forward: up to 256 tokens
+bool attn_bwd_mfma_supported(int tokens, long ldq, long ldo);   // backward: up to 224 tokens
 // with a mask: pairs that are not live get a zero O block (forward), pairs that are not p_f a zero dQKV
 // block (backward); the log-sum-exp is saved for p_f pairs.  The grid has one workgroup per image and
 // "slot" (as many slots as the busiest micro-batch has pairs that take part): slot s of an image works
@@ -258,8 +271,8 @@ bool attn_mfma_supported(int tokens, long ldq, long ldo);
 hipError_t launch_attn_fwd_mfma_masked(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
                                        int n_live, const MicroMask& mask, hipStream_t s);
 hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
-                                       const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
-                                       int n_full, const MicroMask& mask, hipStream_t s);
+                                       const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* bsum, long ld_bsum,
+                                       int batch, int tokens, int n_full, const MicroMask& mask, hipStream_t s);
 // zero the [tokens][width] blocks (column offset position * width, row stride ld; in x and, if given, x2) of
 // the pairs at positions 0 .. n_pos-1 that are skipped, or that are live but not p_f
 enum { PAIRS_SKIPPED = 0, PAIRS_FORWARD_ONLY = 1 };
@@ -267,9 +280,11 @@ hipError_t launch_zero_pairs(int dtype, void* x, void* x2, long ld, int batch, i
                              const MicroMask& mask, hipStream_t s);
 hipError_t launch_attn_fwd_mfma(const void* qkv, long ldq, void* o, long ldo, float* lse, int batch, int tokens,
                                 int n_live, int n_full, hipStream_t s);
+// bsum: null, or [batch][ld_bsum] fp32: row b receives the column sums of image b's dqkv rows (the first
+// n_full * 192 columns), i.e. partial sums of the QKV bias gradient
 hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
-                                const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
-                                int n_full, hipStream_t s);
+                                const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* bsum, long ld_bsum,
+                                int batch, int tokens, int n_full, hipStream_t s);
 
 // bi-level knapsack (Alg. 1 + Alg. 2); all pointers are device pointers into the caller's workspace
 struct KnapsackArgs {

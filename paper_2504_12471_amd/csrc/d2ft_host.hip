@@ -84,7 +84,7 @@ SavedLayout saved_layout(const Dims& s) {
 
 // ---- layout of the scratch buffer ----
 struct ScratchLayout {
-    size_t part, colpart, dz, dv, dx1, d_o, dqkv, du, delta, weff, total;
+    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, dz, dv, dx1, d_o, dqkv, du, delta, weff, total;
     size_t part_floats, colpart_stride;
 };
 ScratchLayout scratch_layout(const Dims& s) {
@@ -100,6 +100,12 @@ ScratchLayout scratch_layout(const Dims& s) {
     L.part = take(L.part_floats * 4);
     L.colpart_stride = (size_t)kColChunks * cols;   // floats per region: four bias reductions, two LayerNorm ones
     L.colpart = take(6 * L.colpart_stride * 4);
+    // column sums that the producing kernels write themselves, one row of partial sums per band of rows:
+    // the dz GEMM's epilogue (bands of 64 or more rows) for b1, the LayerNorm backward for b2 and b_o
+    L.colfuse_b1 = take(((size_t)s.M / 64 + 8) * s.Dm * 4);
+    L.colfuse_b2 = take((size_t)ln_bwd_sums_bands((int)s.M) * s.D * 4);
+    L.colfuse_bo = take((size_t)ln_bwd_sums_bands((int)s.M) * s.D * 4);
+    L.colfuse_bqkv = take((size_t)s.B * s.H * 192 * 4);   // per image, from the attention backward
     L.dz = take(s.M * s.Dm * s.es);
     L.dv = take(s.M * s.D * s.es);
     L.dx1 = take(s.M * s.D * s.es);
@@ -228,6 +234,16 @@ void timing_end(hipStream_t st) {
         if (e__ != hipSuccess) return D2FT_EDEVICE; \
     } while (0)
 
+// a bandwidth-bound launch: also books the algorithmic bytes it moves (read + written once each)
+#define D2FT_TRY_BYTES(nbytes, expr)                \
+    do {                                            \
+        timing_begin(st, #expr);                    \
+        hipError_t e__ = (expr);                    \
+        g_timing.bytes = (double)(nbytes);          \
+        timing_end(st);                             \
+        if (e__ != hipSuccess) return D2FT_EDEVICE; \
+    } while (0)
+
 // one timed GEMM launch (the launch sites use D2FT_TRY_UNTIMED around run_gemm)
 hipError_t timed_mfma(const GemmArgs& g, hipStream_t st) {
     timing_begin(st, "gemm");
@@ -238,8 +254,15 @@ hipError_t timed_mfma(const GemmArgs& g, hipStream_t st) {
     return e;
 }
 
-hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) {
-    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g)) {
+// true if run_gemm takes the matrix-core path for g (the only path that honours g.colsum)
+bool on_mfma_path(const GemmArgs& g, const d2ft_block_desc* d) {
+    return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && gemm_mfma_supported(g);
+}
+
+// colsum_bands: if non-null, receives the number of rows of g.colsum the launches fill
+hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, int* colsum_bands = nullptr) {
+    if (colsum_bands) *colsum_bands = 0;
+    if (on_mfma_path(g, d)) {
         // The 256x256 tile runs one workgroup per CU, so a grid of R*256 + f tiles takes R + 1 rounds
         // however small f is.  When the last round would be under 60% full, the rows of whole rounds
         // go to the large tile and the remaining rows to the 128x128 tile, two of which share a CU.
@@ -260,7 +283,9 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
                     rest.C = static_cast<char*>(g.C) + m_split * g.ldc * es;
                     if (g.residual) rest.residual = static_cast<const char*>(g.residual) + m_split * g.ldr * es;
                     if (g.Z) rest.Z = static_cast<char*>(g.Z) + m_split * g.ldz * es;
+                    rest.colsum_row0 = g.colsum_row0 + 2 * (int)tm_big;
                     if (gemm_mfma_supported(big) && gemm_mfma_supported(rest)) {
+                        if (colsum_bands) *colsum_bands = 2 * (int)tm_big + 2 * ((rest.M + 127) / 128);
                         hipError_t e = timed_mfma(big, s);
                         if (e != hipSuccess) return e;
                         return timed_mfma(rest, s);
@@ -268,8 +293,13 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
                 }
             }
         }
+        if (colsum_bands) {
+            const int bm = gemm_mfma_tile_rows(g);
+            *colsum_bands = 2 * ((g.M + bm - 1) / bm);
+        }
         return timed_mfma(g, s);
     }
+    if (g.colsum) return hipErrorNotSupported;   // callers ask on_mfma_path() first
     timing_begin(s, "gemm");
     g_timing.label = "gemm_simple_kernel";
     g_timing.flops = 2.0 * g.M * g.N * g.K;
@@ -278,9 +308,9 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s) 
     return e;
 }
 
-// bf16, head dimension 64, up to 256 tokens: the matrix-core attention kernels
+// bf16, head dimension 64, up to 224 tokens: the matrix-core attention kernels, forward and backward
 static bool attn_on_mfma(const d2ft_block_desc* d) {
-    return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && d->tokens <= 256;
+    return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && d->tokens <= 224;
 }
 
 hipError_t run_attn_fwd(const d2ft_block_desc* d, const void* qkv, long ldq, void* o, long ldo, float* lse, int batch,
@@ -298,20 +328,26 @@ hipError_t run_attn_fwd(const d2ft_block_desc* d, const void* qkv, long ldq, voi
     return launch_attn_fwd_simple(d->dtype, qkv, ldq, o, ldo, lse, batch, tokens, n_live, n_full, s);
 }
 
+// the matrix-core backward also sums the columns of dqkv per image (bsum, see launch_attn_bwd_mfma)
+static bool attn_bwd_on_mfma(const d2ft_block_desc* d, int tokens, long ldq, long ldo, long ld_do, long ld_dqkv) {
+    return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && attn_bwd_mfma_supported(tokens, ldq, ldo) &&
+           (ld_do % 8) == 0 && (ld_dqkv % 8) == 0;
+}
+
 hipError_t run_attn_bwd(const d2ft_block_desc* d, const void* qkv, long ldq, const void* o, long ldo, const float* lse,
-                        const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, int batch, int tokens,
-                        int n_full, hipStream_t s, const MicroMask* mask = nullptr) {
+                        const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, float* bsum, int batch,
+                        int tokens, int n_full, hipStream_t s, const MicroMask* mask = nullptr) {
     g_timing.flops = 8.0 * batch * n_full * (double)tokens * tokens * 64;
     if (mask) {
         g_timing.label = "attn_bwd_mfma";
-        return launch_attn_bwd_mfma_masked(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, *mask,
-                                           s);
+        return launch_attn_bwd_mfma_masked(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, bsum, ld_dqkv, batch, tokens,
+                                           n_full, *mask, s);
     }
-    if (d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && attn_mfma_supported(tokens, ldq, ldo) &&
-        (ld_do % 8) == 0 && (ld_dqkv % 8) == 0) {
+    if (attn_bwd_on_mfma(d, tokens, ldq, ldo, ld_do, ld_dqkv)) {
         g_timing.label = "attn_bwd_mfma";
-        return launch_attn_bwd_mfma(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, s);
+        return launch_attn_bwd_mfma(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, bsum, ld_dqkv, batch, tokens, n_full, s);
     }
+    if (bsum) return hipErrorNotSupported;   // callers ask attn_bwd_on_mfma() first
     g_timing.label = "attn_bwd_simple";
     return launch_attn_bwd_simple(d->dtype, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, delta, batch, tokens, n_full,
                                   s);
@@ -364,7 +400,7 @@ d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop
     if (splits_out) *splits_out = g.splits;
     D2FT_TRY_UNTIMED(run_gemm(g, d, st));
     if (reduce)
-        D2FT_TRY(launch_reduce_partials(s.dtype, part, g.splits, (long)out_rows * out_cols, out_rows, out_cols, out,
+        D2FT_TRY_BYTES((4.0 * g.splits + s.es) * out_rows * out_cols, launch_reduce_partials(s.dtype, part, g.splits, (long)out_rows * out_cols, out_rows, out_cols, out,
                                         ldo, red_remap, tbl, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
     return D2FT_OK;
 }
@@ -374,7 +410,7 @@ d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop
 d2ft_status bias_grad(const Dims& s, const void* X, long ldx, int cols, float* region, void* out, int remap_cols,
                       ColReduceBatch* batch, hipStream_t st) {
     const int chunks = pick_chunks(s.M);
-    D2FT_TRY(launch_colsum(s.dtype, X, ldx, (int)s.M, cols, region, chunks, st));
+    D2FT_TRY_BYTES(1.0 * s.M * cols * s.es, launch_colsum(s.dtype, X, ldx, (int)s.M, cols, region, chunks, st));
     ColReduceJob& j = batch->job[batch->n++];
     j.partial = region;
     j.out = out;
@@ -384,9 +420,21 @@ d2ft_status bias_grad(const Dims& s, const void* X, long ldx, int cols, float* r
     return D2FT_OK;
 }
 
+// bias gradient whose first half a producing kernel has already done: `bands` rows of column sums in region
+void queue_bias_reduce(ColReduceBatch* batch, const float* region, int bands, int cols, void* out, int remap_cols) {
+    ColReduceJob& j = batch->job[batch->n++];
+    j.partial = region;
+    j.out = out;
+    j.chunks = bands;
+    j.cols = cols;
+    j.remap_cols = remap_cols;
+}
+
 d2ft_status flush_bias_grads(const d2ft_block_desc* d, const Dims& s, ColReduceBatch* batch, const Remap64& tbl_a,
                              const Remap64& tbl_b, hipStream_t st) {
-    D2FT_TRY(launch_col_reduce_batch(s.dtype, *batch, tbl_a, tbl_b, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
+    double nbytes = 0;
+    for (int i = 0; i < batch->n; ++i) nbytes += 4.0 * batch->job[i].chunks * batch->job[i].cols;
+    D2FT_TRY_BYTES(nbytes, launch_col_reduce_batch(s.dtype, *batch, tbl_a, tbl_b, (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0, st));
     batch->n = 0;
     return D2FT_OK;
 }
@@ -499,7 +547,7 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     const void* x1 = x;   // all heads shortcut: the attention residual is x itself
     if (part != PART_MLP && nl > 0) {
         void* u = sv + SL.u;
-        D2FT_TRY(launch_ln_fwd(s.dtype, x, w->ln1_g, w->ln1_b, u, (float*)(sv + SL.mean1), (float*)(sv + SL.rstd1), M,
+        D2FT_TRY_BYTES(2.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_fwd(s.dtype, x, w->ln1_g, w->ln1_b, u, (float*)(sv + SL.mean1), (float*)(sv + SL.rstd1), M,
                                s.D, desc->ln_eps, st));
         // Q, K, V of the live heads only
         GemmArgs g = gemm_base();
@@ -559,7 +607,7 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     memset(&ffn_tbl, 0, sizeof(ffn_tbl));
     if (gate) fill_ffn_table(ffn_tbl, live, nl, slice);
     void* v = sv + SL.v;
-    D2FT_TRY(launch_ln_fwd(s.dtype, x1, w->ln2_g, w->ln2_b, v, (float*)(sv + SL.mean2), (float*)(sv + SL.rstd2), M, s.D,
+    D2FT_TRY_BYTES(2.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_fwd(s.dtype, x1, w->ln2_g, w->ln2_b, v, (float*)(sv + SL.mean2), (float*)(sv + SL.rstd2), M, s.D,
                            desc->ln_eps, st));
     {   // z = v W1^T + b1, g = GELU(z)
         GemmArgs g = gemm_base();
@@ -650,13 +698,20 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (grads->ln2_b) D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->ln2_b, s.D, RED_REMAP_NONE, none, 0, st));
         }
     }
-    if (half != PART_ATTN && grads->b2 && w->b2 && (!gate || nl > 0)) {
+    // The LayerNorm backward of the feed-forward half reads dy and writes dx1: where it runs it also sums
+    // their columns, which are the gradients of b2 and b_o; otherwise those are column-sum passes of their own.
+    const bool ln2_runs = half != PART_ATTN && n_hid > 0;
+    const bool ln2_sums = ln2_runs && ln_bwd_sums_supported(s.D);
+    const bool want_b2 = half != PART_ATTN && grads->b2 && w->b2 && (!gate || nl > 0);
+    const bool want_bo = half != PART_MLP && grads->b_o && w->b_o && nl > 0;
+    if (want_b2 && !ln2_sums) {
         rc = bias_grad(s, dy, s.D, s.D, colpart + 0 * WL.colpart_stride, grads->b2, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
     // gradient of x1.  It is dy when the feed-forward half is not run here: handed over by the caller
     // (PART_ATTN), or gated with no p_f subnet (the residual route alone).
     const void* dx1 = dy;
+    int b1_bands = 0;
     if (half != PART_ATTN && n_hid > 0) {
         if (grads->w2) {   // dW2[:, hidden] = dy^T g
             rc = weight_grad(desc, s, dy, s.D, sv + SL.g, ld_hid, s.D, n_hid, part, grads->w2, s.Dm,
@@ -672,14 +727,18 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             g.M = M; g.N = n_hid; g.K = s.D;
             g.C = ws + WL.dz; g.ldc = n_hid;
             g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = ld_hid;
-            D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+            if (grads->b1 && on_mfma_path(g, desc)) g.colsum = (float*)(ws + WL.colfuse_b1);   // db1 = column sums of dz
+            D2FT_TRY_UNTIMED(run_gemm(g, desc, st, &b1_bands));
+            if (!g.colsum) b1_bands = 0;
         }
         if (grads->w1) {   // dW1[hidden] = dz^T v
             rc = weight_grad(desc, s, ws + WL.dz, n_hid, sv + SL.v, s.D, n_hid, s.D, part, grads->w1, s.D,
                              gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, st);
             if (rc != D2FT_OK) return rc;
         }
-        if (grads->b1) {
+        if (grads->b1 && b1_bands > 0) {
+            queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
+        } else if (grads->b1) {
             rc = bias_grad(s, ws + WL.dz, n_hid, n_hid, colpart + 1 * WL.colpart_stride, grads->b1, gate ? 2 : 0,
                            &bias_batch, st);
             if (rc != D2FT_OK) return rc;
@@ -706,15 +765,25 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         }
         // dx1 = dy + LN2bwd(dv); with no p_f head this already is dx (residual route only)
         void* out = (half == PART_BOTH && nf > 0) ? (void*)(ws + WL.dx1) : dx;
-        D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2), (const float*)(sv + SL.rstd2),
-                               w->ln2_g, dy, out, M, s.D, st));
+        if (ln2_sums && (want_b2 || want_bo)) {
+            float* sum_res = want_b2 ? (float*)(ws + WL.colfuse_b2) : nullptr;
+            float* sum_out = want_bo ? (float*)(ws + WL.colfuse_bo) : nullptr;
+            D2FT_TRY_BYTES(4.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_bwd_sums(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2),
+                                        (const float*)(sv + SL.rstd2), w->ln2_g, dy, out, M, s.D, sum_res, sum_out, st));
+            const int bands = ln_bwd_sums_bands(M);
+            if (want_b2) queue_bias_reduce(&bias_batch, sum_res, bands, s.D, grads->b2, 0);
+            if (want_bo) queue_bias_reduce(&bias_batch, sum_out, bands, s.D, grads->b_o, 0);
+        } else {
+            D2FT_TRY_BYTES(4.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_bwd(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2), (const float*)(sv + SL.rstd2),
+                                   w->ln2_g, dy, out, M, s.D, st));
+        }
         dx1 = out;
     }
     if (half == PART_MLP) return flush_bias_grads(desc, s, &bias_batch, none, ffn_tbl, st);
 
     // ---- attention side ----
     sv = sva;
-    if (grads->b_o && w->b_o && nl > 0) {
+    if (want_bo && !ln2_sums) {
         rc = bias_grad(s, dx1, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
     }
@@ -765,8 +834,11 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                          head_tbl, st);
         if (rc != D2FT_OK) return rc;
     }
+    // the matrix-core attention backward also leaves per-image column sums of dQKV: the QKV bias gradient
+    const bool fuse_bqkv = grads->b_qkv && (mask || attn_bwd_on_mfma(desc, s.T, ldq, ldo, ld_do, ld_dq));
+    float* bqkv_part = fuse_bqkv ? (float*)(ws + WL.colfuse_bqkv) : nullptr;
     D2FT_TRY(run_attn_bwd(desc, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o, ld_do,
-                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), s.B, s.T, nf, st, mask));
+                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), bqkv_part, s.B, s.T, nf, st, mask));
     const void* u = sv + SL.u;
     const bool want_lora = s.r > 0 && (grads->lora_a_q || grads->lora_a_v || grads->lora_b_q || grads->lora_b_v);
     if (grads->w_qkv || want_lora) {   // G = dQKV^T u, rows in compacted order
@@ -782,7 +854,9 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                                          fl, s.H, s.D, s.r, desc->lora_scale, accum, st));
         }
     }
-    if (grads->b_qkv) {
+    if (fuse_bqkv) {
+        queue_bias_reduce(&bias_batch, bqkv_part, s.B, nf * 192, grads->b_qkv, 1);   // table a
+    } else if (grads->b_qkv) {
         rc = bias_grad(s, ws + WL.dqkv, ld_dq, nf * 192, colpart + 3 * WL.colpart_stride, grads->b_qkv, 1, &bias_batch, st);   // table a
         if (rc != D2FT_OK) return rc;
     }
@@ -816,7 +890,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, accum, st));
     }
     // dx = dx1 + LN1bwd(du)
-    D2FT_TRY(launch_ln_bwd(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1), (const float*)(sv + SL.rstd1), w->ln1_g,
+    D2FT_TRY_BYTES(4.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_bwd(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1), (const float*)(sv + SL.rstd1), w->ln1_g,
                            dx1, dx, M, s.D, st));
     return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st);
 }
@@ -943,6 +1017,7 @@ d2ft_status d2ft_block_fwd_mb(const d2ft_block_desc* desc, const d2ft_block_weig
     const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* sv = static_cast<char*>(saved);
+    if (n_micro == 1) return block_fwd_impl(desc, w, ops, x, y, sv, sv, scratch, st, PART_BOTH);   // the plain call
     {
         uint8_t ops_union[D2FT_MAX_HEADS];
         MicroMask mask;
@@ -986,6 +1061,7 @@ d2ft_status d2ft_block_bwd_mb(const d2ft_block_desc* desc, const d2ft_block_weig
     const size_t row_bytes = (size_t)desc->tokens * desc->width * elem_size(desc->dtype);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const char* sv = static_cast<const char*>(saved);
+    if (n_micro == 1) return block_bwd_impl(desc, w, ops, x, dy, dx, grads, sv, sv, scratch, st, PART_BOTH);
     {
         uint8_t ops_union[D2FT_MAX_HEADS];
         MicroMask mask;

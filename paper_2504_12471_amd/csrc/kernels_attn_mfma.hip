@@ -1,4 +1,4 @@
-// Fused softmax attention on the CDNA4 matrix cores for head dimension 64 and up to 256 tokens
+// Fused softmax attention on the CDNA4 matrix cores for head dimension 64 and up to 256 tokens (forward) or 224 tokens (backward)
 // (bf16 storage, fp32 accumulate).  One 256-thread workgroup owns one (image, head); K and V of
 // that pair stay in LDS for the whole kernel.
 //
@@ -14,6 +14,7 @@
 //   operand:  row-or-column c, k-slots 8h .. 8h+7
 //   result :  column c, element e <-> row 8*(e/4) + 4h + e%4
 #include <type_traits>
+#include <utility>
 
 #include "d2ft_common.h"
 
@@ -300,39 +301,58 @@ hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* ls
 //     S  = Q_i K_u^T              P  = exp(S/8 - lse_q)          (probabilities are rebuilt, never stored)
 //     dP = dO_i V_u^T             dS = P * (dP - delta_q),       delta_q = sum_d dO[q][d] O[q][d]
 //     dV_u^T += dO_i^T P          dK_u^T += Q_i^T dS             (P, dS feed the MFMA straight from registers)
-//     dQ_i^T += K_u^T dS^T        (dS goes through a 2 KB per-wavefront LDS tile to change owner)
-// The workgroup has eight wavefronts; wavefront w owns key tile w (a wavefront beyond the last tile
-// only takes part in the loads and barriers) and keeps its dK, dV accumulators in registers for the
-// whole kernel.  The partial dQ_i tiles are summed through four LDS slots in a fixed order:
-// wavefronts 0..3 write, wavefronts 4..7 add theirs onto slot w-4, then the slots are added as
-// (0+1)+(2+3).
+//     dQ_i^T  = sum_u K_u^T dS_iu^T
+// The workgroup has KT + 1 wavefronts.  Wavefront u < KT owns key tile u: it holds the K_u and V_u
+// operand fragments and its dK, dV accumulators in registers for the whole kernel, walks the query
+// tiles and leaves each dS_iu (bf16, 2 KB) in LDS.  Its loop is software-pipelined: the S and dP
+// products of query tile i + 1 are issued before the exponentials of tile i, so the matrix cores work
+// under the vector arithmetic.  The last wavefront owns dQ: one step behind the others it multiplies
+// the KT tiles dS_iu of a query tile with K^T out of LDS, so dQ_i is MFMA chains in a fixed order - no
+// partial sums cross wavefronts - and goes from its registers to memory.  Query tiles (Q_i, dO_i) are
+// triple-buffered and the dS tiles double-buffered in LDS, which leaves one barrier per query tile.
+// The per-query constants ride in the products: a query row of Q carries -8 lse_q and a row of dO
+// carries -delta_q (each split into two bf16 terms) in two extra channels that meet a 1 on the K / V
+// side, so the MFMAs deliver S - 8 lse and dP - delta and the lanes read no per-query values from LDS.
+// If bsum is given the kernel also writes the column sums of the pair's dQ, dK, dV rows (the
+// gradient of the QKV bias: one row of 192 partial sums per image).
 // ---------------------------------------------------------------------------
 constexpr int kTS = 104;   // rows that are read both ways (row-form and transposing): 208 bytes
-constexpr int kBwdWaves = 8;
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop whose index is a compile-time constant
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 template <int KT, typename Mask>
-__global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
-                                                                          const bf16* __restrict__ o, long ldo,
-                                                                          const float* __restrict__ lse,
-                                                                          const bf16* __restrict__ d_o, long ld_do,
-                                                                          bf16* __restrict__ dqkv, long ld_dqkv,
-                                                                          int tokens, int n_full, long rows_total,
-                                                                          Mask mask) {
-    static_assert(KT <= kBwdWaves, "one key tile per wavefront");
+__global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
+                                                                      const bf16* __restrict__ o, long ldo,
+                                                                      const float* __restrict__ lse,
+                                                                      const bf16* __restrict__ d_o, long ld_do,
+                                                                      bf16* __restrict__ dqkv, long ld_dqkv,
+                                                                      float* __restrict__ bsum, long ld_bsum,
+                                                                      int tokens, int n_full, long rows_total,
+                                                                      Mask mask) {
     constexpr int TP = KT * 32;
-    constexpr int NTHR = 64 * kBwdWaves;
+    constexpr int NTHR = 64 * (KT + 1);
+    constexpr int NLD = (512 + NTHR - 1) / NTHR;         // 16-byte chunks of a (Q_i, dO_i) tile pair per thread
+    constexpr int NDL = (TP * 8 + NTHR - 1) / NTHR;      // (query, 16-byte piece) items of the delta sums per thread
+    constexpr int NKL = (TP * 8 + NTHR - 1) / NTHR;      // 16-byte chunks of K per thread
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* Ks = reinterpret_cast<bf16*>(smem_raw);        // [TP][kTS]
-    bf16* Vs = Ks + TP * kTS;                            // [TP][kKS]
-    bf16* Qs = Vs + TP * kKS;                            // [32][kTS]   current query tile
-    bf16* dOs = Qs + 32 * kTS;                           // [32][kTS]
-    bf16* dSs_all = dOs + 32 * kTS;                      // [8][32 keys][32 queries]
-    float* lse_s = reinterpret_cast<float*>(dSs_all + kBwdWaves * 32 * 32);   // [TP]
-    float* del_s = lse_s + TP;                           // [TP]
-    float* dQp = del_s + TP;                             // [4][64 channels][32 queries]
+    bf16* Ks = reinterpret_cast<bf16*>(smem_raw);        // [TP][kTS]      read transposed by the dQ wavefront
+    bf16* Qs = Ks + TP * kTS;                            // [3][32][kTS]   query tile i in buffer i % 3
+    bf16* dOs = Qs + 3 * 32 * kTS;                       // [3][32][kTS]
+    bf16* dSs_all = dOs + 3 * 32 * kTS;                  // [2][KT][32 keys][32 queries]
+    float* lse_s = reinterpret_cast<float*>(dSs_all + 2 * KT * 32 * 32);   // [TP]   -8 lse_q
+    float* del_s = lse_s + TP;                           // [TP]   -delta_q
+    bf16* dq_stage = reinterpret_cast<bf16*>(del_s + TP);   // [32][72]   the dQ wavefront's store staging
+    float* red = reinterpret_cast<float*>(dq_stage + 32 * 72);   // [KT][128]   column sums of dK, dV per key tile
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
-    bf16* dSs = dSs_all + wave * 32 * 32;
     const int b = blockIdx.x / n_full;   // with a mask n_full is the number of slots per image
     int j = blockIdx.x % n_full;
     const long row0 = (long)b * tokens;
@@ -343,10 +363,13 @@ __global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const 
         int r = 0;
         for (uint64_t m = rest; m; m &= m - 1, ++r)   // not p_f in this image's micro-batch: dQ = dK = dV = 0
             if (r % n_full == slot) {
-                bf16* zb = dqkv + row0 * ld_dqkv + __builtin_ctzll(m) * 192;
+                const int p = __builtin_ctzll(m);
+                bf16* zb = dqkv + row0 * ld_dqkv + p * 192;
                 const u32x4 z = {0u, 0u, 0u, 0u};
                 for (int i = threadIdx.x; i < tokens * 24; i += NTHR)
                     *reinterpret_cast<u32x4*>(zb + (long)(i / 24) * ld_dqkv + (i % 24) * 8) = z;
+                if (bsum)
+                    for (int i = threadIdx.x; i < 192; i += NTHR) bsum[(long)b * ld_bsum + p * 192 + i] = 0.f;
             }
         if (slot >= __builtin_popcountll(full)) return;
         uint64_t m = full;
@@ -357,178 +380,407 @@ __global__ __launch_bounds__(64 * kBwdWaves, 2) void attn_bwd_mfma_kernel(const 
     const bf16* dOb = d_o + row0 * ld_do + j * 64;
     const bf16* Ob = o + row0 * ldo + j * 64;
     bf16* dQb = dqkv + row0 * ld_dqkv + j * 192;
+    const int u = wave;                 // this wavefront's key tile (wave == KT: the dQ wavefront)
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-    load_two_tiles64<TP, NTHR>(Qb + 64, Qb + 128, ldq, tokens, Ks, kTS, Vs, kKS);
-    for (int q = threadIdx.x; q < TP; q += NTHR) {
-        float l = 0.f, dl = 0.f;
-        if (q < tokens) {
-            l = lse[(long)j * rows_total + row0 + q];
-            u32x4 a[8], g[8];
+    // ---- prologue: every global load of it is issued before the first use of any ----
+    // chunk id = threadIdx.x + k * NTHR of the 512 chunks of (Q_i, dO_i): ids below 256 are Q's
+    auto fetch_tile = [&](int i, u32x4 (&nx)[NLD]) {
 #pragma unroll
-            for (int ch = 0; ch < 8; ++ch) {
-                a[ch] = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ch * 8);
-                g[ch] = *reinterpret_cast<const u32x4*>(Ob + (long)q * ldo + ch * 8);
-            }
-#pragma unroll
-            for (int ch = 0; ch < 8; ++ch)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    dl = fmaf(__uint_as_float(a[ch][i] << 16), __uint_as_float(g[ch][i] << 16), dl);
-                    dl = fmaf(__uint_as_float(a[ch][i] & 0xffff0000u), __uint_as_float(g[ch][i] & 0xffff0000u), dl);
-                }
+        for (int k = 0; k < NLD; ++k) {
+            const int id = threadIdx.x + k * NTHR;
+            const int t = id & 255, r = t >> 3, ch = (t & 7) * 8;
+            const int q = i * 32 + r;
+            nx[k] = zero4;
+            if (id < 512 && i < KT && q < tokens)
+                nx[k] = (id < 256) ? *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + ch)
+                                   : *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ch);
         }
-        lse_s[q] = l * kLog2e;
-        del_s[q] = dl;
+    };
+    // channels 64 .. 79 of a tile row: the row's constant as two bf16 terms (a = hi + lo), then zeros
+    auto store_extra = [&](bf16* row, float a) {
+        const __bf16 hi = static_cast<__bf16>(a);
+        const __bf16 lo = static_cast<__bf16>(a - static_cast<float>(hi));
+        typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+        bf16x2_t t2;
+        t2[0] = hi;
+        t2[1] = lo;
+        const u32x4 first = {__builtin_bit_cast(uint32_t, t2), 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(row + 64) = first;
+        *reinterpret_cast<u32x4*>(row + 72) = zero4;
+    };
+    auto store_tile = [&](int i, const u32x4 (&nx)[NLD], bool extra) {   // into buffer i % 3
+#pragma unroll
+        for (int k = 0; k < NLD; ++k) {
+            const int id = threadIdx.x + k * NTHR;
+            const int t = id & 255;
+            bf16* dst = (id < 256 ? Qs : dOs) + (i % 3) * 32 * kTS + (t >> 3) * kTS + (t & 7) * 8;
+            if (id < 512) *reinterpret_cast<u32x4*>(dst) = nx[k];
+        }
+        if (extra && threadIdx.x < 64) {   // the constants of tile i's 32 queries: Q rows, then dO rows
+            const int r = threadIdx.x & 31;
+            const bool is_q = threadIdx.x < 32;
+            store_extra((is_q ? Qs : dOs) + (i % 3) * 32 * kTS + r * kTS, (is_q ? lse_s : del_s)[i * 32 + r]);
+        }
+    };
+    // V operand fragments of this wavefront's key tile: rows u*32 + c of V, 8 channels at kk*16 + 8h
+    bf16x8 kfr[5], vfr[5];
+    {
+        typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+        const short one = h == 0 ? (short)0x3F80 : (short)0;   // bf16 1.0 against the two extra channels
+        const s16x8_t ones = {one, one, 0, 0, 0, 0, 0, 0};
+        kfr[4] = vfr[4] = __builtin_bit_cast(bf16x8, ones);
     }
-
-    const int u = wave;                 // this wavefront's key tile
-    const bool has_tile = u < KT;
-    f32x16 dKt[2], dVt[2];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt) {
-        dKt[dt] = zero16();
-        dVt[dt] = zero16();
-    }
-    const float cexp = kScale * kLog2e;
-
-    // one 16-byte chunk of Q_i (threads 0..255) or of dO_i (threads 256..511) per thread; the chunks of
-    // tile i+1 are fetched while tile i is processed
-    const int ld_t = threadIdx.x & 255;
-    const int ld_r = ld_t >> 3, ld_ch = (ld_t & 7) * 8;
-    const bool ld_q = threadIdx.x < 256;
-    const bf16* ld_src = ld_q ? Qb : dOb;
-    const long ld_ld = ld_q ? ldq : ld_do;
-    bf16* ld_dst = (ld_q ? Qs : dOs) + ld_r * kTS + ld_ch;
-    u32x4 nx = {0u, 0u, 0u, 0u};
-    if (ld_r < tokens) nx = *reinterpret_cast<const u32x4*>(ld_src + (long)ld_r * ld_ld + ld_ch);
-    for (int i = 0; i < KT; ++i) {
-        __syncthreads();   // previous query tile fully consumed (and the prologue's LDS writes are visible)
-        *reinterpret_cast<u32x4*>(ld_dst) = nx;
-        {
-            const int q = (i + 1) * 32 + ld_r;
-            nx = u32x4{0u, 0u, 0u, 0u};
-            if (i + 1 < KT && q < tokens) nx = *reinterpret_cast<const u32x4*>(ld_src + (long)q * ld_ld + ld_ch);
-        }
-        __syncthreads();
-        f32x16 dqt[2] = {zero16(), zero16()};
-        if (has_tile) {
-            float L[16], DL[16];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int ql = i * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                L[e] = lse_s[ql];
-                DL[e] = del_s[ql];
-            }
-            f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kTS, c, kk * 16 + 8 * h),
-                                                            frag_rows(Ks, kTS, u * 32 + c, kk * 16 + 8 * h), s, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dOs, kTS, c, kk * 16 + 8 * h),
-                                                             frag_rows(Vs, kKS, u * 32 + c, kk * 16 + 8 * h), dp, 0, 0, 0);
-            }
-            const bool key_ok = (u * 32 + c) < tokens;
-            f32x16 ds;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float p = key_ok ? __builtin_amdgcn_exp2f(s[e] * cexp - L[e]) : 0.f;
-                s[e] = p;
-                ds[e] = p * (dp[e] - DL[e]);
-            }
-            // hand dS to the lanes that own queries: [key][query] tile, 8-byte writes
-#pragma unroll
-            for (int eg = 0; eg < 4; ++eg) {
-                uint2 pk;
-                pk.x = pack_bf16x2(ds[4 * eg], ds[4 * eg + 1]);
-                pk.y = pack_bf16x2(ds[4 * eg + 2], ds[4 * eg + 3]);
-                *reinterpret_cast<uint2*>(dSs + c * 32 + 8 * eg + 4 * h) = pk;
-            }
-#pragma unroll
-            for (int gp = 0; gp < 2; ++gp) {
-                const bf16x8 pf = pack8(s, 8 * gp);
-                const bf16x8 dsf = pack8(ds, 8 * gp);
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    dVt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(dOs, kTS, 16 * gp, dt * 32, lane), pf,
-                                                                      dVt[dt], 0, 0, 0);
-                    dKt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Qs, kTS, 16 * gp, dt * 32, lane), dsf,
-                                                                      dKt[dt], 0, 0, 0);
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int gp = 0; gp < 2; ++gp) {
-                const bf16x8 dst = frag_tr(dSs, 32, 16 * gp, 0, lane);   // column = query c, slots = keys
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    dqt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(Ks, kTS, u * 32 + 16 * gp, dt * 32, lane), dst,
-                                                                      dqt[dt], 0, 0, 0);
-            }
-        }
-        // partial dQ_i^T of this wavefront: rows = channels, column = query c
-        float* slot = dQp + (wave & 3) * 64 * 32;
-        if (wave < 4) {
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) slot[(dt * 32 + 8 * (e >> 2) + 4 * h + (e & 3)) * 32 + c] = dqt[dt][e];
-        }
-        __syncthreads();
-        if (wave >= 4 && has_tile) {
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) slot[(dt * 32 + 8 * (e >> 2) + 4 * h + (e & 3)) * 32 + c] += dqt[dt][e];
-        }
-        __syncthreads();
-        {
-            const int q = threadIdx.x & 31, dch = threadIdx.x >> 5;   // 16 groups of 4 channels
-            float v[4];
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int d = dch * 4 + i4;
-                v[i4] = ((dQp[(0 * 64 + d) * 32 + q] + dQp[(1 * 64 + d) * 32 + q]) +
-                         (dQp[(2 * 64 + d) * 32 + q] + dQp[(3 * 64 + d) * 32 + q])) * kScale;
-            }
-            const int qg = i * 32 + q;
-            if (qg < tokens) {
-                uint2 pk;
-                pk.x = pack_bf16x2(v[0], v[1]);
-                pk.y = pack_bf16x2(v[2], v[3]);
-                *reinterpret_cast<uint2*>(dQb + (long)qg * ld_dqkv + dch * 4) = pk;
-            }
-        }
-    }
-
-    // dK^T, dV^T: rows = channels, column = key owned by the lane -> 8-byte stores of 4 channels
     {
         const int key = u * 32 + c;
-        if (has_tile && key < tokens) {
-            bf16* krow = dQb + (long)key * ld_dqkv + 64;
-            bf16* vrow = krow + 64;
+        const bool ok = wave < KT && key < tokens;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 v = zero4;
+            if (ok) v = *reinterpret_cast<const u32x4*>(Qb + 128 + (long)key * ldq + kk * 16 + 8 * h);
+            vfr[kk] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+    // query tiles in flight from memory: tile t sits in ring slot t % kAhead from its fetch until it is stored to
+    // LDS kAhead steps later (memory latency is several steps long)
+    constexpr int kAhead = 3;
+    u32x4 kl[NKL], da[NDL], dg[NDL], nx0[NLD], nx1[NLD], ring[kAhead][NLD];
+#pragma unroll
+    for (int k = 0; k < NKL; ++k) {
+        const int id = threadIdx.x + k * NTHR;
+        const int r = id >> 3, ch = (id & 7) * 8;
+        kl[k] = zero4;
+        if (r < tokens) kl[k] = *reinterpret_cast<const u32x4*>(Qb + 64 + (long)r * ldq + ch);   // r < tokens <= TP
+    }
+    fetch_tile(0, nx0);
+    fetch_tile(1, nx1);
+#pragma unroll
+    for (int t = 2; t < 2 + kAhead; ++t) fetch_tile(t, ring[t % kAhead]);
+#pragma unroll
+    for (int k = 0; k < NDL; ++k) {
+        const int it = threadIdx.x + k * NTHR;
+        const int q = it >> 3, ch = (it & 7) * 8;
+        da[k] = dg[k] = zero4;
+        if (q < tokens) {
+            da[k] = *reinterpret_cast<const u32x4*>(dOb + (long)q * ld_do + ch);
+            dg[k] = *reinterpret_cast<const u32x4*>(Ob + (long)q * ldo + ch);
+        }
+    }
+    float lq[(TP + NTHR - 1) / NTHR];
+#pragma unroll
+    for (int k = 0; k < (TP + NTHR - 1) / NTHR; ++k) {
+        const int q = threadIdx.x + k * NTHR;
+        lq[k] = q < tokens ? lse[(long)j * rows_total + row0 + q] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < NKL; ++k) {
+        const int id = threadIdx.x + k * NTHR;
+        if (id < TP * 8) *reinterpret_cast<u32x4*>(Ks + (id >> 3) * kTS + (id & 7) * 8) = kl[k];
+    }
+    store_tile(0, nx0, false);
+    store_tile(1, nx1, false);
+    // delta_q = sum_d dO[q][d] O[q][d]: eight lanes per query, one 16-byte piece of the row each
+#pragma unroll
+    for (int k = 0; k < NDL; ++k) {
+        const int it = threadIdx.x + k * NTHR;
+        float dl = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dl = fmaf(__uint_as_float(da[k][i] << 16), __uint_as_float(dg[k][i] << 16), dl);
+            dl = fmaf(__uint_as_float(da[k][i] & 0xffff0000u), __uint_as_float(dg[k][i] & 0xffff0000u), dl);
+        }
+        dl += __shfl_xor(dl, 1, 64);
+        dl += __shfl_xor(dl, 2, 64);
+        dl += __shfl_xor(dl, 4, 64);
+        if ((it & 7) == 0 && it < TP * 8) {
+            const int q = it >> 3;
+            del_s[q] = -dl;
+            if (q < 64) store_extra(dOs + (q >> 5) * 32 * kTS + (q & 31) * kTS, -dl);   // tiles 0 and 1 are in LDS already
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < (TP + NTHR - 1) / NTHR; ++k) {
+        const int q = threadIdx.x + k * NTHR;
+        if (q < TP) {
+            lse_s[q] = -8.f * lq[k];
+            if (q < 64) store_extra(Qs + (q >> 5) * 32 * kTS + (q & 31) * kTS, -8.f * lq[k]);
+        }
+    }
+    __syncthreads();
+    const float cexp = kScale * kLog2e;
+    // LDS area in which a wavefront turns a transposed [64 channels][32 rows] result into 16-byte row pieces
+    // ([32][72] bf16): the dQ wavefront has its own; the key wavefronts use theirs once, after the last step,
+    // in the space of the query tiles
+    bf16* const stage = wave < KT ? Qs + wave * (32 * 72) : dq_stage;
+    float* const bout = bsum ? bsum + (long)b * ld_bsum + j * 192 : nullptr;
+
+    // The two kinds of wavefront run their own copy of the step loop (each keeps a different set of values in
+    // registers for the whole kernel); both copies meet the same barriers.
+    if (wave < KT) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kfr[kk] = frag_rows(Ks, kTS, u * 32 + c, kk * 16 + 8 * h);
+        f32x16 dKt[2], dVt[2];   // dK^T and dV^T of the key tile: rows = channels, column = key c
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            dKt[dt] = zero16();
+            dVt[dt] = zero16();
+        }
+        const float key_on = (u * 32 + c) < tokens ? 1.f : 0.f;   // keys beyond the last token: P = 0
+        // S - 8 lse of query tile t against this wavefront's key tile (kept for two steps: [t & 1])
+        f32x16 sc[2];
+        {
+            f32x16 s0 = zero16();
+#pragma unroll
+            for (int kk = 0; kk < 5; ++kk)
+                s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kTS, c, kk * 16 + 8 * h), kfr[kk], s0, 0, 0, 0);
+            sc[0] = s0;
+        }
+        static_for<KT + 1>([&](auto step_index) {
+            constexpr int i = decltype(step_index)::value;
+            if (i > 0) __syncthreads();   // every wavefront is done with step i - 1
+            if (i + 2 < KT) {   // tile i + 2 is read from the next step on; its buffer held tile i - 1
+                store_tile(i + 2, ring[(i + 2) % kAhead], true);
+                fetch_tile(i + 2 + kAhead, ring[(i + 2) % kAhead]);
+            }
+            if (i < KT) {
+                // Issue order of a step: all fragment reads; dP of this tile and S of the next one on the matrix
+                // cores with the exponentials of this tile's S (computed one step ago) between them on the vector
+                // ALUs; dV with dS and its hand-over between the MFMAs; dK, which runs under the next step's reads.
+                const bf16* Qi = Qs + (i % 3) * 32 * kTS;
+                const bf16* dOi = dOs + (i % 3) * 32 * kTS;
+                const bf16* Qn = Qs + ((i + 1) % 3) * 32 * kTS;
+                bf16x8 dof[5], qnf[5], dot[2][2], qt[2][2];
+#pragma unroll
+                for (int kk = 0; kk < 5; ++kk) dof[kk] = frag_rows(dOi, kTS, c, kk * 16 + 8 * h);
+                if (i + 1 < KT) {
+#pragma unroll
+                    for (int kk = 0; kk < 5; ++kk) qnf[kk] = frag_rows(Qn, kTS, c, kk * 16 + 8 * h);
+                }
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt) {
+                        dot[gp][dt] = frag_tr(dOi, kTS, 16 * gp, dt * 32, lane);
+                        qt[gp][dt] = frag_tr(Qi, kTS, 16 * gp, dt * 32, lane);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                f32x16 dp = zero16(), sn = zero16();   // dP - delta, and S - 8 lse of the next tile
+                f32x16& s = sc[i & 1];
+#pragma unroll
+                for (int kk = 0; kk < 5; ++kk) {
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dof[kk], vfr[kk], dp, 0, 0, 0);
+                    if (i + 1 < KT) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qnf[kk], kfr[kk], sn, 0, 0, 0);
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[e] = __builtin_amdgcn_exp2f(s[e] * cexp) * key_on;   // P
+                bf16x8 pf[2];
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) pf[gp] = pack8(s, 8 * gp);
+                {
+                    constexpr int NM = 5 + (i + 1 < KT ? 5 : 0);   // MFMAs of this phase; 56 vector ALU instructions
+#pragma unroll
+                    for (int k = 0; k < NM; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (56 + NM - 1) / NM, 0);
+                    }
+                }
+                if (i + 1 < KT) sc[(i + 1) & 1] = sn;
+                __builtin_amdgcn_sched_barrier(0);
+                bf16* dSs = dSs_all + ((i & 1) * KT + wave) * 32 * 32;
+                f32x16 ds;
+                bf16x8 dsf[2];
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+                        dVt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot[gp][dt], pf[gp], dVt[dt], 0, 0, 0);
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    // element e = 4 * eg + k is query 8 * eg + 4 * h + k of the tile
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) ds[4 * eg + k] = s[4 * eg + k] * dp[4 * eg + k];
+                    // hand dS to the dQ wavefront: [key][query] tile, 8-byte writes
+                    uint2 pk;
+                    pk.x = pack_bf16x2(ds[4 * eg], ds[4 * eg + 1]);
+                    pk.y = pack_bf16x2(ds[4 * eg + 2], ds[4 * eg + 3]);
+                    *reinterpret_cast<uint2*>(dSs + c * 32 + 8 * eg + 4 * h) = pk;
+                }
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) dsf[gp] = pack8(ds, 8 * gp);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {   // 4 MFMAs; 16 products, 16 conversions, 4 stores
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+                        dKt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[gp][dt], dsf[gp], dKt[dt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        // dK^T, dV^T through the wavefront's LDS area so that a key row leaves as 16-byte pieces
+        __syncthreads();   // the query tiles are free
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                 for (int eg = 0; eg < 4; ++eg) {
-                    const int d = dt * 32 + 8 * eg + 4 * h;
+                    const f32x16& a = m == 0 ? dKt[dt] : dVt[dt];
+                    const float sc4 = m == 0 ? kScale : 1.f;
                     uint2 pk;
-                    pk.x = pack_bf16x2(dKt[dt][4 * eg] * kScale, dKt[dt][4 * eg + 1] * kScale);
-                    pk.y = pack_bf16x2(dKt[dt][4 * eg + 2] * kScale, dKt[dt][4 * eg + 3] * kScale);
-                    *reinterpret_cast<uint2*>(krow + d) = pk;
-                    pk.x = pack_bf16x2(dVt[dt][4 * eg], dVt[dt][4 * eg + 1]);
-                    pk.y = pack_bf16x2(dVt[dt][4 * eg + 2], dVt[dt][4 * eg + 3]);
-                    *reinterpret_cast<uint2*>(vrow + d) = pk;
+                    pk.x = pack_bf16x2(a[4 * eg] * sc4, a[4 * eg + 1] * sc4);
+                    pk.y = pack_bf16x2(a[4 * eg + 2] * sc4, a[4 * eg + 3] * sc4);
+                    *reinterpret_cast<uint2*>(stage + c * 72 + dt * 32 + 8 * eg + 4 * h) = pk;
                 }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int id = lane + 64 * k, r = id >> 3, ch = (id & 7) * 8;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * 72 + ch);
+                const int key = u * 32 + r;
+                if (key < tokens) *reinterpret_cast<u32x4*>(dQb + (long)key * ld_dqkv + 64 + 64 * m + ch) = v;
+            }
+            if (bsum) {   // uniform over the grid
+                // Column sums of the staged tile (the values as they are stored; rows beyond the last token are
+                // zero): lane (p = lane % 32, half = lane / 32) adds channels 2p, 2p + 1 over rows 16 half .. + 15
+                float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t w = *reinterpret_cast<const uint32_t*>(stage + (16 * h + r) * 72 + 2 * c);
+                    s0 += __uint_as_float(w << 16);
+                    s1 += __uint_as_float(w & 0xffff0000u);
+                }
+                s0 += __shfl_xor(s0, 32, 64);
+                s1 += __shfl_xor(s1, 32, 64);
+                if (h == 0) {
+                    red[wave * 128 + 64 * m + 2 * c] = s0;
+                    red[wave * 128 + 64 * m + 2 * c + 1] = s1;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (bsum) __syncthreads();   // the per-tile sums are complete
+    } else {
+        // the dQ wavefront keeps all of K^T as operand fragments: [key tile][16-key half][channel half]
+        bf16x8 ktf[KT][2][2];
+#pragma unroll
+        for (int v = 0; v < KT; ++v)
+#pragma unroll
+            for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) ktf[v][gp][dt] = frag_tr(Ks, kTS, v * 32 + 16 * gp, dt * 32, lane);
+        // column sums of dQ: lane (p = lane % 32, half = lane / 32) adds channels 2p, 2p + 1 over rows 16 half .. + 15 of
+        // every staged tile (the values as they are stored)
+        float qsum0 = 0.f, qsum1 = 0.f;
+#pragma unroll
+        for (int i = 0; i <= KT; ++i) {
+            if (i > 0) __syncthreads();   // the dS tiles of query tile i - 1 are visible
+            if (i + 2 < KT) {
+                store_tile(i + 2, ring[(i + 2) % kAhead], true);
+                fetch_tile(i + 2 + kAhead, ring[(i + 2) % kAhead]);
+            }
+            if (i >= 1) {
+                // dQ^T of query tile i - 1: rows = channels, column = query c; four MFMA chains (channel half x
+                // 16-key half), added pairwise at the end.  The dS fragments of key tile v + 1 are read from LDS
+                // while the products of key tile v run.
+                const int t = i - 1;
+                const bf16* dSt = dSs_all + ((t & 1) * KT) * 32 * 32;
+                f32x16 acc[2][2] = {{zero16(), zero16()}, {zero16(), zero16()}};
+                bf16x8 dsf[2][2];   // [buffer][16-key half]
+                auto read_group = [&](int v, int buf) {
+#pragma unroll
+                    for (int gp = 0; gp < 2; ++gp)
+                        dsf[buf][gp] = frag_tr(dSt + v * 32 * 32, 32, 16 * gp, 0, lane);   // column = query c, slots = keys
+                };
+                read_group(0, 0);
+#pragma unroll
+                for (int v = 0; v < KT; ++v) {
+                    if (v + 1 < KT) read_group(v + 1, (v + 1) & 1);
+#pragma unroll
+                    for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                        for (int dt = 0; dt < 2; ++dt)
+                            acc[gp][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[v][gp][dt], dsf[v & 1][gp], acc[gp][dt], 0, 0, 0);
+                    if (v + 1 < KT) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read of the next group
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // through the wavefront's LDS area, so that a query row leaves as 16-byte pieces
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    f32x16 r;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) r[e] = (acc[0][dt][e] + acc[1][dt][e]) * kScale;
+#pragma unroll
+                    for (int eg = 0; eg < 4; ++eg) {
+                        uint2 pk;
+                        pk.x = pack_bf16x2(r[4 * eg], r[4 * eg + 1]);
+                        pk.y = pack_bf16x2(r[4 * eg + 2], r[4 * eg + 3]);
+                        *reinterpret_cast<uint2*>(stage + c * 72 + dt * 32 + 8 * eg + 4 * h) = pk;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int id = lane + 64 * k, r = id >> 3, ch = (id & 7) * 8;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * 72 + ch);
+                    if (t * 32 + r < tokens) *reinterpret_cast<u32x4*>(dQb + (long)(t * 32 + r) * ld_dqkv + ch) = v;
+                }
+                if (bsum) {   // rows beyond the last token are zero
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const uint32_t w = *reinterpret_cast<const uint32_t*>(stage + (16 * h + r) * 72 + 2 * c);
+                        qsum0 += __uint_as_float(w << 16);
+                        qsum1 += __uint_as_float(w & 0xffff0000u);
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        __syncthreads();   // matches the key wavefronts' barrier before their stores
+        if (bsum) {
+            qsum0 += __shfl_xor(qsum0, 32, 64);
+            qsum1 += __shfl_xor(qsum1, 32, 64);
+            if (h == 0) {
+                bout[2 * c] = qsum0;
+                bout[2 * c + 1] = qsum1;
+            }
+            __syncthreads();
         }
     }
+    if (bsum && threadIdx.x < 128) {   // dK and dV sums: key tiles added in index order
+        float t = 0.f;
+#pragma unroll
+        for (int v = 0; v < KT; ++v) t += red[v * 128 + threadIdx.x];
+        bout[64 + threadIdx.x] = t;
+    }
+}
+
+template <int KT>
+constexpr size_t bwd_lds_bytes() {
+    constexpr int TP = KT * 32;
+    static_assert(KT * 32 * 72 <= 6 * 32 * kTS, "the key wavefronts' store staging fits the query tiles' space");
+    constexpr size_t tiles = (size_t)(TP * kTS + 6 * 32 * kTS + 2 * KT * 32 * 32 + 32 * 72) * sizeof(bf16) +
+                             (size_t)(2 * TP + KT * 128) * sizeof(float);
+    return tiles;
 }
 
 template <int KT, typename Mask>
 hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, const float* lse, const bf16* d_o, long ld_do,
-                         bf16* dqkv, long ld_dqkv, int batch, int tokens, int n_full, const Mask& mask, hipStream_t s) {
-    constexpr int TP = KT * 32;
-    constexpr size_t lds = (size_t)(TP * kTS + TP * kKS + 2 * 32 * kTS + kBwdWaves * 32 * 32) * sizeof(bf16) +
-                           (size_t)(2 * TP + 4 * 64 * 32) * sizeof(float);
+                         bf16* dqkv, long ld_dqkv, float* bsum, long ld_bsum, int batch, int tokens, int n_full,
+                         const Mask& mask, hipStream_t s) {
+    constexpr size_t lds = bwd_lds_bytes<KT>();
+    static_assert(lds <= 160 * 1024, "the pair's tiles must fit a compute unit's LDS");
     auto kern = attn_bwd_mfma_kernel<KT, Mask>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -536,8 +788,8 @@ hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * kBwdWaves), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv,
-                       ld_dqkv, tokens, n_full, (long)batch * tokens, mask);
+    hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * (KT + 1)), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv,
+                       ld_dqkv, bsum, ld_bsum, tokens, n_full, (long)batch * tokens, mask);
     return hipGetLastError();
 }
 
@@ -545,6 +797,11 @@ hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, con
 
 bool attn_mfma_supported(int tokens, long ldq, long ldo) {
     return tokens >= 1 && tokens <= 256 && (ldq % 8) == 0 && (ldo % 8) == 0;
+}
+// The backward keeps one wavefront per 32-key tile plus one for dQ at up to 256 registers each, which a
+// compute unit holds for at most seven key tiles.
+bool attn_bwd_mfma_supported(int tokens, long ldq, long ldo) {
+    return attn_mfma_supported(tokens, ldq, ldo) && tokens <= 224;
 }
 
 template <typename Mask>
@@ -590,36 +847,38 @@ namespace d2ft {
 
 template <typename Mask>
 static hipError_t attn_bwd_dispatch(const void* qkv, long ldq, const void* o, long ldo, const float* lse, const void* d_o,
-                                    long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens, int n_full,
-                                    const Mask& mask, hipStream_t s) {
+                                    long ld_do, void* dqkv, long ld_dqkv, float* bsum, long ld_bsum, int batch, int tokens,
+                                    int n_full, const Mask& mask, hipStream_t s) {
     if (n_full <= 0) return hipSuccess;
     const bf16* q = static_cast<const bf16*>(qkv);
     const bf16* op = static_cast<const bf16*>(o);
     const bf16* dop = static_cast<const bf16*>(d_o);
     bf16* dq = static_cast<bf16*>(dqkv);
 #define D2FT_BWD_CASE(KT) \
-    case KT: return launch_bwd_kt<KT, Mask>(q, ldq, op, ldo, lse, dop, ld_do, dq, ld_dqkv, batch, tokens, n_full, mask, s);
+    case KT: return launch_bwd_kt<KT, Mask>(q, ldq, op, ldo, lse, dop, ld_do, dq, ld_dqkv, bsum, ld_bsum, batch, tokens, n_full, mask, s);
     switch ((tokens + 31) / 32) {
         D2FT_BWD_CASE(1) D2FT_BWD_CASE(2) D2FT_BWD_CASE(3) D2FT_BWD_CASE(4)
-        D2FT_BWD_CASE(5) D2FT_BWD_CASE(6) D2FT_BWD_CASE(7) D2FT_BWD_CASE(8)
+        D2FT_BWD_CASE(5) D2FT_BWD_CASE(6) D2FT_BWD_CASE(7)
         default: return hipErrorNotSupported;
     }
 #undef D2FT_BWD_CASE
 }
 
 hipError_t launch_attn_bwd_mfma(const void* qkv, long ldq, const void* o, long ldo, const float* lse, const void* d_o,
-                                long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens, int n_full,
-                                hipStream_t s) {
-    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, n_full, WholeBatch{}, s);
+                                long ld_do, void* dqkv, long ld_dqkv, float* bsum, long ld_bsum, int batch, int tokens,
+                                int n_full, hipStream_t s) {
+    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, bsum, ld_bsum, batch, tokens, n_full,
+                             WholeBatch{}, s);
 }
 
 hipError_t launch_attn_bwd_mfma_masked(const void* qkv, long ldq, const void* o, long ldo, const float* lse,
-                                       const void* d_o, long ld_do, void* dqkv, long ld_dqkv, int batch, int tokens,
-                                       int n_full, const MicroMask& mask, hipStream_t s) {
+                                       const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* bsum, long ld_bsum,
+                                       int batch, int tokens, int n_full, const MicroMask& mask, hipStream_t s) {
     if (n_full != mask.n_full_pos) return hipErrorInvalidValue;
     if (n_full <= 0) return hipSuccess;
     const int slots = busiest(mask.full, mask.n);
-    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, batch, tokens, slots > 0 ? slots : 1, mask, s);
+    return attn_bwd_dispatch(qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv, ld_dqkv, bsum, ld_bsum, batch, tokens,
+                             slots > 0 ? slots : 1, mask, s);
 }
 
 }  // namespace d2ft

@@ -418,6 +418,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         const int nb = en0 + wn * WTN + (lane % CPR) * 8;
         if (!P && bias && nb < g.N) braw = *reinterpret_cast<const u32x4*>(bias + (g.bias_remap ? g.tbl(nb) : nb));
     }
+    // column sums of the tile's results (the bias gradient of the layer that produced the GEMM's input):
+    // a lane adds up its 8 columns over all its rows, the lanes that share columns are combined at the
+    // end of the tile, and the wavefront's WTM-row band becomes one row of g.colsum
+    constexpr bool kColsum = !A_COL;   // weight-gradient forms (A with K strided) never ask for it
+    float csum[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) csum[i] = 0.f;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
 #pragma unroll
@@ -471,10 +478,30 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                         for (int i = 0; i < 8; ++i) v[i] += rr[i];
                     }
                     store8(C + (long)m * g.ldc + n, v);
+                    if constexpr (kColsum) {
+                        if (g.colsum) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) csum[i] += v[i];
+                        }
+                    }
                 }
             }
         }
         __builtin_amdgcn_wave_barrier();
+    }
+    if (kColsum && g.colsum) {   // uniform over the grid
+        static_assert(CPR == 8, "lanes 8 apart share their columns");
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float t = csum[i];
+            t += __shfl_xor(t, 8, 64);
+            t += __shfl_xor(t, 16, 64);
+            t += __shfl_xor(t, 32, 64);
+            csum[i] = t;
+        }
+        const int n = en0 + wn * WTN + lane * 8;
+        if (lane < CPR && n < g.N)
+            store8(g.colsum + (long)(g.colsum_row0 + (em0 / BM) * WGM + wm) * g.N + n, csum);
     }
     __syncthreads();   // the stage area is operand buffer space of the next tile
     }
@@ -567,6 +594,7 @@ bool gemm_mfma_supported(const GemmArgs& g) {
     }
     const long b_span = b_row ? b_n * g.b_cs : b_k * g.b_rs;
     if (a_span * 2 >= (1L << 31) || b_span * 2 >= (1L << 31)) return false;
+    if (g.colsum && (g.partial || g.a_cs != 1 || !al16(g.colsum))) return false;
     if (g.partial) return al16(g.partial);
     if (!g.C || !al16(g.C) || !mult8(g.ldc)) return false;
     if (g.bias && !al16(g.bias)) return false;
@@ -587,6 +615,11 @@ static int pick_tile(const GemmArgs& g) {
     const long mid = (long)((g.M + 191) / 192) * tn * splits;
     if (big < 256 && mid <= 256 && mid > big) return 3;
     return 1;
+}
+
+int gemm_mfma_tile_rows(const GemmArgs& g) {
+    const int tile = pick_tile(g);
+    return tile == 0 ? 128 : (tile == 3 ? 192 : 256);
 }
 
 const char* gemm_mfma_config_name(const GemmArgs& g) {

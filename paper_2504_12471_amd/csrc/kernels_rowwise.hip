@@ -185,6 +185,135 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ d, co
 }
 
 // ---------------------------------------------------------------------------
+// The same backward, also summing columns: of the residual it adds (sum_res) and of the result it
+// writes (sum_out) - the gradients of the two biases that sit on the residual stream on either side
+// of the feed-forward network.  A workgroup owns kLnSumRows consecutive rows, a wavefront every
+// fourth of them; while a wavefront works on one row the loads of its next row are in flight.  The
+// wavefront keeps the column sums of its rows in registers, the four wavefronts' sums are added
+// through LDS in a fixed order, and the workgroup writes one row of partial sums: [gridDim.x][width].
+// ---------------------------------------------------------------------------
+constexpr int kLnSumRows = 16;
+
+// 8 consecutive elements as they sit in memory, unpacked to fp32 on use
+template <typename T> struct Raw8;
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p) {
+        a = *reinterpret_cast<const float4*>(p);
+        b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void get(float (&o)[8]) const {
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+};
+template <> struct Raw8<bf16> {
+    uint4 r;
+    __device__ __forceinline__ void load(const bf16* p) { r = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void get(float (&o)[8]) const {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = __uint_as_float(w[i] << 16);
+            o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void ln_bwd_sums_kernel(const T* __restrict__ d, const T* __restrict__ x,
+                                                          const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                          const T* __restrict__ gamma, const T* res, T* dx, int rows,
+                                                          int width, float* __restrict__ sum_res,
+                                                          float* __restrict__ sum_out) {
+    __shared__ float red[4][NV * 512];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float sr[NV][8], so[NV][8], g[NV][8];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = (j * 64 + lane) * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sr[j][i] = so[j][i] = g[j][i] = 0.f;
+        if (c < width) load8(gamma + c, g[j]);
+    }
+    Raw8<T> nd[NV], nx[NV], nr[NV];   // the next row's d, x, res
+    float nmu = 0.f, nrs = 0.f;
+    auto fetch = [&](int row) {
+        if (row < rows) {
+            const long off = (long)row * width;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int c = (j * 64 + lane) * 8;
+                if (c < width) {
+                    nd[j].load(d + off + c);
+                    nx[j].load(x + off + c);
+                    nr[j].load(res + off + c);
+                }
+            }
+            nmu = mean[row];
+            nrs = rstd[row];
+        }
+    };
+    const int row0 = blockIdx.x * kLnSumRows + wave;
+    fetch(row0);
+#pragma unroll
+    for (int it = 0; it < kLnSumRows / 4; ++it) {
+        const int row = row0 + it * 4;
+        if (row >= rows) break;
+        const long off = (long)row * width;
+        const float mu = nmu, rs = nrs;
+        float dh[NV][8], xh[NV][8], r[NV][8];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+                float dv[8], xv[8];
+                nd[j].get(dv);
+                nx[j].get(xv);
+                nr[j].get(r[j]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    dh[j][i] = dv[i] * g[j][i];
+                    xh[j][i] = (xv[i] - mu) * rs;
+                    s1 += dh[j][i];
+                    s2 += dh[j][i] * xh[j][i];
+                }
+            }
+        }
+        if (it + 1 < kLnSumRows / 4) fetch(row + 4);   // in flight under the reductions and the stores below
+        const float m1 = wave_sum(s1) / (float)width;
+        const float m2 = wave_sum(s2) / (float)width;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            if (c < width) {
+                float o[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    o[i] = rs * (dh[j][i] - m1 - xh[j][i] * m2) + r[j][i];
+                    sr[j][i] += r[j][i];
+                    so[j][i] += o[i];
+                }
+                store8(dx + off + c, o);
+            }
+        }
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+        float* out = pass == 0 ? sum_res : sum_out;   // uniform over the grid
+        if (!out) continue;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = (j * 64 + lane) * 8;
+            store8(&red[wave][c], pass == 0 ? sr[j] : so[j]);
+        }
+        __syncthreads();
+        for (int c = threadIdx.x; c < width; c += 256)
+            out[(long)blockIdx.x * width + c] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
 // column sums over a chunk of rows.  A workgroup covers 256 columns (32 lanes x 8 columns, 16-byte
 // loads) and 8 row lanes; LN = true sums d*xhat and d (LayerNorm scale / shift gradients).
 // ---------------------------------------------------------------------------
@@ -292,27 +421,40 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 }
 
 // ---------------------------------------------------------------------------
-// up to four column reductions in one launch: blockIdx.y picks the job; chunks are added in index
-// order, eight loads in flight at a time (the same order as reduce_partials_kernel on one row)
+// up to four column reductions in one launch: blockIdx.y picks the job.  A workgroup owns 32 columns
+// (8 threads x 4 columns) and spreads the chunks over 32 row lanes: lane l adds chunks l, l + 32, ... in
+// index order (eight loads in flight at a time), then the 32 lanes' sums are added in lane order.
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void col_reduce_batch_kernel(ColReduceBatch batch, int accumulate, Remap64 tbl_a,
                                                                 Remap64 tbl_b) {
+    __shared__ float4 red[32][8];
     const ColReduceJob job = batch.job[blockIdx.y];
-    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
-    if (c >= job.cols) return;
+    const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+    const int c = blockIdx.x * 32 + cg * 4;
+    if (blockIdx.x * 32 >= job.cols) return;   // uniform over the workgroup
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float* src = job.partial + c;
-    int k = 0;
-    for (; k + 8 <= job.chunks; k += 8) {
-        float4 v[8];
+    if (c < job.cols) {
+        const float* src = job.partial + c;
+        int k = rl;
+        for (; k + 7 * 32 < job.chunks; k += 8 * 32) {
+            float4 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4*>(src + (long)(k + j) * job.cols);
+            for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4*>(src + (long)(k + 32 * j) * job.cols);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
+            for (int j = 0; j < 8; ++j) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
+        }
+        for (; k < job.chunks; k += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(src + (long)k * job.cols);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
     }
-    for (; k < job.chunks; ++k) {
-        const float4 v = *reinterpret_cast<const float4*>(src + (long)k * job.cols);
+    red[rl][cg] = s;
+    __syncthreads();
+    if (rl != 0 || c >= job.cols) return;
+#pragma unroll 8
+    for (int l = 1; l < 32; ++l) {
+        const float4 v = red[l][cg];
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
     T* o = static_cast<T*>(job.out) + (job.remap_cols == 1 ? tbl_a(c) : (job.remap_cols == 2 ? tbl_b(c) : c));
@@ -642,6 +784,23 @@ hipError_t launch_ln_fwd(int dtype, const void* x, const void* gamma, const void
     return hipGetLastError();
 }
 
+bool ln_bwd_sums_supported(int width) { return width <= 2048; }
+int ln_bwd_sums_bands(int rows) { return (rows + kLnSumRows - 1) / kLnSumRows; }
+
+hipError_t launch_ln_bwd_sums(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
+                              const void* gamma, const void* res, void* dx, int rows, int width, float* sum_res,
+                              float* sum_out, hipStream_t s) {
+    if (!ln_bwd_sums_supported(width) || !res) return hipErrorNotSupported;
+    const dim3 grid(ln_bwd_sums_bands(rows)), block(256);
+#define D2FT_LN_BWD_SUMS(NV)                                                                                         \
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL((ln_bwd_sums_kernel<T, NV>), grid, block, 0, s, (const T*)d, (const T*)x, \
+                                            mean, rstd, (const T*)gamma, (const T*)res, (T*)dx, rows, width, sum_res,  \
+                                            sum_out);)
+    if (width <= 512) { D2FT_LN_BWD_SUMS(1) } else if (width <= 1024) { D2FT_LN_BWD_SUMS(2) } else { D2FT_LN_BWD_SUMS(4) }
+#undef D2FT_LN_BWD_SUMS
+    return hipGetLastError();
+}
+
 hipError_t launch_ln_bwd(int dtype, const void* d, const void* x, const float* mean, const float* rstd,
                          const void* gamma, const void* res, void* dx, int rows, int width, hipStream_t s) {
     const dim3 grid((rows + 3) / 4), block(256);
@@ -701,7 +860,7 @@ hipError_t launch_col_reduce_batch(int dtype, const ColReduceBatch& batch, const
     if (batch.n <= 0) return hipSuccess;
     int cols = 0;
     for (int i = 0; i < batch.n; ++i) cols = batch.job[i].cols > cols ? batch.job[i].cols : cols;   // multiples of 8
-    const dim3 grid((unsigned)((cols / 4 + 255) / 256), batch.n), block(256);
+    const dim3 grid((unsigned)((cols + 31) / 32), batch.n), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL(col_reduce_batch_kernel<T>, grid, block, 0, s, batch, accumulate, tbl_a, tbl_b);)
     return hipGetLastError();
 }

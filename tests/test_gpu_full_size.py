@@ -100,9 +100,13 @@ def check_whole_stack(name):
         for k in BASE_FIELDS:
             errs[f"d{k}[{l}]"] = rel_inf(grads[l][k], rgrads[l][k])
     worst = sorted(errs, key=errs.get)[-3:]
-    print(f"[{name} whole stack, {w.blocks} blocks] y={errs['y']:.2e} dx={errs['dx']:.2e} worst: "
+    # The hidden state is rounded to the storage type twice per block and those roundings are independent,
+    # so over a chain of L blocks they add in quadrature: the bar of one step through 12 blocks (2e-2) is
+    # scaled by sqrt(L / 12) for deeper stacks.  Every block on its own is held to 2e-2 above.
+    tol = TOL[w.dtype] * max(1.0, (w.blocks / 12.0) ** 0.5)
+    print(f"[{name} whole stack, {w.blocks} blocks, bar {tol:.2e}] y={errs['y']:.2e} dx={errs['dx']:.2e} worst: "
           + " ".join(f"{k}={errs[k]:.2e}" for k in worst), flush=True)
-    assert all(v <= TOL[w.dtype] for v in errs.values()), {k: v for k, v in errs.items() if not v <= TOL[w.dtype]}
+    assert all(v <= tol for v in errs.values()), {k: v for k, v in errs.items() if not v <= tol}
 
 
 @pytest.mark.parametrize("l", range(12))

@@ -61,7 +61,7 @@ def test_full_step(dtype, gate):
     P.d2ft_patch_embed_bwd(edesc, dtokd, ge["w_pe"], ge["b_pe"], ge["cls"], ge["pos"], esaved, escr)
     torch.cuda.synchronize()
 
-    tol = 1e-4 if dtype == "f32" else 3e-2      # bf16: rounding accumulates through the whole network
+    tol = 1e-4 if dtype == "f32" else 2e-2
     assert abs(loss - rloss) <= tol * max(1.0, abs(rloss)), (loss, rloss)
     errs = {"dtokens": rel_inf(dtokd.float().cpu().numpy(), dtok)}
     for k in ge:
