@@ -349,7 +349,7 @@ d2ft_status d2ft_classifier_fwd_bwd(const d2ft_head_desc *desc, const void *toke
  * the paper's compute-cost claim of Sec. IV-A on this hardware).  Not thread safe.
  *   out  HOST [max_entries] */
 typedef struct d2ft_kernel_time {
-    char name[64];
+    char name[96];
     int64_t launches;
     double ms;
     double flops;

@@ -101,7 +101,7 @@ _lib.d2ft_sgd_step.argtypes = [C.POINTER(BlockDesc), C.POINTER(_Ptrs), C.POINTER
 
 
 class KernelTime(C.Structure):
-    _fields_ = [("name", C.c_char * 64), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+    _fields_ = [("name", C.c_char * 96), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
 
 

@@ -94,6 +94,17 @@ struct Remap64 {
 enum { REMAP_NONE = 0, REMAP_B_N = 1, REMAP_B_K = 2 };
 enum { ACT_NONE = 0, ACT_GELU = 1, ACT_DGELU = 2 };
 
+// One problem of a grouped weight-gradient launch: C_g[m][n] = sum_k A_g[k][m] * B_g[k][n], k over the token
+// rows (both operands stored with k strided: lda, ldb are the row strides in elements)
+struct GemmGroup {
+    const void* A;
+    const void* B;
+    long lda, ldb;
+    int M, N;
+    int tiles_m, tile0;   // 256-row tiles of this problem; index of its first tile in the launch's tile list
+};
+constexpr int kMaxGemmGroups = 4;
+
 struct GemmArgs {
     const void* A;
     const void* B;
@@ -111,6 +122,11 @@ struct GemmArgs {
     float* partial;       // non-null: split-K mode, raw fp32 sums go to partial[split][M][N]
     int splits;
     int tile_hint;        // 0: kernel chooses its tile, 1: 256x256, 2: 128x128, 3: 192x256
+    // grouped mode (n_groups > 0; launch_gemm_grouped): the problems share K.  Every 256x256 tile of every
+    // problem is cut into `splits` runs of units_per_wg K slabs; unit u = split * total_tiles + tile leaves its
+    // fp32 sums in slot u of `partial` ([slots][256][256]); reduce_grouped adds a tile's slots in split order.
+    int n_groups, units_per_wg, slabs_per_tile, total_tiles;
+    GemmGroup grp[kMaxGemmGroups];
     float* colsum;        // non-null (MFMA path only): column sums of C's values over bands of rows, fp32
                           // [bands][N]; band = colsum_row0 + 2 * (row tile) + (upper / lower half of the tile)
     int colsum_row0;
@@ -122,6 +138,23 @@ hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
+// Grouped weight-gradient launch (bf16 MFMA only).  The caller fills K, partial, n_groups and grp[].{A, B, lda,
+// ldb, M, N}; the launcher fills the tile bookkeeping and returns it in *g for the reduction.  partial must hold
+// gemm_grouped_slots(g) tiles of 256 x 256 floats.  hipErrorNotSupported if an operand does not fit the kernel.
+size_t gemm_grouped_slots(const GemmArgs& g);
+hipError_t launch_gemm_grouped(GemmArgs* g, hipStream_t s);
+// out_g[r'][c'] (=|+=) sum over the slots of each tile, (r', c') through the group's remap
+struct ReduceGroup {
+    void* out;
+    long ldo;
+    int remap;      // RED_REMAP_*
+    int table;      // which of the tables the remap uses
+};
+struct ReduceGroupedArgs {
+    ReduceGroup grp[kMaxGemmGroups];
+    Remap64 tbl[3];
+};
+hipError_t launch_reduce_grouped(int dtype, const GemmArgs& g, const ReduceGroupedArgs& r, int accumulate, hipStream_t s);
 // rows of the output tile launch_gemm_mfma would pick (a tile makes two bands of g.colsum)
 int gemm_mfma_tile_rows(const GemmArgs& g);
 // static string naming the kernel instantiation launch_gemm_mfma would pick (for timing records)

@@ -97,6 +97,12 @@ ScratchLayout scratch_layout(const Dims& s) {
     if ((size_t)192 * s.H > cols) cols = 192 * s.H;
     if ((size_t)s.D > cols) cols = s.D;
     L.part_floats = mat * kMaxSplits;
+    {   // or one 256 x 256 tile per (workgroup, tile) pair of the grouped weight-gradient launch
+        auto t256 = [](size_t r, size_t c) { return ((r + 255) / 256) * ((c + 255) / 256); };
+        const size_t tiles = 2 * t256(s.Dm, s.D) + t256(s.D, (size_t)64 * s.H) + t256((size_t)192 * s.H, s.D);
+        const size_t grouped = tiles * 8 * 65536;   // up to 8 splits
+        if (grouped > L.part_floats) L.part_floats = grouped;
+    }
     L.part = take(L.part_floats * 4);
     L.colpart_stride = (size_t)kColChunks * cols;   // floats per region: four bias reductions, two LayerNorm ones
     L.colpart = take(6 * L.colpart_stride * 4);
@@ -405,6 +411,71 @@ d2ft_status weight_grad(const d2ft_block_desc* d, const Dims& s, const void* Aop
     return D2FT_OK;
 }
 
+// The weight gradients of one backward call, collected and run as ONE grouped launch at the end of the call:
+// each is a reduction over the token rows, and together they have enough tiles to fill the chip with about a
+// third of the split-K partial traffic that separate launches need.
+struct WeightGradBatch {
+    bool enabled;
+    GemmArgs g;
+    ReduceGroupedArgs r;
+};
+
+void weight_grad_batch_init(WeightGradBatch* b, const d2ft_block_desc* d) {
+    memset(b, 0, sizeof(*b));
+    b->g.splits = 1;
+    b->enabled = d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA);
+}
+
+// queue dW[out_rows][out_cols] = Aop^T Bop (arguments as weight_grad); table_slot: which of the batch's three
+// remap tables tbl is kept in
+d2ft_status weight_grad_queue(WeightGradBatch* b, const d2ft_block_desc* d, const Dims& s, const void* Aop, long lda,
+                              const void* Bop, long ldb, int out_rows, int out_cols, float* part, void* out, long ldo,
+                              int red_remap, const Remap64& tbl, int table_slot, hipStream_t st) {
+    if (!b->enabled || b->g.n_groups >= kMaxGemmGroups)
+        return weight_grad(d, s, Aop, lda, Bop, ldb, out_rows, out_cols, part, out, ldo, red_remap, tbl, st);
+    const int i = b->g.n_groups++;
+    GemmGroup& G = b->g.grp[i];
+    G.A = Aop; G.lda = lda; G.B = Bop; G.ldb = ldb; G.M = out_rows; G.N = out_cols;
+    ReduceGroup& R = b->r.grp[i];
+    R.out = out; R.ldo = ldo; R.remap = red_remap; R.table = table_slot;
+    b->r.tbl[table_slot] = tbl;
+    return D2FT_OK;
+}
+
+d2ft_status weight_grad_flush(WeightGradBatch* b, const d2ft_block_desc* d, const Dims& s, float* part, size_t part_floats,
+                              hipStream_t st) {
+    if (b->g.n_groups == 0) return D2FT_OK;
+    GemmArgs& g = b->g;
+    g.K = (int)s.M;
+    g.partial = part;
+    const int accum = (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
+    hipError_t e = hipErrorNotSupported;
+    if (gemm_grouped_slots(g) * 65536 <= part_floats) {
+        timing_begin(st, "gemm");
+        g_timing.label = "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 0, false, true>";
+        for (int i = 0; i < g.n_groups; ++i) g_timing.flops += 2.0 * g.grp[i].M * g.grp[i].N * s.M;
+        e = launch_gemm_grouped(&g, st);
+        timing_end(st);
+    }
+    if (e == hipSuccess) {
+        // every (workgroup, tile) partial is read once, every output element written once
+        const double nbytes = 4.0 * 65536 * g.total_tiles * g.splits;
+        D2FT_TRY_BYTES(nbytes, launch_reduce_grouped(s.dtype, g, b->r, accum, st));
+    } else if (e == hipErrorNotSupported) {   // an operand the grouped kernel does not take: one launch per gradient
+        for (int i = 0; i < g.n_groups; ++i) {
+            const GemmGroup& G = g.grp[i];
+            const ReduceGroup& R = b->r.grp[i];
+            const d2ft_status rc = weight_grad(d, s, G.A, G.lda, G.B, G.ldb, G.M, G.N, part, R.out, R.ldo, R.remap,
+                                               b->r.tbl[R.table], st);
+            if (rc != D2FT_OK) return rc;
+        }
+    } else {
+        return D2FT_EDEVICE;
+    }
+    g.n_groups = 0;
+    return D2FT_OK;
+}
+
 // bias gradient, first half: column sums of X over row chunks into its own partial region; the reduction
 // over the chunks is queued and done for all of a block's biases by one launch (flush_bias_grads)
 d2ft_status bias_grad(const Dims& s, const void* X, long ldx, int cols, float* region, void* out, int remap_cols,
@@ -672,10 +743,18 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     float* ln_part = colpart + 4 * WL.colpart_stride;
     ColReduceBatch bias_batch;
     memset(&bias_batch, 0, sizeof(bias_batch));
+    WeightGradBatch wgrads;
+    weight_grad_batch_init(&wgrads, desc);
     Remap64 none;
     memset(&none, 0, sizeof(none));
     const void* x1 = (half != PART_MLP && nl > 0) ? (const void*)(sva + SL.x1) : x;
     d2ft_status rc;
+    // the call's last launches: the collected weight gradients, then the bias reductions
+    auto finish = [&](const Remap64& tbl_a, const Remap64& tbl_b) -> d2ft_status {
+        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st);
+        if (rw != D2FT_OK) return rw;
+        return flush_bias_grads(desc, s, &bias_batch, tbl_a, tbl_b, st);
+    };
 
     // ---- feed-forward network: all of it, or (gated) the slices of the p_f heads, a prefix of the compacted layout ----
     const bool gate = (desc->flags & D2FT_FLAG_GATE_FFN) != 0;
@@ -714,8 +793,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     int b1_bands = 0;
     if (half != PART_ATTN && n_hid > 0) {
         if (grads->w2) {   // dW2[:, hidden] = dy^T g
-            rc = weight_grad(desc, s, dy, s.D, sv + SL.g, ld_hid, s.D, n_hid, part, grads->w2, s.Dm,
-                             gate ? RED_REMAP_COLS : RED_REMAP_NONE, ffn_tbl, st);
+            rc = weight_grad_queue(&wgrads, desc, s, dy, s.D, sv + SL.g, ld_hid, s.D, n_hid, part, grads->w2, s.Dm,
+                                   gate ? RED_REMAP_COLS : RED_REMAP_NONE, ffn_tbl, 0, st);
             if (rc != D2FT_OK) return rc;
         }
         {   // dz = (dy W2[:, hidden]) * GELU'(z)
@@ -732,8 +811,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (!g.colsum) b1_bands = 0;
         }
         if (grads->w1) {   // dW1[hidden] = dz^T v
-            rc = weight_grad(desc, s, ws + WL.dz, n_hid, sv + SL.v, s.D, n_hid, s.D, part, grads->w1, s.D,
-                             gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, st);
+            rc = weight_grad_queue(&wgrads, desc, s, ws + WL.dz, n_hid, sv + SL.v, s.D, n_hid, s.D, part, grads->w1, s.D,
+                                   gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, 0, st);
             if (rc != D2FT_OK) return rc;
         }
         if (grads->b1 && b1_bands > 0) {
@@ -779,7 +858,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         }
         dx1 = out;
     }
-    if (half == PART_MLP) return flush_bias_grads(desc, s, &bias_batch, none, ffn_tbl, st);
+    if (half == PART_MLP) return finish(none, ffn_tbl);
 
     // ---- attention side ----
     sv = sva;
@@ -810,7 +889,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             timing_end(st);
             if (e != hipSuccess) return D2FT_EDEVICE;
         }
-        return flush_bias_grads(desc, s, &bias_batch, none, ffn_tbl, st);
+        return finish(none, ffn_tbl);
     }
 
     const long ldq = (long)nl * 192, ldo = (long)nl * 64;
@@ -830,8 +909,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
     }
     if (grads->w_o) {   // dWo[:, head cols] = dx1^T O_h
-        rc = weight_grad(desc, s, dx1, s.D, sv + SL.o, ldo, s.D, nf * 64, part, grads->w_o, (long)s.H * 64, RED_REMAP_COLS,
-                         head_tbl, st);
+        rc = weight_grad_queue(&wgrads, desc, s, dx1, s.D, sv + SL.o, ldo, s.D, nf * 64, part, grads->w_o, (long)s.H * 64,
+                               RED_REMAP_COLS, head_tbl, 1, st);
         if (rc != D2FT_OK) return rc;
     }
     // the matrix-core attention backward also leaves per-image column sums of dQKV: the QKV bias gradient
@@ -841,7 +920,11 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                           ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), bqkv_part, s.B, s.T, nf, st, mask));
     const void* u = sv + SL.u;
     const bool want_lora = s.r > 0 && (grads->lora_a_q || grads->lora_a_v || grads->lora_b_q || grads->lora_b_v);
-    if (grads->w_qkv || want_lora) {   // G = dQKV^T u, rows in compacted order
+    if (grads->w_qkv && !want_lora) {   // dWqkv = dQKV^T u, rows scattered to the p_f heads' planes
+        rc = weight_grad_queue(&wgrads, desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D,
+                               RED_REMAP_ROWS, qkv_tbl, 2, st);
+        if (rc != D2FT_OK) return rc;
+    } else if (want_lora) {   // G = dQKV^T u, rows in compacted order
         int splits = 1;
         rc = weight_grad(desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D, RED_REMAP_ROWS, qkv_tbl,
                          st, &splits, grads->w_qkv != nullptr);
@@ -889,10 +972,14 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         if (grads->ln1_b)
             D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, accum, st));
     }
+    if (dx1 == dx) {   // the rows of dx1 are about to be rewritten in place: its weight gradients go first
+        rc = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st);
+        if (rc != D2FT_OK) return rc;
+    }
     // dx = dx1 + LN1bwd(du)
     D2FT_TRY_BYTES(4.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_bwd(s.dtype, ws + WL.du, x, (const float*)(sv + SL.mean1), (const float*)(sv + SL.rstd1), w->ln1_g,
                            dx1, dx, M, s.D, st));
-    return flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st);
+    return finish(qkv_tbl, ffn_tbl);
 }
 
 d2ft_status d2ft_block_bwd(const d2ft_block_desc* desc, const d2ft_block_weights* w, const uint8_t* ops,

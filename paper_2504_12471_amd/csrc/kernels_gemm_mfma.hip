@@ -232,7 +232,7 @@ __device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, i
     tn = in_group / gsize;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool GROUPED = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
@@ -260,6 +260,37 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     // the next tile ahead of the current tile's epilogue, and the epilogue's global stores drain while
     // the next tile is being multiplied.
     int m0 = 0, n0 = 0, split = 0, kb = 0, ke = 0, nslabs = 0;
+    // Grouped mode (weight gradients of several layers in one launch, all reducing over the same K): the work
+    // is the list of units (tile, split) = unit % total_tiles, unit / total_tiles; every tile's K is cut into
+    // g.splits equal runs of slabs.  Workgroup ids are renumbered so that the units of one XCD's workgroups are
+    // neighbouring tiles of the same split (they share operand slabs through its L2); a workgroup takes units
+    // id, id + grid, ... and leaves each unit's raw sums in partial slot `unit`.
+    constexpr bool grouped = GROUPED;
+    int unit = 0;
+    if constexpr (grouped) unit = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int piece_slot = 0;
+    auto setup_piece = [&]() -> bool {   // false when the workgroup's units are used up
+        if (!grouped || unit >= g.total_tiles * g.splits) return false;
+        const int t = unit % g.total_tiles, sp = unit / g.total_tiles;
+        int gi = 0;
+        while (gi + 1 < g.n_groups && t >= g.grp[gi + 1].tile0) ++gi;
+        const GemmGroup& G = g.grp[gi];
+        const int lt = t - G.tile0;
+        m0 = (lt % G.tiles_m) * BM;
+        n0 = (lt / G.tiles_m) * BN;
+        kb = sp * g.units_per_wg * BK;                    // units_per_wg: slabs per split
+        ke = min(g.K, kb + g.units_per_wg * BK);
+        la.template init<false>(static_cast<const bf16*>(G.A), 1, G.lda, m0, G.M, g.tbl);
+        lb.template init<false>(static_cast<const bf16*>(G.B), 1, G.ldb, n0, G.N, g.tbl);
+        nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
+        if (nslabs > 0) {
+            la.template load<false, KTAIL>(kb, ke, g.tbl);
+            lb.template load<false, KTAIL>(kb, ke, g.tbl);
+        }
+        piece_slot = unit;
+        unit += gridDim.x;
+        return true;
+    };
     auto setup_tile = [&](int pid) {
         int tile_m, tile_n;
         tile_of_block(pid, total, tiles_m, tiles_n, tile_m, tile_n, split);
@@ -319,8 +350,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     constexpr int NW = KA + SlabLoader<BN, BK, B_COL, kThreads>::kPerThread;   // stores = loads per slab
     static_assert(BK == 64, "the pipeline below is written for four MFMA groups per slab");
 
-    setup_tile(blockIdx.x);
-    for (int pid = blockIdx.x; pid < total; pid += gridDim.x) {
+    int pid = blockIdx.x;
+    bool have_work = true;
+    if constexpr (grouped) have_work = setup_piece(); else setup_tile(pid);
+    while (have_work) {
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -392,8 +425,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         if (s < nslabs) slab(s, no, no);
     }
     __syncthreads();   // the epilogue reuses the operand buffers
-    const int em0 = m0, en0 = n0, esplit = split;
-    if (pid + (int)gridDim.x < total) setup_tile(pid + gridDim.x);   // its first slab arrives under the epilogue
+    const int em0 = m0, en0 = n0, esplit = split, eslot = piece_slot;
+    // the next tile's first slab arrives under the epilogue
+    if constexpr (grouped) {
+        have_work = setup_piece();
+    } else {
+        pid += gridDim.x;
+        have_work = pid < total;
+        if (have_work) setup_tile(pid);
+    }
 
     // ---- epilogue ----
     // Accumulator element e of MFMA tile (t,u) is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
@@ -410,6 +450,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     const bf16* R = static_cast<const bf16*>(g.residual);
     bf16* Z = static_cast<bf16*>(g.Z);
     float* P = g.partial ? g.partial + (long)esplit * g.M * g.N : nullptr;
+    float* const Pslot = g.partial + (long)eslot * (BM * BN);   // grouped mode: a whole tile per slot
     // a lane reads back the same 8 columns in every chunk (64 is a multiple of the chunks per row),
     // so its bias values are fetched once per tile
     static_assert(64 % CPR == 0, "a lane keeps its columns over the chunks of a band");
@@ -439,7 +480,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
             const int r = id / CPR, cc = (id % CPR) * 8;
             const int m = em0 + wm * WTM + t * 32 + r;
             const int n = en0 + wn * WTN + cc;
-            if (m < g.M && n < g.N) {
+            if constexpr (grouped) {   // raw sums of the whole tile (rows and columns outside the problem are zeros)
+                float v[8];
+                const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
+                const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
+                v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+                store8(Pslot + (wm * WTM + t * 32 + r) * BN + wn * WTN + cc, v);
+            } else if (m < g.M && n < g.N) {
                 float v[8];
                 const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
                 const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
@@ -538,6 +585,54 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+constexpr int kGroupedMaxSplits = 8;
+
+// grouped launch: always the 256x256 tile with both operands K-strided; the grid is what the chip holds
+template <bool KTAIL>
+hipError_t launch_grouped_cfg(GemmArgs* g, hipStream_t s) {
+    constexpr int BM = 256, BN = 256, BK = 64, WGM = 2, WGN = 4;
+    constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, true, true>();
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, true, true, REMAP_NONE, KTAIL, true>;
+    static int resident = 0;
+    if (resident == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        int dev = 0, cus = 0, per_cu = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * WGM * WGN, lds)) != hipSuccess) return e;
+        if (per_cu < 1) per_cu = 1;
+        resident = cus * per_cu / 8 * 8;
+        if (resident < 8) resident = 8;
+    }
+    int tile = 0;
+    for (int i = 0; i < g->n_groups; ++i) {
+        GemmGroup& G = g->grp[i];
+        G.tiles_m = (G.M + BM - 1) / BM;
+        G.tile0 = tile;
+        tile += G.tiles_m * ((G.N + BN - 1) / BN);
+    }
+    g->total_tiles = tile;
+    g->slabs_per_tile = (g->K + BK - 1) / BK;
+    // Split count: the cheapest of 1 .. 8 in slab times - rounds of the grid, each a run of slabs plus a unit's
+    // fixed cost (first-slab latency, writing the partial tile), plus the reduction's pass over the partials.
+    const int S = g->slabs_per_tile;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int sp = 1; sp <= kGroupedMaxSplits && sp <= S; ++sp) {
+        const long units = (long)tile * sp;
+        const long rounds = (units + resident - 1) / resident;
+        const double cost = rounds * ((S + sp - 1) / sp + 8.0) + 0.04 * units;
+        if (cost < best_cost) { best_cost = cost; best = sp; }
+    }
+    g->splits = best;
+    g->units_per_wg = (S + best - 1) / best;
+    const long units = (long)tile * best;
+    long grid = units < resident ? (units + 7) / 8 * 8 : resident;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, *g);
+    return hipGetLastError();
+}
+
 // K a multiple of 64 (every shape of the model): the slab loads carry no per-chunk k check
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
 hipError_t launch_tail(const GemmArgs& g, hipStream_t s) {
@@ -631,11 +726,37 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
     char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail];
     if (!name[0]) {
         const int bm = tile == 0 ? 128 : (tile == 3 ? 192 : 256), bn = tile == 0 ? 128 : 256;
-        snprintf(name, sizeof(names[0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s>", bm, bn,
+        snprintf(name, sizeof(names[0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false>", bm, bn,
                  tile == 0 ? 2 : 4, a_col ? "true" : "false", b_col ? "true" : "false",
                  g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false");
     }
     return name;
+}
+
+static bool grouped_ok(const GemmArgs& g) {
+    if (g.n_groups < 1 || g.n_groups > kMaxGemmGroups || g.K <= 0 || !g.partial || !al16(g.partial)) return false;
+    for (int i = 0; i < g.n_groups; ++i) {
+        const GemmGroup& G = g.grp[i];
+        if (G.M <= 0 || G.N <= 0 || !G.A || !G.B || !al16(G.A) || !al16(G.B)) return false;
+        if (!mult8(G.M) || !mult8(G.N) || !mult8(G.lda) || !mult8(G.ldb)) return false;
+        if ((long)g.K * G.lda * 2 >= (1L << 31) || (long)g.K * G.ldb * 2 >= (1L << 31)) return false;   // 32-bit offsets
+    }
+    return true;
+}
+
+size_t gemm_grouped_slots(const GemmArgs& g) {
+    size_t tiles = 0;
+    for (int i = 0; i < g.n_groups; ++i)
+        tiles += (size_t)((g.grp[i].M + 255) / 256) * ((g.grp[i].N + 255) / 256);
+    return tiles * kGroupedMaxSplits;   // one slot per (tile, split)
+}
+
+hipError_t launch_gemm_grouped(GemmArgs* g, hipStream_t s) {
+    if (!grouped_ok(*g)) return hipErrorNotSupported;
+    g->M = g->N = 0;
+    g->remap = REMAP_NONE;
+    if (g->K % 64) return launch_grouped_cfg<true>(g, s);
+    return launch_grouped_cfg<false>(g, s);
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {

@@ -421,6 +421,44 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 }
 
 // ---------------------------------------------------------------------------
+// Reduction of a grouped weight-gradient launch (see GemmArgs): the splits of tile t left their fp32 partial
+// tiles in slots t, t + total_tiles, ...; they are added in split order (eight loads in flight at a time),
+// then the sum goes to the tile's place in its problem's output, rows or columns through
+// the problem's remap, added to what is there if asked.  blockIdx.y = tile, blockIdx.x = 4 rows of it; a
+// thread owns 4 consecutive columns.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_grouped_kernel(const float* __restrict__ partial, GemmArgs g,
+                                                             ReduceGroupedArgs ra, int accumulate) {
+    const int t = blockIdx.y;
+    int gi = 0;
+    while (gi + 1 < g.n_groups && t >= g.grp[gi + 1].tile0) ++gi;
+    const GemmGroup G = g.grp[gi];
+    const ReduceGroup R = ra.grp[gi];
+    const int lt = t - G.tile0;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), c = (threadIdx.x & 63) * 4;
+    const int m = (lt % G.tiles_m) * 256 + r, n = (lt / G.tiles_m) * 256 + c;
+    if (m >= G.M || n >= G.N) return;
+    const float* src = partial + ((long)t * 256 + r) * 256 + c;
+    const long stride = (long)g.total_tiles * 256 * 256;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 v[8];   // g.splits <= 8
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        if (k < g.splits) v[k] = *reinterpret_cast<const float4*>(src + k * stride);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        if (k < g.splits) { s.x += v[k].x; s.y += v[k].y; s.z += v[k].z; s.w += v[k].w; }
+    const int ro = (R.remap == RED_REMAP_ROWS) ? ra.tbl[R.table](m) : m;
+    const int co = (R.remap == RED_REMAP_COLS) ? ra.tbl[R.table](n) : n;
+    T* o = static_cast<T*>(R.out) + (long)ro * R.ldo + co;
+    if (accumulate) {
+        s.x += ld<T>(o); s.y += ld<T>(o + 1); s.z += ld<T>(o + 2); s.w += ld<T>(o + 3);
+    }
+    st<T>(o, s.x); st<T>(o + 1, s.y); st<T>(o + 2, s.z); st<T>(o + 3, s.w);
+}
+
+// ---------------------------------------------------------------------------
 // up to four column reductions in one launch: blockIdx.y picks the job.  A workgroup owns 32 columns
 // (8 threads x 4 columns) and spreads the chunks over 32 row lanes: lane l adds chunks l, l + 32, ... in
 // index order (eight loads in flight at a time), then the 32 lanes' sums are added in lane order.
@@ -836,6 +874,13 @@ hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, l
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     D2FT_DISPATCH(dtype, hipLaunchKernelGGL(reduce_partials_kernel<T>, grid, block, 0, s, partial, splits,
                                             slice_stride, rows, cols, (T*)out, ldo, remap, accumulate, tbl);)
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_grouped(int dtype, const GemmArgs& g, const ReduceGroupedArgs& r, int accumulate, hipStream_t s) {
+    if (g.total_tiles <= 0) return hipSuccess;
+    const dim3 grid(64, g.total_tiles), block(256);
+    D2FT_DISPATCH(dtype, hipLaunchKernelGGL(reduce_grouped_kernel<T>, grid, block, 0, s, g.partial, g, r, accumulate);)
     return hipGetLastError();
 }
 
