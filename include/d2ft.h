@@ -158,7 +158,10 @@ d2ft_status d2ft_block_fwd(const d2ft_block_desc *desc, const d2ft_block_weights
 /* Backward of one block, for the same desc, weights, ops and x that the forward
  * call saw, and the `saved` buffer it filled.  Attention-side backward work
  * runs for p_f heads only (Sec. II-A.2: p_o keeps the forward pass and skips
- * backward propagation; the gradient goes by the residual route).
+ * backward propagation; the gradient goes by the residual route).  The weights
+ * must hold the values the forward call read: with LoRA (Sec. II-D) `saved`
+ * carries the merged QKV weights W + s B A of the live heads and the backward
+ * call multiplies with those.
  *   dy     [B][T][D] upstream gradient
  *   dx     [B][T][D] out; must not alias dy
  *   grads  HOST struct of device pointers; NULL fields are skipped.  Slices of

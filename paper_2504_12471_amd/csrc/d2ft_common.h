@@ -179,7 +179,8 @@ hipError_t launch_ln_param_grad(int dtype, const void* d, const void* x, const f
 hipError_t launch_colsum(int dtype, const void* X, long ld, int rows, int cols, float* partial, int chunks,
                          hipStream_t s);
 
-enum { RED_REMAP_NONE = 0, RED_REMAP_ROWS = 1, RED_REMAP_COLS = 2 };
+// RED_REMAP_F32 (grouped reduction only): the output is fp32, no remap, never accumulated
+enum { RED_REMAP_NONE = 0, RED_REMAP_ROWS = 1, RED_REMAP_COLS = 2, RED_REMAP_F32 = 3 };
 // out[r'][c'] (=|+=) scale * sum_s partial[s][r][c], (r',c') through the remap
 hipError_t launch_reduce_partials(int dtype, const float* partial, int splits, long slice_stride, int rows, int cols,
                                   void* out, long ldo, int remap, const Remap64& tbl, int accumulate,

@@ -60,7 +60,7 @@ Dims dims_of(const d2ft_block_desc* d) {
 
 // ---- layout of the saved buffer (forward -> backward) ----
 struct SavedLayout {
-    size_t mean1, rstd1, u, qkv, o, lse, x1, mean2, rstd2, v, z, g, total;
+    size_t mean1, rstd1, u, qkv, o, lse, x1, mean2, rstd2, v, z, g, weff, total;
 };
 SavedLayout saved_layout(const Dims& s) {
     SavedLayout L;
@@ -78,13 +78,16 @@ SavedLayout saved_layout(const Dims& s) {
     L.v = take(s.M * s.D * s.es);
     L.z = take(s.M * s.Dm * s.es);   // GELU'(z) of the hidden units in use (what the backward needs of z)
     L.g = take(s.M * s.Dm * s.es);
+    // LoRA: the merged QKV weights of the live heads (compacted order), built by the forward call and read
+    // again by the backward call (the p_f heads are the first rows)
+    L.weff = take(s.r > 0 ? (size_t)192 * s.H * s.D * s.es : 0);
     L.total = off;
     return L;
 }
 
 // ---- layout of the scratch buffer ----
 struct ScratchLayout {
-    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, dz, dv, dx1, d_o, dqkv, du, delta, weff, total;
+    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, dz, dv, dx1, d_o, dqkv, du, delta, lora_g, total;
     size_t part_floats, colpart_stride;
 };
 ScratchLayout scratch_layout(const Dims& s) {
@@ -119,7 +122,7 @@ ScratchLayout scratch_layout(const Dims& s) {
     L.dqkv = take(s.M * s.H * 192 * s.es);
     L.du = take(s.M * s.D * s.es);
     L.delta = take((size_t)s.H * s.M * 4);
-    L.weff = take(s.r > 0 ? (size_t)192 * s.H * s.D * s.es : 0);
+    L.lora_g = take(s.r > 0 ? (size_t)192 * s.H * s.D * 4 : 0);   // fp32 dW_eff of the p_f heads, for the LoRA gradients
     L.total = off;
     return L;
 }
@@ -418,6 +421,9 @@ struct WeightGradBatch {
     bool enabled;
     GemmArgs g;
     ReduceGroupedArgs r;
+    // a group with remap RED_REMAP_F32 leaves its fp32 product for a consumer: after the flush f32_splits says
+    // how (0: summed, in the group's out; n > 0: n split-K slices, one after the other, at the start of `part`)
+    int f32_splits;
 };
 
 void weight_grad_batch_init(WeightGradBatch* b, const d2ft_block_desc* d) {
@@ -465,8 +471,15 @@ d2ft_status weight_grad_flush(WeightGradBatch* b, const d2ft_block_desc* d, cons
         for (int i = 0; i < g.n_groups; ++i) {
             const GemmGroup& G = g.grp[i];
             const ReduceGroup& R = b->r.grp[i];
-            const d2ft_status rc = weight_grad(d, s, G.A, G.lda, G.B, G.ldb, G.M, G.N, part, R.out, R.ldo, R.remap,
-                                               b->r.tbl[R.table], st);
+            d2ft_status rc;
+            if (R.remap == RED_REMAP_F32) {   // queued last: nothing overwrites its slices before the consumer runs
+                int splits = 1;
+                rc = weight_grad(d, s, G.A, G.lda, G.B, G.ldb, G.M, G.N, part, nullptr, 0, RED_REMAP_NONE, b->r.tbl[0], st,
+                                 &splits, false);
+                b->f32_splits = splits;
+            } else {
+                rc = weight_grad(d, s, G.A, G.lda, G.B, G.ldb, G.M, G.N, part, R.out, R.ldo, R.remap, b->r.tbl[R.table], st);
+            }
             if (rc != D2FT_OK) return rc;
         }
     } else {
@@ -631,8 +644,8 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             HeadList hl; hl.n = nl;
             for (int j = 0; j < nl; ++j) hl.h[j] = (uint8_t)live[j];
             D2FT_TRY(launch_lora_merge(s.dtype, w->w_qkv, w->lora_a_q, w->lora_a_v, w->lora_b_q, w->lora_b_v,
-                                       ws + WL.weff, hl, nl, s.H, s.D, s.r, desc->lora_scale, st));
-            g.B = ws + WL.weff; g.b_rs = 1; g.b_cs = s.D; g.remap = REMAP_NONE;
+                                       sv + SL.weff, hl, nl, s.H, s.D, s.r, desc->lora_scale, st));
+            g.B = sv + SL.weff; g.b_rs = 1; g.b_cs = s.D; g.remap = REMAP_NONE;
         } else {
             g.B = w->w_qkv; g.b_rs = 1; g.b_cs = s.D; g.remap = REMAP_B_N;
         }
@@ -749,9 +762,26 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     memset(&none, 0, sizeof(none));
     const void* x1 = (half != PART_MLP && nl > 0) ? (const void*)(sva + SL.x1) : x;
     d2ft_status rc;
+    // LoRA: dW_eff of the p_f heads rides in the weight-gradient batch as an fp32 product; the adapters' gradients
+    // are projected from it once the batch has run
+    bool lora_queued = false;
+    HeadList lora_heads; lora_heads.n = 0;
+    auto flush_wgrads = [&]() -> d2ft_status {
+        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st);
+        if (rw != D2FT_OK) return rw;
+        if (lora_queued) {
+            lora_queued = false;
+            const long elems = (long)lora_heads.n * 192 * s.D;
+            const float* G = wgrads.f32_splits > 0 ? part : (const float*)(ws + WL.lora_g);
+            D2FT_TRY(launch_lora_project(s.dtype, G, wgrads.f32_splits > 0 ? wgrads.f32_splits : 1, elems, w->lora_a_q,
+                                         w->lora_a_v, w->lora_b_q, w->lora_b_v, grads->lora_a_q, grads->lora_a_v,
+                                         grads->lora_b_q, grads->lora_b_v, lora_heads, s.H, s.D, s.r, desc->lora_scale, accum, st));
+        }
+        return D2FT_OK;
+    };
     // the call's last launches: the collected weight gradients, then the bias reductions
     auto finish = [&](const Remap64& tbl_a, const Remap64& tbl_b) -> d2ft_status {
-        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st);
+        const d2ft_status rw = flush_wgrads();
         if (rw != D2FT_OK) return rw;
         return flush_bias_grads(desc, s, &bias_batch, tbl_a, tbl_b, st);
     };
@@ -924,7 +954,15 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         rc = weight_grad_queue(&wgrads, desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D,
                                RED_REMAP_ROWS, qkv_tbl, 2, st);
         if (rc != D2FT_OK) return rc;
-    } else if (want_lora) {   // G = dQKV^T u, rows in compacted order
+    } else if (want_lora && !grads->w_qkv && wgrads.enabled && wgrads.g.n_groups < kMaxGemmGroups) {
+        // G = dQKV^T u (rows in compacted order) as one more group of the batch, left in fp32
+        rc = weight_grad_queue(&wgrads, desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, ws + WL.lora_g, s.D,
+                               RED_REMAP_F32, qkv_tbl, 2, st);
+        if (rc != D2FT_OK) return rc;
+        lora_queued = true;
+        lora_heads.n = nf;
+        for (int j = 0; j < nf; ++j) lora_heads.h[j] = (uint8_t)live[j];
+    } else if (want_lora) {   // the same product by a launch of its own
         int splits = 1;
         rc = weight_grad(desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D, RED_REMAP_ROWS, qkv_tbl,
                          st, &splits, grads->w_qkv != nullptr);
@@ -947,12 +985,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         GemmArgs g = gemm_base();
         g.tbl = qkv_tbl;
         g.A = ws + WL.dqkv; g.a_rs = ld_dq; g.a_cs = 1;
-        if (s.r > 0) {
-            HeadList fl; fl.n = nf;
-            for (int j = 0; j < nf; ++j) fl.h[j] = (uint8_t)live[j];
-            D2FT_TRY(launch_lora_merge(s.dtype, w->w_qkv, w->lora_a_q, w->lora_a_v, w->lora_b_q, w->lora_b_v,
-                                       ws + WL.weff, fl, nf, s.H, s.D, s.r, desc->lora_scale, st));
-            g.B = ws + WL.weff; g.remap = REMAP_NONE;
+        if (s.r > 0) {   // the forward call's merged weights; the p_f heads are their first nf * 192 rows
+            g.B = sv + SL.weff; g.remap = REMAP_NONE;
         } else {
             g.B = w->w_qkv; g.remap = REMAP_B_K;
         }
@@ -973,7 +1007,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, accum, st));
     }
     if (dx1 == dx) {   // the rows of dx1 are about to be rewritten in place: its weight gradients go first
-        rc = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st);
+        rc = flush_wgrads();
         if (rc != D2FT_OK) return rc;
     }
     // dx = dx1 + LN1bwd(du)

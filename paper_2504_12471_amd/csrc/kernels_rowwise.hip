@@ -449,6 +449,10 @@ __global__ __launch_bounds__(256) void reduce_grouped_kernel(const float* __rest
 #pragma unroll
     for (int k = 0; k < 8; ++k)
         if (k < g.splits) { s.x += v[k].x; s.y += v[k].y; s.z += v[k].z; s.w += v[k].w; }
+    if (R.remap == RED_REMAP_F32) {
+        *reinterpret_cast<float4*>(static_cast<float*>(R.out) + (long)m * R.ldo + n) = s;
+        return;
+    }
     const int ro = (R.remap == RED_REMAP_ROWS) ? ra.tbl[R.table](m) : m;
     const int co = (R.remap == RED_REMAP_COLS) ? ra.tbl[R.table](n) : n;
     T* o = static_cast<T*>(R.out) + (long)ro * R.ldo + co;
