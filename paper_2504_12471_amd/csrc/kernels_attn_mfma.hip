@@ -69,32 +69,35 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
 
 // copy rows [0, rows_valid) x 64 channels of a [token][ld] global tile to LDS rows of `stride`, zero rows above.
 // All global loads of the tile are issued before the first LDS store, so their latencies overlap.
-template <int TP>
-__device__ __forceinline__ void load_tile64(const bf16* __restrict__ g, long ld, int rows_valid, bf16* lds, int stride) {
-    constexpr int N = TP * 8 / 256;
+template <int TP, int NTHR = 256>   // NTHR threads take part, numbered by t (threadIdx.x, or the lane for one wavefront)
+__device__ __forceinline__ void load_tile64(const bf16* __restrict__ g, long ld, int rows_valid, bf16* lds, int stride,
+                                            int t = threadIdx.x) {
+    constexpr int N = TP * 8 / NTHR;
+    static_assert(TP * 8 % NTHR == 0, "the tile divides over the threads");
     u32x4 v[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const int c = threadIdx.x + i * 256;
+        const int c = t + i * NTHR;
         const int r = c >> 3, ch = (c & 7) * 8;
         v[i] = u32x4{0u, 0u, 0u, 0u};
         if (r < rows_valid) v[i] = *reinterpret_cast<const u32x4*>(g + (long)r * ld + ch);
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const int c = threadIdx.x + i * 256;
+        const int c = t + i * NTHR;
         *reinterpret_cast<u32x4*>(lds + (c >> 3) * stride + (c & 7) * 8) = v[i];
     }
 }
 // the same for two tiles at once (K and V): twice the loads in flight
-template <int TP, int NTHR = 256>
+template <int TP, int NTHR = 256>   // NTHR threads take part, numbered by t (threadIdx.x, or the lane for one wavefront)
 __device__ __forceinline__ void load_two_tiles64(const bf16* __restrict__ g0, const bf16* __restrict__ g1, long ld,
-                                                 int rows_valid, bf16* lds0, int stride0, bf16* lds1, int stride1) {
+                                                 int rows_valid, bf16* lds0, int stride0, bf16* lds1, int stride1,
+                                                 int t = threadIdx.x) {
     constexpr int N = (TP * 8 + NTHR - 1) / NTHR;
     u32x4 v0[N], v1[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const int c = threadIdx.x + i * NTHR;
+        const int c = t + i * NTHR;
         const int r = c >> 3, ch = (c & 7) * 8;
         v0[i] = u32x4{0u, 0u, 0u, 0u};
         v1[i] = u32x4{0u, 0u, 0u, 0u};
@@ -105,11 +108,38 @@ __device__ __forceinline__ void load_two_tiles64(const bf16* __restrict__ g0, co
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const int c = threadIdx.x + i * NTHR;
+        const int c = t + i * NTHR;
         if (TP * 8 % NTHR == 0 || c < TP * 8) {
             *reinterpret_cast<u32x4*>(lds0 + (c >> 3) * stride0 + (c & 7) * 8) = v0[i];
             *reinterpret_cast<u32x4*>(lds1 + (c >> 3) * stride1 + (c & 7) * 8) = v1[i];
         }
+    }
+}
+
+// the same by ONE wavefront with every load of both tiles in flight: raw buffer loads whose declared size
+// ends with the last valid row (rows above read as zeros without touching memory), one offset register
+// for all chunks (a lane's chunks are 8 rows apart: the distance goes into the scalar offset)
+template <int TP>
+__device__ __forceinline__ void load_two_tiles64_wave(const bf16* __restrict__ g0, const bf16* __restrict__ g1, long ld,
+                                                      int rows_valid, bf16* lds0, int stride0, bf16* lds1, int stride1,
+                                                      int lane) {
+    constexpr int N = TP * 8 / 64;
+    const uint32_t bytes = (uint32_t)(rows_valid - 1) * (uint32_t)ld * 2u + 128u;
+    const __amdgpu_buffer_rsrc_t r0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(g0), 0, bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(g1), 0, bytes, 0x00020000);
+    const uint32_t off = (uint32_t)(lane >> 3) * (uint32_t)ld * 2u + (uint32_t)(lane & 7) * 16u;
+    const uint32_t step = 8u * (uint32_t)ld * 2u;
+    u32x4 v0[N], v1[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        v0[i] = __builtin_amdgcn_raw_buffer_load_b128(r0, off, step * i, 0);
+        v1[i] = __builtin_amdgcn_raw_buffer_load_b128(r1, off, step * i, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = lane + i * 64;
+        *reinterpret_cast<u32x4*>(lds0 + (c >> 3) * stride0 + (c & 7) * 8) = v0[i];
+        *reinterpret_cast<u32x4*>(lds1 + (c >> 3) * stride1 + (c & 7) * 8) = v1[i];
     }
 }
 
@@ -121,6 +151,183 @@ constexpr int kVS = 96;   // V rows in LDS: 192 bytes (transposing reads)
 // ---------------------------------------------------------------------------
 struct WholeBatch {};   // no mask: every (image, head) pair is live, the first n_full positions are p_f
 
+// One query tile of one pair: S^T = K Q^T against all key tiles, softmax over the keys, O^T = V^T P^T.
+// qf: the tile's Q fragments (this lane's query); after_s() runs once the S products are issued (qf is
+// free from then on).  Leaves the unnormalised O^T in ot, the row maximum in m, the row sum in sum.
+template <int KT, typename AfterS>
+__device__ __forceinline__ void fwd_unit(const bf16* Ks, const bf16* Vs, bf16x8 (&qf)[4], int tokens, int lane,
+                                         f32x16 (&ot)[2], float& m, float& sum, AfterS&& after_s) {
+    const int c = lane & 31, h = lane >> 5;
+    // S^T tiles: rows = keys of tile u, column = this lane's query.  K fragments of tile u+1 are
+    // fetched from LDS while the MFMAs of tile u run (one read behind each MFMA).
+    f32x16 s[KT];
+    const f32x16 zero_acc = zero16();   // shared C operand of every tile's first MFMA
+    bf16x8 kf[3][4];   // the fragments of a tile are requested two tiles (eight products) before their use
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kf[0][kk] = frag_rows(Ks, kKS, c, kk * 16 + 8 * h);
+    if (KT > 1) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kf[1][kk] = frag_rows(Ks, kKS, 32 + c, kk * 16 + 8 * h);
+    }
+#pragma unroll
+    for (int u = 0; u < KT; ++u) {
+        if (u + 2 < KT) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kf[(u + 2) % 3][kk] = frag_rows(Ks, kKS, (u + 2) * 32 + c, kk * 16 + 8 * h);
+        }
+        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u % 3][0], qf[0], zero_acc, 0, 0, 0);
+#pragma unroll
+        for (int kk = 1; kk < 4; ++kk)
+            s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u % 3][kk], qf[kk], s[u], 0, 0, 0);
+        if (u + 2 < KT) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    after_s();
+    // first V fragments are fetched under the softmax arithmetic
+    bf16x8 vf[2][4];
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) vf[0][gp * 2 + dt] = frag_tr(Vs, kVS, 16 * gp, dt * 32, lane);
+    {   // only the last key tile reaches past the last token (KT = ceil(tokens / 32)): element e of a lane
+        // is key 32 (KT - 1) + 8 (e / 4) + 4 h + e % 4
+        const int lim = tokens - (KT - 1) * 32 - 4 * h;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (8 * (e >> 2) + (e & 3) >= lim) s[KT - 1][e] = -INFINITY;
+    }
+    m = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < KT; ++u) {
+        // three-input maxima: half the instructions of a chain of two-input ones
+        float t0 = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
+        float t1 = fmaxf(fmaxf(s[u][3], s[u][4]), s[u][5]);
+        float t2 = fmaxf(fmaxf(s[u][6], s[u][7]), s[u][8]);
+        float t3 = fmaxf(fmaxf(s[u][9], s[u][10]), s[u][11]);
+        float t4 = fmaxf(fmaxf(s[u][12], s[u][13]), s[u][14]);
+        t0 = fmaxf(fmaxf(t0, t1), t2);
+        t3 = fmaxf(fmaxf(t3, t4), s[u][15]);
+        m = fmaxf(fmaxf(m, t0), t3);
+    }
+    m = fmaxf(m, __shfl_xor(m, 32, 64));
+    const float cexp = kScale * kLog2e;
+    const float mc = m * cexp;
+    sum = 0.f;
+    auto exp_tile = [&](int u) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[u][e], cexp, -mc));
+            s[u][e] = p;
+            sum += p;
+        }
+    };
+    exp_tile(0);
+    // O^T = V^T P^T: rows = channels, column = this lane's query.  The products of key tile u run on the
+    // matrix cores while the vector units take the exponentials of tile u + 1; V fragments one tile ahead.
+    ot[0] = zero16();
+    ot[1] = zero16();
+#pragma unroll
+    for (int u = 0; u < KT; ++u) {
+        const bf16x8 pf0 = pack8(s[u], 0), pf1 = pack8(s[u], 8);
+        if (u + 1 < KT) {
+#pragma unroll
+            for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+                    vf[(u + 1) & 1][gp * 2 + dt] = frag_tr(Vs, kVS, (u + 1) * 32 + 16 * gp, dt * 32, lane);
+        }
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u & 1][dt], pf0, ot[dt], 0, 0, 0);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u & 1][2 + dt], pf1, ot[dt], 0, 0, 0);
+        if (u + 1 < KT) {
+            exp_tile(u + 1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one product
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);    // two fragment reads
+                __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);   // a quarter of the tile's exponentials
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    sum += __shfl_xor(sum, 32, 64);   // the two lanes of a query hold different keys
+}
+
+// This lane's query row of the unit's result: O = O^T columns / sum, and the log-sum-exp if asked for.
+// A lane holds 4 consecutive channels per group of 8 and its partner 32 lanes up (same query) the other 4:
+// the two exchange halves (v_permlane32_swap), so each stores 16-byte pieces and a query row goes out as
+// 32 contiguous bytes per store instruction.  All lanes must call; ok says whether this lane's query exists.
+__device__ __forceinline__ void fwd_store(const f32x16 (&ot)[2], float m, float sum, bf16* orow, float* lse_q, int h, bool ok) {
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            uint32_t a[2], b[2];   // groups 2p and 2p + 1: this lane's 4 channels of each, packed
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                a[r] = pack_bf16x2(ot[dt][8 * p + 2 * r] * inv, ot[dt][8 * p + 2 * r + 1] * inv);
+                b[r] = pack_bf16x2(ot[dt][8 * p + 4 + 2 * r] * inv, ot[dt][8 * p + 4 + 2 * r + 1] * inv);
+                // upper half of a <-> lower half of b
+                const auto sw = __builtin_amdgcn_permlane32_swap(a[r], b[r], false, false);
+                a[r] = sw[0];
+                b[r] = sw[1];
+            }
+            // lower lanes now hold channels 8 (2p) .. + 7 (their own 4, then the partner's), upper lanes 8 (2p + 1) .. + 7
+            if (ok) *reinterpret_cast<uint4*>(orow + dt * 32 + 8 * (2 * p + h)) = make_uint4(a[0], a[1], b[0], b[1]);
+        }
+    if (ok && h == 0 && lse_q) *lse_q = m * kScale + __logf(sum);
+}
+
+// the Q fragments of query q (16 bytes per 16-channel step), zeros for a query past the last token
+__device__ __forceinline__ void load_q_frags(const bf16* Qb, long ldq, int q, bool q_ok, int h, bf16x8 (&qf)[4]) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (q_ok) v = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + kk * 16 + 8 * h);
+        qf[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+}
+
+// which pair a (image, slot) position works on.  Without a mask slot j is live head j and the first n_full
+// of them are p_f.  With a mask the position first zero-fills its share of the image's skipped heads (all
+// threads of the workgroup), then takes the slot-th live head of the image's micro-batch, if there is one.
+template <typename Mask>
+__device__ __forceinline__ bool fwd_pair(const Mask& mask, int b, int slot, int n_live, int n_full, int tokens, bf16* o, long ldo,
+                                         int& j, bool& save_lse) {
+    j = slot;
+    save_lse = slot < n_full;
+    if constexpr (std::is_same<Mask, MicroMask>::value) {
+        const long row0 = (long)b * tokens;
+        const int mb = mask.micro_of(b);
+        const uint64_t live = mask.live[mb];
+        const uint64_t skipped = ~live & (mask.n_live_pos >= 64 ? ~0ull : ((1ull << mask.n_live_pos) - 1ull));
+        int r = 0;
+        for (uint64_t mm = skipped; mm; mm &= mm - 1, ++r)   // heads skipped in this image's micro-batch: O = 0
+            if (r % n_live == slot) {
+                const int p = __builtin_ctzll(mm);
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                for (int i = threadIdx.x; i < tokens * 8; i += blockDim.x)
+                    *reinterpret_cast<u32x4*>(o + (row0 + (i >> 3)) * ldo + p * 64 + (i & 7) * 8) = z;
+            }
+        if (slot >= __builtin_popcountll(live)) return false;
+        uint64_t mm = live;
+        for (int t = 0; t < slot; ++t) mm &= mm - 1;
+        j = __builtin_ctzll(mm);   // this slot's live head
+        save_lse = (mask.full[mb] >> j) & 1;
+    }
+    return true;
+}
+
+// One workgroup per (image, slot), four wavefronts that share the query tiles (tokens above 224, where the
+// kernel below would need a ninth wavefront).
 template <int KT, typename Mask>   // KT: number of 32-token tiles
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, long ldq,
                                                             bf16* __restrict__ o, long ldo, float* __restrict__ lse,
@@ -133,146 +340,100 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int b = blockIdx.x / n_live;   // with a mask n_live is the number of slots per image
-    int j = blockIdx.x % n_live;
     const long row0 = (long)b * tokens;
-    bool save_lse = j < n_full;
-    if constexpr (std::is_same<Mask, MicroMask>::value) {
-        const int mb = mask.micro_of(b), slot = j;
-        const uint64_t live = mask.live[mb];
-        const uint64_t skipped = ~live & (mask.n_live_pos >= 64 ? ~0ull : ((1ull << mask.n_live_pos) - 1ull));
-        int r = 0;
-        for (uint64_t m = skipped; m; m &= m - 1, ++r)   // heads skipped in this image's micro-batch: O = 0
-            if (r % n_live == slot) {
-                const int p = __builtin_ctzll(m);
-                const u32x4 z = {0u, 0u, 0u, 0u};
-                for (int i = threadIdx.x; i < tokens * 8; i += 256)
-                    *reinterpret_cast<u32x4*>(o + (row0 + (i >> 3)) * ldo + p * 64 + (i & 7) * 8) = z;
-            }
-        if (slot >= __builtin_popcountll(live)) return;
-        uint64_t m = live;
-        for (int t = 0; t < slot; ++t) m &= m - 1;
-        j = __builtin_ctzll(m);   // this slot's live head
-        save_lse = (mask.full[mb] >> j) & 1;
-    }
+    int j;
+    bool save_lse;
+    if (!fwd_pair(mask, b, blockIdx.x % n_live, n_live, n_full, tokens, o, ldo, j, save_lse)) return;
     const bf16* Qb = qkv + row0 * ldq + j * 192;
     load_two_tiles64<TP>(Qb + 64, Qb + 128, ldq, tokens, Ks, kKS, Vs, kVS);
     __syncthreads();
-
     for (int qt = wave; qt < KT; qt += 4) {
         const int q = qt * 32 + c;
         const bool q_ok = q < tokens;
         bf16x8 qf[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (q_ok) v = *reinterpret_cast<const u32x4*>(Qb + (long)q * ldq + kk * 16 + 8 * h);
-            qf[kk] = __builtin_bit_cast(bf16x8, v);
-        }
-        // S^T tiles: rows = keys of tile u, column = this lane's query.  K fragments of tile u+1 are
-        // fetched from LDS while the MFMAs of tile u run (one read behind each MFMA).
-        f32x16 s[KT];
-        const f32x16 zero_acc = zero16();   // shared C operand of every tile's first MFMA
-        bf16x8 kf[2][4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) kf[0][kk] = frag_rows(Ks, kKS, c, kk * 16 + 8 * h);
-#pragma unroll
-        for (int u = 0; u < KT; ++u) {
-            if (u + 1 < KT) {
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) kf[(u + 1) & 1][kk] = frag_rows(Ks, kKS, (u + 1) * 32 + c, kk * 16 + 8 * h);
-            }
-            s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u & 1][0], qf[0], zero_acc, 0, 0, 0);
-#pragma unroll
-            for (int kk = 1; kk < 4; ++kk)
-                s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u & 1][kk], qf[kk], s[u], 0, 0, 0);
-            if (u + 1 < KT) {
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        load_q_frags(Qb, ldq, q, q_ok, h, qf);
+        f32x16 ot[2];
+        float m, sum;
+        fwd_unit<KT>(Ks, Vs, qf, tokens, lane, ot, m, sum, [] {});
+        fwd_store(ot, m, sum, o + (row0 + q) * ldo + j * 64, save_lse ? lse + (long)j * rows_total + row0 + q : nullptr, h, q_ok);
+    }
+}
+
+// Persistent form for up to 224 tokens: a workgroup of KT + 1 wavefronts walks the positions
+// blockIdx.x, blockIdx.x + gridDim.x, ... (the grid is what the chip holds at once).  Wavefront t < KT
+// owns query tile t of every pair; the last wavefront is the loader: while the others work on pair i out
+// of one LDS buffer it copies K and V of pair i + 1 into the other, all its loads in flight at once, so
+// after the first pair no wavefront waits for K or V.  A compute wavefront fetches the Q fragments of its
+// next pair as soon as the S products of the current one are issued.  One barrier per pair.
+template <int KT, typename Mask>
+__global__ __launch_bounds__(64 * (KT + 1), 2) void attn_fwd_pipe_kernel(const bf16* __restrict__ qkv, long ldq,
+                                                                        bf16* __restrict__ o, long ldo,
+                                                                        float* __restrict__ lse, int tokens, int n_live,
+                                                                        int n_full, long rows_total, int n_pos,
+                                                                        Mask mask) {
+    constexpr int TP = KT * 32, NTHR = 64 * (KT + 1);
+    constexpr int BUF = TP * (kKS + kVS);   // elements of one K + V buffer
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* const smem = reinterpret_cast<bf16*>(smem_raw);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, h = lane >> 5;
+
+    int pos = blockIdx.x;
+    int j = 0;
+    bool save_lse = false;
+    bool active = fwd_pair(mask, pos / n_live, pos % n_live, n_live, n_full, tokens, o, ldo, j, save_lse);
+    {
+        const bf16* Qb = qkv + (long)(pos / n_live) * tokens * ldq + j * 192;
+        if (active) load_two_tiles64<TP, NTHR>(Qb + 64, Qb + 128, ldq, tokens, smem, kKS, smem + TP * kKS, kVS);
+    }
+    if (wave == KT) {
+        // ---- loader: K and V of the next position into the other buffer, every load in flight at once ----
+        __syncthreads();
+        for (int i = 0; pos < n_pos; ++i) {
+            const int npos = pos + gridDim.x;
+            if (npos < n_pos) {
+                int nj;
+                bool nsave;
+                if (fwd_pair(mask, npos / n_live, npos % n_live, n_live, n_full, tokens, o, ldo, nj, nsave)) {
+                    const bf16* nQb = qkv + (long)(npos / n_live) * tokens * ldq + nj * 192;
+                    bf16* nK = smem + ((i + 1) & 1) * BUF;
+                    load_two_tiles64_wave<TP>(nQb + 64, nQb + 128, ldq, tokens, nK, kKS, nK + TP * kKS, kVS, lane);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            pos = npos;
         }
-        // first V fragments are fetched under the softmax arithmetic
-        bf16x8 vf[2][4];
-#pragma unroll
-        for (int gp = 0; gp < 2; ++gp)
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) vf[0][gp * 2 + dt] = frag_tr(Vs, kVS, 16 * gp, dt * 32, lane);
-        float m = -INFINITY;
-#pragma unroll
-        for (int u = 0; u < KT; ++u) {
-            if (u * 32 + 31 >= tokens) {   // only tiles that reach past the last token need the mask
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = u * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                    if (key >= tokens) s[u][e] = -INFINITY;
-                }
+    } else {
+        // ---- compute: query tile `wave` of every position ----
+        const int q = wave * 32 + c;
+        const bool q_ok = q < tokens;
+        bf16x8 qf[4];
+        if (active) load_q_frags(qkv + (long)(pos / n_live) * tokens * ldq + j * 192, ldq, q, q_ok, h, qf);
+        __syncthreads();
+        for (int i = 0; pos < n_pos; ++i) {
+            const bf16* const Ks = smem + (i & 1) * BUF;
+            const bf16* const Vs = Ks + TP * kKS;
+            const int npos = pos + gridDim.x;   // the next position of this workgroup (uniform over it)
+            int nj = 0;
+            bool nsave = false, nactive = false;
+            if (npos < n_pos) nactive = fwd_pair(mask, npos / n_live, npos % n_live, n_live, n_full, tokens, o, ldo, nj, nsave);
+            const bf16* nQb = qkv + (long)(npos < n_pos ? npos / n_live : 0) * tokens * ldq + nj * 192;
+            if (active) {
+                const long row0 = (long)(pos / n_live) * tokens;
+                f32x16 ot[2];
+                float m, sum;
+                fwd_unit<KT>(Ks, Vs, qf, tokens, lane, ot, m, sum, [&] {
+                    if (nactive) load_q_frags(nQb, ldq, q, q_ok, h, qf);
+                });
+                fwd_store(ot, m, sum, o + (row0 + q) * ldo + j * 64, save_lse ? lse + (long)j * rows_total + row0 + q : nullptr, h, q_ok);
+            } else if (nactive) {
+                load_q_frags(nQb, ldq, q, q_ok, h, qf);
             }
-            // three-input maxima: half the instructions of a chain of two-input ones
-            float t0 = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
-            float t1 = fmaxf(fmaxf(s[u][3], s[u][4]), s[u][5]);
-            float t2 = fmaxf(fmaxf(s[u][6], s[u][7]), s[u][8]);
-            float t3 = fmaxf(fmaxf(s[u][9], s[u][10]), s[u][11]);
-            float t4 = fmaxf(fmaxf(s[u][12], s[u][13]), s[u][14]);
-            t0 = fmaxf(fmaxf(t0, t1), t2);
-            t3 = fmaxf(fmaxf(t3, t4), s[u][15]);
-            m = fmaxf(fmaxf(m, t0), t3);
-        }
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
-        const float cexp = kScale * kLog2e;
-        const float mc = m * cexp;
-        float sum = 0.f;
-#pragma unroll
-        for (int u = 0; u < KT; ++u)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[u][e], cexp, -mc));
-                s[u][e] = p;
-                sum += p;
-            }
-        sum += __shfl_xor(sum, 32, 64);
-        // O^T = V^T P^T: rows = channels, column = this lane's query; V fragments one tile ahead
-        f32x16 ot[2] = {zero16(), zero16()};
-#pragma unroll
-        for (int u = 0; u < KT; ++u) {
-            if (u + 1 < KT) {
-#pragma unroll
-                for (int gp = 0; gp < 2; ++gp)
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-                        vf[(u + 1) & 1][gp * 2 + dt] = frag_tr(Vs, kVS, (u + 1) * 32 + 16 * gp, dt * 32, lane);
-            }
-#pragma unroll
-            for (int gp = 0; gp < 2; ++gp) {
-                const bf16x8 pf = pack8(s[u], 8 * gp);
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    ot[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u & 1][gp * 2 + dt], pf, ot[dt], 0, 0, 0);
-            }
-            if (u + 1 < KT) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (q_ok) {
-            const float inv = 1.0f / sum;
-            bf16* orow = o + (row0 + q) * ldo + j * 64;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int eg = 0; eg < 4; ++eg) {
-                    uint2 pk;
-                    pk.x = pack_bf16x2(ot[dt][4 * eg] * inv, ot[dt][4 * eg + 1] * inv);
-                    pk.y = pack_bf16x2(ot[dt][4 * eg + 2] * inv, ot[dt][4 * eg + 3] * inv);
-                    *reinterpret_cast<uint2*>(orow + dt * 32 + 8 * eg + 4 * h) = pk;
-                }
-            if (h == 0 && save_lse) lse[(long)j * rows_total + row0 + q] = m * kScale + __logf(sum);
+            __syncthreads();
+            pos = npos;
+            j = nj;
+            save_lse = nsave;
+            active = nactive;
         }
     }
 }
@@ -280,17 +441,40 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 template <int KT, typename Mask>
 hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* lse, int batch, int tokens, int n_live,
                          int n_full, const Mask& mask, hipStream_t s) {
-    constexpr size_t lds = (size_t)KT * 32 * (kKS + kVS) * sizeof(bf16);
-    auto kern = attn_fwd_mfma_kernel<KT, Mask>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    if constexpr (KT <= 7) {
+        constexpr size_t lds = 2 * (size_t)KT * 32 * (kKS + kVS) * sizeof(bf16);
+        constexpr int threads = 64 * (KT + 1);
+        auto kern = attn_fwd_pipe_kernel<KT, Mask>;
+        static int resident = 0;   // workgroups the chip holds at once
+        if (resident == 0) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            int dev = 0, cus = 0, per_cu = 0;
+            if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+            if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, lds)) != hipSuccess) return e;
+            resident = cus * (per_cu < 1 ? 1 : per_cu);
+        }
+        const int n_pos = batch * n_live;
+        // every workgroup gets the same number of positions, give or take one
+        const int rounds = (n_pos + resident - 1) / resident;
+        const int grid = (n_pos + rounds - 1) / rounds;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, s, qkv, ldq, o, ldo, lse, tokens, n_live, n_full,
+                           (long)batch * tokens, n_pos, mask);
+        return hipGetLastError();
+    } else {
+        constexpr size_t lds = (size_t)KT * 32 * (kKS + kVS) * sizeof(bf16);
+        auto kern = attn_fwd_mfma_kernel<KT, Mask>;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(batch * n_live), dim3(256), lds, s, qkv, ldq, o, ldo, lse, tokens, n_live, n_full,
+                           (long)batch * tokens, mask);
+        return hipGetLastError();
     }
-    hipLaunchKernelGGL(kern, dim3(batch * n_live), dim3(256), lds, s, qkv, ldq, o, ldo, lse, tokens, n_live, n_full,
-                       (long)batch * tokens, mask);
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
