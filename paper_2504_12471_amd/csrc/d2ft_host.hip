@@ -272,16 +272,29 @@ bool on_mfma_path(const GemmArgs& g, const d2ft_block_desc* d) {
 hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, int* colsum_bands = nullptr) {
     if (colsum_bands) *colsum_bands = 0;
     if (on_mfma_path(g, d)) {
-        // The 256x256 tile runs one workgroup per CU, so a grid of R*256 + f tiles takes R + 1 rounds
-        // however small f is.  When the last round would be under 60% full, the rows of whole rounds
-        // go to the large tile and the remaining rows to the 128x128 tile, two of which share a CU.
+        // Tile plan for shapes of more than one round of the chip's 256 CUs.  The one-per-CU tiles take whole
+        // rounds however few tiles the last one has, so three plans are priced in microseconds with per-round
+        // costs measured on this part (a round = fixed cost + slabs of 64 of K; ep = the epilogue's extra work):
+        // all 256x256 tiles; the rows of the whole rounds as 256x256 tiles and the remaining rows as 128x128
+        // tiles, two of which share a CU; all 192x256 tiles.
         if (!g.partial && g.tile_hint == 0 && g.M >= 512 && g.N >= 256) {
             const long tn = (g.N + 255) / 256, tm = (g.M + 255) / 256, total = tm * tn;
-            const long rounds = total / 256, tail = total % 256;
-            if (rounds >= 1 && tail > 0 && tail < 154) {
+            const double slabs = (g.K + 63) / 64;
+            const double ep = g.act == ACT_GELU ? 8.0 : ((g.act == ACT_DGELU || g.residual) ? 3.0 : 0.0);
+            auto rounds_of = [](long tiles, long per_round) { return (double)((tiles + per_round - 1) / per_round); };
+            const double r256 = 8.5 + 1.6 * slabs + ep, r192 = 9.0 + 1.1 * slabs + 0.75 * ep, r128 = 8.0 + 1.2 * slabs + 0.4 * ep;
+            if (total > 256) {
+                const double c_all256 = rounds_of(total, 256) * r256;
+                const double c_all192 = rounds_of((long)((g.M + 191) / 192) * tn, 256) * r192;
+                const long rounds = total / 256;
                 const long tm_big = rounds * 256 / tn;
                 const long m_split = tm_big * 256;
+                double c_split = 1e30;
                 if (m_split > 0 && m_split < g.M) {
+                    const long rest_tiles = ((g.M - m_split + 127) / 128) * ((g.N + 127) / 128);
+                    c_split = rounds_of(tm_big * tn, 256) * r256 + rounds_of(rest_tiles, 512) * r128;
+                }
+                if (c_split < c_all256 && c_split < c_all192) {
                     GemmArgs big = g, rest = g;
                     big.M = (int)m_split;
                     big.tile_hint = 1;
@@ -298,6 +311,13 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, 
                         hipError_t e = timed_mfma(big, s);
                         if (e != hipSuccess) return e;
                         return timed_mfma(rest, s);
+                    }
+                } else if (c_all192 < c_all256) {
+                    GemmArgs t = g;
+                    t.tile_hint = 3;
+                    if (gemm_mfma_supported(t)) {
+                        if (colsum_bands) *colsum_bands = 2 * ((g.M + 191) / 192);
+                        return timed_mfma(t, s);
                     }
                 }
             }
