@@ -260,12 +260,12 @@ __device__ __forceinline__ void fwd_unit(const bf16* Ks, const bf16* Vs, bf16x8 
     sum += __shfl_xor(sum, 32, 64);   // the two lanes of a query hold different keys
 }
 
-// This lane's query row of the unit's result: O = O^T columns / sum, and the log-sum-exp if asked for.
-// A lane holds 4 consecutive channels per group of 8 and its partner 32 lanes up (same query) the other 4:
-// the two exchange halves (v_permlane32_swap), so each stores 16-byte pieces and a query row goes out as
-// 32 contiguous bytes per store instruction.  All lanes must call; ok says whether this lane's query exists.
-__device__ __forceinline__ void fwd_store(const f32x16 (&ot)[2], float m, float sum, bf16* orow, float* lse_q, int h, bool ok) {
-    const float inv = 1.0f / sum;
+// A transposed 64 x 32 result (rows = channels in two 32-row halves, column = this lane's token) times mul
+// goes to the token's row.  A lane holds 4 consecutive channels per group of 8 and its partner 32 lanes up
+// (same token) the other 4: the two exchange halves (v_permlane32_swap), so each stores 16-byte pieces and a
+// row goes out as 32 contiguous bytes per store instruction.  All lanes must call; ok says whether this
+// lane's token exists.
+__device__ __forceinline__ void store_t_rows(const f32x16 (&ot)[2], float mul, bf16* orow, int h, bool ok) {
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -273,8 +273,8 @@ __device__ __forceinline__ void fwd_store(const f32x16 (&ot)[2], float m, float 
             uint32_t a[2], b[2];   // groups 2p and 2p + 1: this lane's 4 channels of each, packed
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
-                a[r] = pack_bf16x2(ot[dt][8 * p + 2 * r] * inv, ot[dt][8 * p + 2 * r + 1] * inv);
-                b[r] = pack_bf16x2(ot[dt][8 * p + 4 + 2 * r] * inv, ot[dt][8 * p + 4 + 2 * r + 1] * inv);
+                a[r] = pack_bf16x2(ot[dt][8 * p + 2 * r] * mul, ot[dt][8 * p + 2 * r + 1] * mul);
+                b[r] = pack_bf16x2(ot[dt][8 * p + 4 + 2 * r] * mul, ot[dt][8 * p + 4 + 2 * r + 1] * mul);
                 // upper half of a <-> lower half of b
                 const auto sw = __builtin_amdgcn_permlane32_swap(a[r], b[r], false, false);
                 a[r] = sw[0];
@@ -283,6 +283,11 @@ __device__ __forceinline__ void fwd_store(const f32x16 (&ot)[2], float m, float 
             // lower lanes now hold channels 8 (2p) .. + 7 (their own 4, then the partner's), upper lanes 8 (2p + 1) .. + 7
             if (ok) *reinterpret_cast<uint4*>(orow + dt * 32 + 8 * (2 * p + h)) = make_uint4(a[0], a[1], b[0], b[1]);
         }
+}
+
+// this lane's query row of a forward unit: O = O^T columns / sum, and the log-sum-exp if asked for
+__device__ __forceinline__ void fwd_store(const f32x16 (&ot)[2], float m, float sum, bf16* orow, float* lse_q, int h, bool ok) {
+    store_t_rows(ot, 1.0f / sum, orow, h, ok);
     if (ok && h == 0 && lse_q) *lse_q = m * kScale + __logf(sum);
 }
 
@@ -500,7 +505,30 @@ hipError_t launch_fwd_kt(const bf16* qkv, long ldq, bf16* o, long ldo, float* ls
 // If bsum is given the kernel also writes the column sums of the pair's dQ, dK, dV rows (the
 // gradient of the QKV bias: one row of 192 partial sums per image).
 // ---------------------------------------------------------------------------
-constexpr int kTS = 104;   // rows that are read both ways (row-form and transposing): 208 bytes
+constexpr int kTS = 104;   // K rows, read both ways once (row-form and transposing): 208 bytes
+// Query tiles (Q_i, dO_i) are read both ways in every step.  A 128-bit row-form read is free of bank conflicts
+// when eight consecutive rows start in different 16-byte slots of a 128-byte line (row stride an odd multiple
+// of 16 bytes); a transposing read when the four rows of a 16-lane group start 32 bytes apart modulo 128.  No
+// stride does both for rows in their natural order, so row r of every group of eight is kept at position
+// (0, 2, 4, 6, 1, 3, 5, 7)[r % 8] with a stride of 176 bytes: eight rows still start in eight different slots,
+// and rows r .. r + 3 of a half group sit two strides apart, i.e. 96 bytes modulo 128.
+constexpr int kQS = 88;
+__device__ __forceinline__ int tile_row(int r) { return (r & ~7) | ((r & 3) << 1) | ((r >> 2) & 1); }
+// the transposing read of frag_tr for such a tile: logical rows t0 + 4h + {0..3} and t0 + 8 + 4h + {0..3}
+__device__ __forceinline__ bf16x8 frag_tr_tile(const bf16* lds, int t0, int ch0, int lane) {
+    const int j = lane & 15;
+    const bf16* p = lds + (t0 + 2 * (j >> 2) + (lane >> 5)) * kQS + ch0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr_t;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 8 * kQS));
+    s16x8 r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return __builtin_bit_cast(bf16x8, r);
+}
+// dS tiles [32 keys][32 queries]: rows of 96 bytes, so that the four key rows of a transposing read start
+// 32 bytes apart modulo 128
+constexpr int kDS = 48;
 
 // f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop whose index is a compile-time constant
 template <typename F, int... I>
@@ -528,13 +556,14 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
     constexpr int NKL = (TP * 8 + NTHR - 1) / NTHR;      // 16-byte chunks of K per thread
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* Ks = reinterpret_cast<bf16*>(smem_raw);        // [TP][kTS]      read transposed by the dQ wavefront
-    bf16* Qs = Ks + TP * kTS;                            // [3][32][kTS]   query tile i in buffer i % 3
-    bf16* dOs = Qs + 3 * 32 * kTS;                       // [3][32][kTS]
-    bf16* dSs_all = dOs + 3 * 32 * kTS;                  // [2][KT][32 keys][32 queries]
-    float* lse_s = reinterpret_cast<float*>(dSs_all + 2 * KT * 32 * 32);   // [TP]   -8 lse_q
+    bf16* Qs = Ks + TP * kTS;                            // [3][32][kQS]   query tile i in buffer i % 3, rows permuted
+    bf16* dOs = Qs + 3 * 32 * kQS;                       // [3][32][kQS]
+    bf16* dSs_all = dOs + 3 * 32 * kQS;                  // [2][KT][32 keys][kDS]
+    float* lse_s = reinterpret_cast<float*>(dSs_all + 2 * KT * 32 * kDS);   // [TP]   -8 lse_q
     float* del_s = lse_s + TP;                           // [TP]   -delta_q
     bf16* dq_stage = reinterpret_cast<bf16*>(del_s + TP);   // [32][72]   the dQ wavefront's store staging
     float* red = reinterpret_cast<float*>(dq_stage + 32 * 72);   // [KT][128]   column sums of dK, dV per key tile
+    float* sk_s = red + KT * 128;                        // [TP]   sum over the queries of dS[q][key], for dQ's column sums
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int b = blockIdx.x / n_full;   // with a mask n_full is the number of slots per image
@@ -598,13 +627,13 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
         for (int k = 0; k < NLD; ++k) {
             const int id = threadIdx.x + k * NTHR;
             const int t = id & 255;
-            bf16* dst = (id < 256 ? Qs : dOs) + (i % 3) * 32 * kTS + (t >> 3) * kTS + (t & 7) * 8;
+            bf16* dst = (id < 256 ? Qs : dOs) + (i % 3) * 32 * kQS + tile_row(t >> 3) * kQS + (t & 7) * 8;
             if (id < 512) *reinterpret_cast<u32x4*>(dst) = nx[k];
         }
         if (extra && threadIdx.x < 64) {   // the constants of tile i's 32 queries: Q rows, then dO rows
             const int r = threadIdx.x & 31;
             const bool is_q = threadIdx.x < 32;
-            store_extra((is_q ? Qs : dOs) + (i % 3) * 32 * kTS + r * kTS, (is_q ? lse_s : del_s)[i * 32 + r]);
+            store_extra((is_q ? Qs : dOs) + (i % 3) * 32 * kQS + tile_row(r) * kQS, (is_q ? lse_s : del_s)[i * 32 + r]);
         }
     };
     // V operand fragments of this wavefront's key tile: rows u*32 + c of V, 8 channels at kk*16 + 8h
@@ -679,15 +708,16 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
         if ((it & 7) == 0 && it < TP * 8) {
             const int q = it >> 3;
             del_s[q] = -dl;
-            if (q < 64) store_extra(dOs + (q >> 5) * 32 * kTS + (q & 31) * kTS, -dl);   // tiles 0 and 1 are in LDS already
+            if (q < 64) store_extra(dOs + (q >> 5) * 32 * kQS + tile_row(q & 31) * kQS, -dl);   // tiles 0 and 1 are in LDS already
         }
     }
 #pragma unroll
     for (int k = 0; k < (TP + NTHR - 1) / NTHR; ++k) {
         const int q = threadIdx.x + k * NTHR;
         if (q < TP) {
+            sk_s[q] = 0.f;
             lse_s[q] = -8.f * lq[k];
-            if (q < 64) store_extra(Qs + (q >> 5) * 32 * kTS + (q & 31) * kTS, -8.f * lq[k]);
+            if (q < 64) store_extra(Qs + (q >> 5) * 32 * kQS + tile_row(q & 31) * kQS, -8.f * lq[k]);
         }
     }
     __syncthreads();
@@ -716,7 +746,7 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
             f32x16 s0 = zero16();
 #pragma unroll
             for (int kk = 0; kk < 5; ++kk)
-                s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kTS, c, kk * 16 + 8 * h), kfr[kk], s0, 0, 0, 0);
+                s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, kQS, tile_row(c), kk * 16 + 8 * h), kfr[kk], s0, 0, 0, 0);
             sc[0] = s0;
         }
         static_for<KT + 1>([&](auto step_index) {
@@ -730,22 +760,22 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
                 // Issue order of a step: all fragment reads; dP of this tile and S of the next one on the matrix
                 // cores with the exponentials of this tile's S (computed one step ago) between them on the vector
                 // ALUs; dV with dS and its hand-over between the MFMAs; dK, which runs under the next step's reads.
-                const bf16* Qi = Qs + (i % 3) * 32 * kTS;
-                const bf16* dOi = dOs + (i % 3) * 32 * kTS;
-                const bf16* Qn = Qs + ((i + 1) % 3) * 32 * kTS;
+                const bf16* Qi = Qs + (i % 3) * 32 * kQS;
+                const bf16* dOi = dOs + (i % 3) * 32 * kQS;
+                const bf16* Qn = Qs + ((i + 1) % 3) * 32 * kQS;
                 bf16x8 dof[5], qnf[5], dot[2][2], qt[2][2];
 #pragma unroll
-                for (int kk = 0; kk < 5; ++kk) dof[kk] = frag_rows(dOi, kTS, c, kk * 16 + 8 * h);
+                for (int kk = 0; kk < 5; ++kk) dof[kk] = frag_rows(dOi, kQS, tile_row(c), kk * 16 + 8 * h);
                 if (i + 1 < KT) {
 #pragma unroll
-                    for (int kk = 0; kk < 5; ++kk) qnf[kk] = frag_rows(Qn, kTS, c, kk * 16 + 8 * h);
+                    for (int kk = 0; kk < 5; ++kk) qnf[kk] = frag_rows(Qn, kQS, tile_row(c), kk * 16 + 8 * h);
                 }
 #pragma unroll
                 for (int gp = 0; gp < 2; ++gp)
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
-                        dot[gp][dt] = frag_tr(dOi, kTS, 16 * gp, dt * 32, lane);
-                        qt[gp][dt] = frag_tr(Qi, kTS, 16 * gp, dt * 32, lane);
+                        dot[gp][dt] = frag_tr_tile(dOi, 16 * gp, dt * 32, lane);
+                        qt[gp][dt] = frag_tr_tile(Qi, 16 * gp, dt * 32, lane);
                     }
                 __builtin_amdgcn_sched_barrier(0);
                 f32x16 dp = zero16(), sn = zero16();   // dP - delta, and S - 8 lse of the next tile
@@ -770,7 +800,7 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
                 }
                 if (i + 1 < KT) sc[(i + 1) & 1] = sn;
                 __builtin_amdgcn_sched_barrier(0);
-                bf16* dSs = dSs_all + ((i & 1) * KT + wave) * 32 * 32;
+                bf16* dSs = dSs_all + ((i & 1) * KT + wave) * 32 * kDS;
                 f32x16 ds;
                 bf16x8 dsf[2];
 #pragma unroll
@@ -787,7 +817,7 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
                     uint2 pk;
                     pk.x = pack_bf16x2(ds[4 * eg], ds[4 * eg + 1]);
                     pk.y = pack_bf16x2(ds[4 * eg + 2], ds[4 * eg + 3]);
-                    *reinterpret_cast<uint2*>(dSs + c * 32 + 8 * eg + 4 * h) = pk;
+                    *reinterpret_cast<uint2*>(dSs + c * kDS + 8 * eg + 4 * h) = pk;
                 }
 #pragma unroll
                 for (int gp = 0; gp < 2; ++gp) dsf[gp] = pack8(ds, 8 * gp);
@@ -803,22 +833,38 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt)
                         dKt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[gp][dt], dsf[gp], dKt[dt], 0, 0, 0);
+                if (bsum) {   // uniform over the grid
+                    // the dS values as the dQ wavefront multiplies them (bf16), added over this lane's 16 queries
+                    // under the products above and then to the key's running sum in LDS (both lanes of a key add)
+                    float t = 0.f;
+#pragma unroll
+                    for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) t += static_cast<float>(dsf[gp][k]);
+                    atomicAdd(sk_s + u * 32 + c, t);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        // dK^T, dV^T through the wavefront's LDS area so that a key row leaves as 16-byte pieces
+        // The column sums of dQ = (1/8) dS K follow from the query sums of dS: sum_q dQ[q][d] = (1/8) sum_k sk[k] K[k][d];
+        // the dQ wavefront forms them from the sums in sk_s while the key wavefronts store dK and dV.
         __syncthreads();   // the query tiles are free
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
+        // dK^T: straight from the accumulators, 16-byte pieces after a half-wave exchange.  Its column sums are
+        // not formed: sum_k dK[k][.] = (1/8) sum_q (sum_k dS[q][k]) Q[q][.] and sum_k dS[q][k] = sum_k P dP - delta_q = 0
+        // (softmax does not see a shift of all keys), so the key bias gradient is written as the zero it is.
+        store_t_rows(dKt, kScale, dQb + (long)(u * 32 + c) * ld_dqkv + 64, h, u * 32 + c < tokens);
+        if (!bsum) {
+            store_t_rows(dVt, 1.f, dQb + (long)(u * 32 + c) * ld_dqkv + 128, h, u * 32 + c < tokens);
+        } else {
+            // dV^T through the wavefront's LDS area, where its column sums are taken
+            constexpr int m = 1;
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                 for (int eg = 0; eg < 4; ++eg) {
-                    const f32x16& a = m == 0 ? dKt[dt] : dVt[dt];
-                    const float sc4 = m == 0 ? kScale : 1.f;
                     uint2 pk;
-                    pk.x = pack_bf16x2(a[4 * eg] * sc4, a[4 * eg + 1] * sc4);
-                    pk.y = pack_bf16x2(a[4 * eg + 2] * sc4, a[4 * eg + 3] * sc4);
+                    pk.x = pack_bf16x2(dVt[dt][4 * eg], dVt[dt][4 * eg + 1]);
+                    pk.y = pack_bf16x2(dVt[dt][4 * eg + 2], dVt[dt][4 * eg + 3]);
                     *reinterpret_cast<uint2*>(stage + c * 72 + dt * 32 + 8 * eg + 4 * h) = pk;
                 }
             __builtin_amdgcn_wave_barrier();
@@ -829,7 +875,7 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
                 const int key = u * 32 + r;
                 if (key < tokens) *reinterpret_cast<u32x4*>(dQb + (long)key * ld_dqkv + 64 + 64 * m + ch) = v;
             }
-            if (bsum) {   // uniform over the grid
+            {
                 // Column sums of the staged tile (the values as they are stored; rows beyond the last token are
                 // zero): lane (p = lane % 32, half = lane / 32) adds channels 2p, 2p + 1 over rows 16 half .. + 15
                 float s0 = 0.f, s1 = 0.f;
@@ -858,9 +904,6 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
             for (int gp = 0; gp < 2; ++gp)
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt) ktf[v][gp][dt] = frag_tr(Ks, kTS, v * 32 + 16 * gp, dt * 32, lane);
-        // column sums of dQ: lane (p = lane % 32, half = lane / 32) adds channels 2p, 2p + 1 over rows 16 half .. + 15 of
-        // every staged tile (the values as they are stored)
-        float qsum0 = 0.f, qsum1 = 0.f;
 #pragma unroll
         for (int i = 0; i <= KT; ++i) {
             if (i > 0) __syncthreads();   // the dS tiles of query tile i - 1 are visible
@@ -870,82 +913,71 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
             }
             if (i >= 1) {
                 // dQ^T of query tile i - 1: rows = channels, column = query c; four MFMA chains (channel half x
-                // 16-key half), added pairwise at the end.  The dS fragments of key tile v + 1 are read from LDS
-                // while the products of key tile v run.
+                // 16-key half), added pairwise at the end.  All dS fragments of the query tile are requested from
+                // LDS before the first product: this wavefront's step is the longest of the workgroup.
                 const int t = i - 1;
-                const bf16* dSt = dSs_all + ((t & 1) * KT) * 32 * 32;
+                const bf16* dSt = dSs_all + ((t & 1) * KT) * 32 * kDS;
                 f32x16 acc[2][2] = {{zero16(), zero16()}, {zero16(), zero16()}};
-                bf16x8 dsf[2][2];   // [buffer][16-key half]
-                auto read_group = [&](int v, int buf) {
+                bf16x8 dsf[KT][2];   // [key tile][16-key half]
+#pragma unroll
+                for (int v = 0; v < KT; ++v)
 #pragma unroll
                     for (int gp = 0; gp < 2; ++gp)
-                        dsf[buf][gp] = frag_tr(dSt + v * 32 * 32, 32, 16 * gp, 0, lane);   // column = query c, slots = keys
-                };
-                read_group(0, 0);
+                        dsf[v][gp] = frag_tr(dSt + v * 32 * kDS, kDS, 16 * gp, 0, lane);   // column = query c, slots = keys
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int v = 0; v < KT; ++v) {
-                    if (v + 1 < KT) read_group(v + 1, (v + 1) & 1);
 #pragma unroll
                     for (int gp = 0; gp < 2; ++gp)
 #pragma unroll
                         for (int dt = 0; dt < 2; ++dt)
-                            acc[gp][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[v][gp][dt], dsf[v & 1][gp], acc[gp][dt], 0, 0, 0);
-                    if (v + 1 < KT) {
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read of the next group
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                            acc[gp][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[v][gp][dt], dsf[v][gp], acc[gp][dt], 0, 0, 0);
                 }
-                // through the wavefront's LDS area, so that a query row leaves as 16-byte pieces
+                __builtin_amdgcn_sched_barrier(0);
+                // straight from the accumulators: 16-byte pieces after a half-wave exchange
 #pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    f32x16 r;
+                for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) r[e] = (acc[0][dt][e] + acc[1][dt][e]) * kScale;
-#pragma unroll
-                    for (int eg = 0; eg < 4; ++eg) {
-                        uint2 pk;
-                        pk.x = pack_bf16x2(r[4 * eg], r[4 * eg + 1]);
-                        pk.y = pack_bf16x2(r[4 * eg + 2], r[4 * eg + 3]);
-                        *reinterpret_cast<uint2*>(stage + c * 72 + dt * 32 + 8 * eg + 4 * h) = pk;
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int id = lane + 64 * k, r = id >> 3, ch = (id & 7) * 8;
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * 72 + ch);
-                    if (t * 32 + r < tokens) *reinterpret_cast<u32x4*>(dQb + (long)(t * 32 + r) * ld_dqkv + ch) = v;
-                }
-                if (bsum) {   // rows beyond the last token are zero
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const uint32_t w = *reinterpret_cast<const uint32_t*>(stage + (16 * h + r) * 72 + 2 * c);
-                        qsum0 += __uint_as_float(w << 16);
-                        qsum1 += __uint_as_float(w & 0xffff0000u);
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
+                    for (int e = 0; e < 16; ++e) acc[0][dt][e] += acc[1][dt][e];
+                store_t_rows(acc[0], kScale, dQb + (long)(t * 32 + c) * ld_dqkv, h, t * 32 + c < tokens);
             }
         }
-        __syncthreads();   // matches the key wavefronts' barrier before their stores
+        __syncthreads();   // matches the key wavefronts' barrier before their stores; their sk are visible
         if (bsum) {
-            qsum0 += __shfl_xor(qsum0, 32, 64);
-            qsum1 += __shfl_xor(qsum1, 32, 64);
-            if (h == 0) {
-                bout[2 * c] = qsum0;
-                bout[2 * c + 1] = qsum1;
+            // sum_k sk[k] K[k][.]: lane (piece = lane % 8, part = lane / 8) takes channels 8 piece .. + 7 of the keys
+            // k = part, part + 8, ...; the eight parts are added in lane order
+            float a8[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a8[i] = 0.f;
+            const int piece = lane & 7, part = lane >> 3;
+#pragma unroll 4
+            for (int k = part; k < TP; k += 8) {   // rows of K beyond the last token are zero
+                const u32x4 kv = *reinterpret_cast<const u32x4*>(Ks + k * kTS + piece * 8);
+                const float w = sk_s[k];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    a8[2 * i] = fmaf(w, __uint_as_float(kv[i] << 16), a8[2 * i]);
+                    a8[2 * i + 1] = fmaf(w, __uint_as_float(kv[i] & 0xffff0000u), a8[2 * i + 1]);
+                }
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float t = a8[i];
+                t += __shfl_xor(t, 8, 64);
+                t += __shfl_xor(t, 16, 64);
+                t += __shfl_xor(t, 32, 64);
+                a8[i] = t * kScale;
+            }
+            if (part == 0) store8(bout + piece * 8, a8);
             __syncthreads();
         }
     }
-    if (bsum && threadIdx.x < 128) {   // dK and dV sums: key tiles added in index order
+    if (bsum && threadIdx.x < 128) {   // dK sums (zero) and dV sums: key tiles added in index order
         float t = 0.f;
+        if (threadIdx.x >= 64) {
 #pragma unroll
-        for (int v = 0; v < KT; ++v) t += red[v * 128 + threadIdx.x];
+            for (int v = 0; v < KT; ++v) t += red[v * 128 + threadIdx.x];
+        }
         bout[64 + threadIdx.x] = t;
     }
 }
@@ -953,9 +985,9 @@ __global__ __launch_bounds__(64 * (KT + 1)) void attn_bwd_mfma_kernel(const bf16
 template <int KT>
 constexpr size_t bwd_lds_bytes() {
     constexpr int TP = KT * 32;
-    static_assert(KT * 32 * 72 <= 6 * 32 * kTS, "the key wavefronts' store staging fits the query tiles' space");
-    constexpr size_t tiles = (size_t)(TP * kTS + 6 * 32 * kTS + 2 * KT * 32 * 32 + 32 * 72) * sizeof(bf16) +
-                             (size_t)(2 * TP + KT * 128) * sizeof(float);
+    static_assert(KT * 32 * 72 <= 6 * 32 * kQS, "the key wavefronts' store staging fits the query tiles' space");
+    constexpr size_t tiles = (size_t)(TP * kTS + 6 * 32 * kQS + 2 * KT * 32 * kDS + 32 * 72) * sizeof(bf16) +
+                             (size_t)(3 * TP + KT * 128) * sizeof(float);
     return tiles;
 }
 
