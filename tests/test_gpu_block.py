@@ -143,6 +143,19 @@ def test_bf16_vit_small_block(flags):
     run_case(MID_BF16, [FULL, FWD, SKIP, FULL, FULL, FWD], seed=11, flags=flags)
 
 
+def test_bf16_key_bias_gradient_is_exactly_zero():
+    """The matrix-core attention backward writes the key-bias gradient as the zero it is (softmax does not see
+    a common shift of the keys; pinned for the oracle in test_oracle_block.py) instead of adding up rounded
+    dK rows; the value and query planes of the same tensor are compared with the oracle by run_case."""
+    ops = [FULL, FWD, SKIP, FULL, FULL, FWD]
+    got, _ = run_case(MID_BF16, ops, seed=13)
+    gb = np.asarray(got[2]["b_qkv"], dtype=np.float64).reshape(3, MID_BF16.heads, 64)
+    for h, o in enumerate(ops):
+        if o == FULL:
+            assert np.all(gb[1, h] == 0.0)
+            assert np.abs(gb[0, h]).max() > 0.0 and np.abs(gb[2, h]).max() > 0.0
+
+
 def test_bf16_ragged_widths():
     w = di.Workload("ragged_bf16", 2, 50, 200, 3, 64, 328, 1, "bf16")
     run_case(w, [FWD, FULL, FULL], seed=12)

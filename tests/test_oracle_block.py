@@ -208,6 +208,37 @@ def test_non_full_heads_get_exactly_zero_gradients(ops):
                 assert np.all(s == 0.0) and not np.any(np.signbit(s))
 
 
+def test_key_bias_gradient_vanishes_and_value_bias_gradient_is_the_sum_of_dO():
+    """Two closed forms of softmax attention (Sec. II-A.2, the p_f backward).  A shift of every key of a head
+    by the same vector moves all scores of a query by the same amount, which the softmax does not see, so the
+    gradient of the key bias is zero.  The rows of the probability matrix sum to one, so the gradient of the
+    value bias is the column sum of the gradient that reaches the head's output."""
+    w = tiny(heads=3)
+    x, wt, dy = draw(w, 21)
+    ops = (FULL, FWD, FULL)
+    _, cache = orc.block_fwd(wt, ops, x, w.head_dim)
+    _, g = orc.block_bwd(wt, cache, dy)
+    scale = np.abs(g["b_qkv"]).max()
+    assert scale > 0.0
+    dh = w.head_dim
+    # dO = dx1 W_o[:, head]: rebuilt here from the out-projection bias gradient's operand, dx1 = sum of dy routes
+    # (taken through autograd, which knows neither identity)
+    ref, xt, P = torch_block(wt, ops, x, w.head_dim)
+    ref.backward(torch.tensor(dy))
+    gb = P["b_qkv"].grad.numpy()
+    for h, o in enumerate(ops):
+        if o != FULL:
+            continue
+        assert np.abs(g["b_qkv"][1, h]).max() <= 1e-12 * scale        # key plane
+        assert np.abs(gb[1, h]).max() <= 1e-12 * scale
+        assert relerr(g["b_qkv"][2, h], gb[2, h]) < 1e-10             # value plane against autograd
+    # the value plane is also W_o^T applied to the out-projection bias gradient, head by head
+    wo = wt["w_o"]
+    for h, o in enumerate(ops):
+        if o == FULL:
+            assert relerr(g["b_qkv"][2, h], g["b_o"] @ wo[:, h * dh:(h + 1) * dh]) < 1e-10
+
+
 def test_no_full_heads_gives_residual_and_mlp_gradient_only():
     w = tiny(heads=3)
     x, wt, dy = draw(w, 9)
