@@ -105,6 +105,25 @@ struct GemmGroup {
 };
 constexpr int kMaxGemmGroups = 4;
 
+// Row segments of a GEMM whose output columns come in "positions" of `slice` columns, with a set of positions
+// per segment that take part (micro-batches with their own op codes over gated feed-forward slices): an
+// output element of a row in segment i and a column of position p is computed if bit p of pos[i] is set and
+// written as zero otherwise.  launch_gemm_mfma_seg skips the 256x256 tiles no row of which takes part (they are
+// only zero-filled) and deals the tiles with work evenly over the workgroups.
+constexpr int kMaxGemmSegments = 8;
+constexpr int kMaxSegTileRows = 64;
+struct GemmRowSegments {
+    int n;                               // 0: not in use
+    int slice;                           // columns per position, a multiple of 64
+    int end[kMaxGemmSegments];           // row ends, ascending; the last is M
+    uint64_t pos[kMaxGemmSegments];
+    // filled by the launcher, for 256 x 256 tiles
+    int live_tiles;
+    uint16_t row_live[kMaxSegTileRows];        // tile row t: bit j = column tile j has work in a segment the row overlaps
+    uint16_t row_before[kMaxSegTileRows + 1];  // tiles with work in the tile rows before t
+    uint8_t pos_segs[64];                      // position p: bit i = it takes part in segment i
+};
+
 struct GemmArgs {
     const void* A;
     const void* B;
@@ -131,6 +150,7 @@ struct GemmArgs {
                           // [bands][N]; band = colsum_row0 + 2 * (row tile) + (upper / lower half of the tile)
     int colsum_row0;
     Remap64 tbl;
+    GemmRowSegments seg;  // launch_gemm_mfma_seg only
 };
 
 // launchers (defined in the kernel sources); each returns hipGetLastError()
@@ -141,6 +161,12 @@ bool gemm_mfma_supported(const GemmArgs& g);
 // Grouped weight-gradient launch (bf16 MFMA only).  The caller fills K, partial, n_groups and grp[].{A, B, lda,
 // ldb, M, N}; the launcher fills the tile bookkeeping and returns it in *g for the reduction.  partial must hold
 // gemm_grouped_slots(g) tiles of 256 x 256 floats.  hipErrorNotSupported if an operand does not fit the kernel.
+// The forms with A row-major (C = A B, no split-K, no residual) over row segments: prepare takes g->seg.n, slice,
+// end and pos and fills the rest of g->seg, or returns hipErrorNotSupported if the shape does not fit (more than
+// 64 tile rows or 16 tile columns of 256, K not a multiple of 64, operands the matrix-core path does not take);
+// the launch takes a prepared g.
+hipError_t gemm_mfma_seg_prepare(GemmArgs* g);
+hipError_t launch_gemm_mfma_seg(const GemmArgs& g, hipStream_t s);
 size_t gemm_grouped_slots(const GemmArgs& g);
 hipError_t launch_gemm_grouped(GemmArgs* g, hipStream_t s);
 // out_g[r'][c'] (=|+=) sum over the slots of each tile, (r', c') through the group's remap

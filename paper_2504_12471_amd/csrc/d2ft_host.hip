@@ -337,6 +337,33 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, 
     return e;
 }
 
+// A gated feed-forward product over the whole batch whose micro-batches have their own codes: the rows of
+// micro-batch i times the slices (positions of `slice` columns) in pos_of[i], zeros elsewhere; 256x256 tiles
+// that no micro-batch needs are not multiplied.  hipErrorNotSupported (nothing launched) if the shape does not
+// fit: the caller then multiplies the union of the slices over all rows and zeroes afterwards.
+hipError_t run_gemm_segments(GemmArgs g, const d2ft_block_desc* d, const MicroMask& mask, const uint64_t* pos_of, int tokens,
+                             int slice, hipStream_t s, int* colsum_bands = nullptr) {
+    if (colsum_bands) *colsum_bands = 0;
+    if (!on_mfma_path(g, d) || mask.n > kMaxGemmSegments) return hipErrorNotSupported;
+    g.seg.n = mask.n;
+    g.seg.slice = slice;
+    double cols = 0.0;   // row x column pairs that take part
+    for (int i = 0; i < mask.n; ++i) {
+        g.seg.end[i] = mask.img_end[i] * tokens;
+        g.seg.pos[i] = pos_of[i];
+        cols += (double)(mask.img_end[i] - (i ? mask.img_end[i - 1] : 0)) * tokens * __builtin_popcountll(pos_of[i]) * slice;
+    }
+    if (gemm_mfma_seg_prepare(&g) != hipSuccess) return hipErrorNotSupported;
+    if (colsum_bands) *colsum_bands = 2 * ((g.M + 255) / 256);
+    timing_begin(s, "gemm");
+    g_timing.label = g.b_rs != 1 ? "gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 1, false, false, true>"
+                                 : "gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 1, false, false, true>";
+    g_timing.flops = 2.0 * cols * g.K;
+    const hipError_t e = launch_gemm_mfma_seg(g, s);
+    timing_end(s);
+    return e;
+}
+
 // bf16, head dimension 64, up to 224 tokens: the matrix-core attention kernels, forward and backward
 static bool attn_on_mfma(const d2ft_block_desc* d) {
     return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && d->tokens <= 224;
@@ -478,7 +505,7 @@ d2ft_status weight_grad_flush(WeightGradBatch* b, const d2ft_block_desc* d, cons
     hipError_t e = hipErrorNotSupported;
     if (gemm_grouped_slots(g) * 65536 <= part_floats) {
         timing_begin(st, "gemm");
-        g_timing.label = "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 0, false, true>";
+        g_timing.label = "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 0, false, true, false>";
         for (int i = 0; i < g.n_groups; ++i) g_timing.flops += 2.0 * g.grp[i].M * g.grp[i].N * s.M;
         e = launch_gemm_grouped(&g, st);
         timing_end(st);
@@ -722,9 +749,15 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         g.C = sv + SL.g; g.ldc = n_hid;
         g.bias = w->b1; g.bias_remap = gate ? 1 : 0;
         g.act = ACT_GELU; g.Z = sv + SL.z; g.ldz = n_hid;
-        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
-        // a subnet skipped in a micro-batch adds nothing to that micro-batch's rows
-        if (gate && mask) D2FT_TRY(launch_zero_pairs(s.dtype, sv + SL.g, sv + SL.z, n_hid, s.B, s.T, nl, slice, PAIRS_SKIPPED, *mask, st));
+        // a subnet skipped in a micro-batch adds nothing to that micro-batch's rows: left out of the product, or
+        // zeroed behind it
+        hipError_t es = (gate && mask) ? run_gemm_segments(g, desc, *mask, mask->live, s.T, slice, st) : hipErrorNotSupported;
+        if (es == hipErrorNotSupported) {
+            D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+            if (gate && mask) D2FT_TRY(launch_zero_pairs(s.dtype, sv + SL.g, sv + SL.z, n_hid, s.B, s.T, nl, slice, PAIRS_SKIPPED, *mask, st));
+        } else if (es != hipSuccess) {
+            return D2FT_EDEVICE;
+        }
     }
     {   // y = x1 + g W2^T + b2
         GemmArgs g = gemm_base();
@@ -857,7 +890,11 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             g.C = ws + WL.dz; g.ldc = n_hid;
             g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = ld_hid;
             if (grads->b1 && on_mfma_path(g, desc)) g.colsum = (float*)(ws + WL.colfuse_b1);   // db1 = column sums of dz
-            D2FT_TRY_UNTIMED(run_gemm(g, desc, st, &b1_bands));
+            // micro-batches with their own codes: the saved GELU' is zero where a slice was not p_f, so those
+            // products need not be formed
+            hipError_t es = (gate && mask) ? run_gemm_segments(g, desc, *mask, mask->full, s.T, slice, st, &b1_bands) : hipErrorNotSupported;
+            if (es == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(g, desc, st, &b1_bands));
+            else if (es != hipSuccess) return D2FT_EDEVICE;
             if (!g.colsum) b1_bands = 0;
         }
         if (grads->w1) {   // dW1[hidden] = dz^T v

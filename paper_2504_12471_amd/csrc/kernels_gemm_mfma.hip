@@ -232,7 +232,8 @@ __device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, i
     tn = in_group / gsize;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool GROUPED = false>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool GROUPED = false,
+          bool SEGMENTS = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    const int total = tiles_m * tiles_n * (g.partial ? g.splits : 1);
+    const int total = SEGMENTS ? g.seg.live_tiles : tiles_m * tiles_n * (g.partial ? g.splits : 1);
 
     f32x16 acc[MT][NT];
     SlabLoader<BM, BK, A_COL, kThreads> la;
@@ -293,12 +294,30 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     };
     auto setup_tile = [&](int pid) {
         int tile_m, tile_n;
-        tile_of_block(pid, total, tiles_m, tiles_n, tile_m, tile_n, split);
+        if (SEGMENTS && total == tiles_m * tiles_n) {
+            tile_of_block(pid, total, tiles_m, tiles_n, tile_m, tile_n, split);
+        } else if constexpr (SEGMENTS) {
+            // the pid-th tile with work, counted row by row (ids with equal id mod 8 get a contiguous range)
+            const int xcd = pid & 7, idx = pid >> 3;
+            const int lid = xcd * (total >> 3) + min(xcd, total & 7) + idx;
+            int hi = tiles_m;   // the last tile row with row_before <= lid (bisection: each probe is a scalar load)
+            tile_m = 0;
+            while (hi - tile_m > 1) {
+                const int mid = (tile_m + hi) >> 1;
+                if ((int)g.seg.row_before[mid] <= lid) tile_m = mid; else hi = mid;
+            }
+            uint32_t live = g.seg.row_live[tile_m];
+            for (int j = lid - (int)g.seg.row_before[tile_m]; j > 0; --j) live &= live - 1;
+            tile_n = __builtin_ctz(live);
+            split = 0;
+        } else {
+            tile_of_block(pid, total, tiles_m, tiles_n, tile_m, tile_n, split);
+        }
         m0 = tile_m * BM;
         n0 = tile_n * BN;
         kb = 0;
         ke = g.K;
-        if (g.partial) {
+        if (!SEGMENTS && g.partial) {
             int per = (g.K + g.splits - 1) / g.splits;
             per = (per + BK - 1) / BK * BK;
             kb = split * per;
@@ -352,7 +371,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
 
     int pid = blockIdx.x;
     bool have_work = true;
-    if constexpr (grouped) have_work = setup_piece(); else setup_tile(pid);
+    if constexpr (grouped) {
+        have_work = setup_piece();
+    } else {
+        if constexpr (SEGMENTS) have_work = pid < total;
+        if (have_work) setup_tile(pid);
+    }
     while (have_work) {
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -447,13 +471,49 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     const int col_l = lane & 31, row_l = 4 * (lane >> 5);
     bf16* __restrict__ C = static_cast<bf16*>(g.C);
     const bf16* bias = static_cast<const bf16*>(g.bias);
-    const bf16* R = static_cast<const bf16*>(g.residual);
+    const bf16* R = SEGMENTS ? nullptr : static_cast<const bf16*>(g.residual);   // the segment form takes neither
     bf16* Z = static_cast<bf16*>(g.Z);
-    float* P = g.partial ? g.partial + (long)esplit * g.M * g.N : nullptr;
+    float* P = (!SEGMENTS && g.partial) ? g.partial + (long)esplit * g.M * g.N : nullptr;
     float* const Pslot = g.partial + (long)eslot * (BM * BN);   // grouped mode: a whole tile per slot
     // a lane reads back the same 8 columns in every chunk (64 is a multiple of the chunks per row),
     // so its bias values are fetched once per tile
     static_assert(64 % CPR == 0, "a lane keeps its columns over the chunks of a band");
+    // row segments: bit t * CPL + c of rows_alive = the lane's row of chunk c in band t lies in a segment in which
+    // the wavefront's 64 columns (all of one position) take part
+    uint32_t rows_alive = 0;
+    if constexpr (SEGMENTS) {
+        static_assert(MT * CPL <= 32, "one bit per row a lane reads back");
+        // the segments in which the position takes part, one bit each (two scalar loads, both issued at once)
+        const int p = __builtin_amdgcn_readfirstlane((en0 + wn * WTN) / g.seg.slice);
+        const uint32_t segs = g.seg.pos_segs[p & 63];
+        const int first = __builtin_amdgcn_readfirstlane(em0 + wm * WTM);
+        // the segment ends are fetched here, per tile: as loop invariants they would be held in registers the
+        // main loop has no room for
+        int at;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(at));
+        int ends[kMaxGemmSegments - 1];
+#pragma unroll
+        for (int i = 0; i + 1 < kMaxGemmSegments; ++i) ends[i] = g.seg.end[at + i];
+        int s0 = 0, s1 = 0;   // segments of the wavefront's first and last row
+#pragma unroll
+        for (int i = 0; i + 1 < kMaxGemmSegments; ++i) {
+            s0 += (first >= ends[i]) ? 1 : 0;
+            s1 += (first + WTM - 1 >= ends[i]) ? 1 : 0;
+        }
+        if (s0 == s1) {   // nearly always: no segment ends inside the wavefront's rows
+            rows_alive = ((segs >> s0) & 1) ? 0xffffffffu : 0u;
+        } else {
+            const int mbase = first + lane / CPR;
+#pragma unroll
+            for (int j = 0; j < MT * CPL; ++j) {
+                const int m = mbase + (j / CPL) * 32 + (j % CPL) * (64 / CPR);
+                int si = 0;
+#pragma unroll
+                for (int i = 0; i + 1 < kMaxGemmSegments; ++i) si += (m >= ends[i]) ? 1 : 0;
+                rows_alive |= ((segs >> si) & 1) << j;
+            }
+        }
+    }
     u32x4 braw = {0u, 0u, 0u, 0u};
     {
         const int nb = en0 + wn * WTN + (lane % CPR) * 8;
@@ -491,6 +551,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                 const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
                 const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
                 v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+                const bool alive = !SEGMENTS || ((rows_alive >> (t * CPL + c)) & 1);
                 if (P) {
                     store8(P + (long)m * g.N + n, v);
                 } else {
@@ -511,12 +572,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                             gp[i] = fmaf(zr * 0.39894228040143267794f, __builtin_amdgcn_exp2f(-0.72134752044448170368f * zr * zr), ph);
                             v[i] = zr * ph;
                         }
+                        if (SEGMENTS && !alive) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) gp[i] = 0.f;
+                        }
                         store8(Z + (long)m * g.ldz + n, gp);
                     } else if (g.act == ACT_DGELU) {
                         float gp[8];
                         load8(Z + (long)m * g.ldz + n, gp);
 #pragma unroll
                         for (int i = 0; i < 8; ++i) v[i] *= gp[i];
+                    }
+                    if (SEGMENTS && !alive) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] = 0.f;
                     }
                     if (R) {
                         float rr[8];
@@ -551,6 +620,40 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
             store8(g.colsum + (long)(g.colsum_row0 + (em0 / BM) * WGM + wm) * g.N + n, csum);
     }
     __syncthreads();   // the stage area is operand buffer space of the next tile
+    }
+    if constexpr (SEGMENTS) {
+        // Tiles without work: zeros (results, saved derivative, column-sum bands), written in strips of 32 rows by
+        // the workgroups that had one tile less to multiply while the others are still busy, or by all of them,
+        // the last ones first, if those would be too few to keep the memory system busy.
+        const int dead = (tiles_m * tiles_n - total) * (BM / 32);
+        const int grid = gridDim.x, heavy = total % grid;   // workgroups 0 .. heavy-1 had the extra tile
+        const bool all_fill = grid - heavy < 64;
+        const int fillers = all_fill ? grid : grid - heavy;
+        bf16* Cz = static_cast<bf16*>(g.C);
+        bf16* Zz = static_cast<bf16*>(g.Z);
+        const float zero8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int du = all_fill ? grid - 1 - (int)blockIdx.x : (int)blockIdx.x - heavy; du >= 0 && du < dead; du += fillers) {
+            const int d = du / (BM / 32), strip = du % (BM / 32);
+            int tm = 0, hi = tiles_m;   // the last tile row with no more than d tiles without work before it
+            while (hi - tm > 1) {
+                const int mid = (tm + hi) >> 1;
+                if (mid * tiles_n - (int)g.seg.row_before[mid] <= d) tm = mid; else hi = mid;
+            }
+            uint32_t bits = ~(uint32_t)g.seg.row_live[tm] & ((1u << tiles_n) - 1u);
+            for (int j = d - (tm * tiles_n - (int)g.seg.row_before[tm]); j > 0; --j) bits &= bits - 1;
+            const int tn = __builtin_ctz(bits);
+            for (int i = threadIdx.x; i < 32 * (BN / 8); i += kThreads) {
+                const int m = tm * BM + strip * 32 + i / (BN / 8), n = tn * BN + (i % (BN / 8)) * 8;
+                if (m < g.M && n < g.N) {
+                    store8(Cz + (long)m * g.ldc + n, zero8);
+                    if (g.act == ACT_GELU) store8(Zz + (long)m * g.ldz + n, zero8);
+                }
+            }
+            if (g.colsum && strip < WGM && threadIdx.x < BN / 8) {
+                const int n = tn * BN + threadIdx.x * 8;
+                if (n < g.N) store8(g.colsum + (long)(g.colsum_row0 + tm * WGM + strip) * g.N + n, zero8);
+            }
+        }
     }
 }
 
@@ -630,6 +733,30 @@ hipError_t launch_grouped_cfg(GemmArgs* g, hipStream_t s) {
     const long units = (long)tile * best;
     long grid = units < resident ? (units + 7) / 8 * 8 : resident;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, *g);
+    return hipGetLastError();
+}
+
+// row-segment launch: the 256x256 tile, A row-major, K a multiple of 64
+template <bool B_COL, int REMAP>
+hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
+    constexpr int BM = 256, BN = 256, BK = 64, WGM = 2, WGN = 4;
+    constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, false, B_COL>();
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, false, B_COL, REMAP, false, false, true>;
+    static int resident = 0;
+    if (resident == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        int dev = 0, cus = 0, per_cu = 0;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * WGM * WGN, lds)) != hipSuccess) return e;
+        if (per_cu < 1) per_cu = 1;
+        resident = cus * per_cu / 8 * 8;
+        if (resident < 8) resident = 8;
+    }
+    const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
+    const long grid = tiles < resident ? (tiles + 7) / 8 * 8 : resident;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, g);
     return hipGetLastError();
 }
 
@@ -722,11 +849,11 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
     const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
     const int tile = pick_tile(g);
     const bool tail = (g.K % 64) != 0;
-    static char names[4][3][3][2][72];
+    static char names[4][3][3][2][80];
     char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail];
     if (!name[0]) {
         const int bm = tile == 0 ? 128 : (tile == 3 ? 192 : 256), bn = tile == 0 ? 128 : 256;
-        snprintf(name, sizeof(names[0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false>", bm, bn,
+        snprintf(name, sizeof(names[0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false, false>", bm, bn,
                  tile == 0 ? 2 : 4, a_col ? "true" : "false", b_col ? "true" : "false",
                  g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false");
     }
@@ -742,6 +869,52 @@ static bool grouped_ok(const GemmArgs& g) {
         if ((long)g.K * G.lda * 2 >= (1L << 31) || (long)g.K * G.ldb * 2 >= (1L << 31)) return false;   // 32-bit offsets
     }
     return true;
+}
+
+hipError_t gemm_mfma_seg_prepare(GemmArgs* g) {
+    GemmRowSegments& S = g->seg;
+    if (!gemm_mfma_supported(*g) || g->partial || g->a_cs != 1 || g->K % 64) return hipErrorNotSupported;
+    if (g->residual) return hipErrorNotSupported;   // a row that takes no part is written as zero, not as the residual
+    const int tiles_m = (g->M + 255) / 256, tiles_n = (g->N + 255) / 256;
+    if (S.n < 1 || S.n > kMaxGemmSegments || S.slice < 64 || S.slice % 64 || tiles_m > kMaxSegTileRows || tiles_n > 16 ||
+        (g->N + S.slice - 1) / S.slice > 64 || S.end[S.n - 1] != g->M)
+        return hipErrorNotSupported;
+    for (int i = 0; i < S.n; ++i)
+        if (S.end[i] <= (i ? S.end[i - 1] : 0)) return hipErrorNotSupported;
+    for (int i = S.n; i < kMaxGemmSegments; ++i) {   // rows beyond M belong to no segment that takes part
+        S.end[i] = 0x7fffffff;
+        S.pos[i] = 0;
+    }
+    int before = 0;
+    for (int t = 0; t < tiles_m; ++t) {
+        const int r0 = t * 256, r1 = (t + 1) * 256 < g->M ? (t + 1) * 256 : g->M;
+        uint64_t pos = 0;   // positions that take part in any segment the tile row overlaps
+        for (int i = 0; i < S.n; ++i)
+            if ((i ? S.end[i - 1] : 0) < r1 && S.end[i] > r0) pos |= S.pos[i];
+        uint32_t live = 0;
+        for (int j = 0; j < tiles_n; ++j) {
+            const int p0 = j * 256 / S.slice, p1 = ((j + 1) * 256 < g->N ? (j + 1) * 256 : g->N) - 1;
+            for (int p = p0; p <= p1 / S.slice; ++p)
+                if ((pos >> p) & 1) live |= 1u << j;
+        }
+        S.row_live[t] = (uint16_t)live;
+        S.row_before[t] = (uint16_t)before;
+        before += __builtin_popcount(live);
+    }
+    for (int t = tiles_m; t <= kMaxSegTileRows; ++t) S.row_before[t] = (uint16_t)before;
+    for (int t = tiles_m; t < kMaxSegTileRows; ++t) S.row_live[t] = 0;
+    for (int p = 0; p < 64; ++p) {
+        S.pos_segs[p] = 0;
+        for (int i = 0; i < S.n; ++i) S.pos_segs[p] |= (uint8_t)(((S.pos[i] >> p) & 1) << i);
+    }
+    S.live_tiles = before;
+    return g->remap == REMAP_B_N ? hipSuccess : hipErrorNotSupported;   // the gated feed-forward forms
+}
+
+hipError_t launch_gemm_mfma_seg(const GemmArgs& g, hipStream_t s) {
+    const bool b_col = (g.b_rs != 1);
+    if (g.remap != REMAP_B_N || g.seg.n < 1) return hipErrorNotSupported;
+    return b_col ? launch_seg_cfg<true, REMAP_B_N>(g, s) : launch_seg_cfg<false, REMAP_B_N>(g, s);
 }
 
 size_t gemm_grouped_slots(const GemmArgs& g) {

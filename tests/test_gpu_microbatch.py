@@ -116,6 +116,46 @@ def test_bf16_union_of_codes_gated_feed_forward():
         assert np.all(g["w1"][h * S:(h + 1) * S] == 0.0) and np.all(g["w2"][:, h * S:(h + 1) * S] == 0.0)
 
 
+def segment_launches(fn):
+    """Runs fn with the library's per-kernel timing on; returns the launches of the row-segment GEMM kernels."""
+    import paper_2504_12471_amd as P
+    P.d2ft_timing_enable(True)
+    try:
+        fn()
+        recs = P.d2ft_timing_read(256)
+    finally:
+        P.d2ft_timing_enable(False)
+    return sum(r["launches"] for r in recs if r["name"].endswith("false, true>"))
+
+
+def test_bf16_gated_segments_slices_across_tiles_and_ends_inside_tiles():
+    """Gated feed-forward products over row segments: slices of 192 columns (positions straddle the 256-column
+    tiles), micro-batch ends inside the 256-row tiles, tiles without work (only head 0 lives in the last micro-
+    batch, nothing is p_f in the second), a single-image micro-batch."""
+    w = di.Workload("mb_seg_192", 9, 70, 512, 8, 64, 1536, 1, "bf16")
+    ops_mb = [[FULL, FWD, SKIP, FULL, FWD, SKIP, FULL, SKIP],
+              [FWD, SKIP, FWD, SKIP, SKIP, FWD, SKIP, SKIP],
+              [SKIP, FULL, FULL, FWD, SKIP, SKIP, FULL, FWD],
+              [FULL, SKIP, SKIP, SKIP, SKIP, SKIP, SKIP, SKIP]]
+    n = segment_launches(lambda: run_mb(w, ops_mb, [1, 3, 2, 3], seed=91, gate=True))
+    assert n == 2   # FC1 forward and the backward's dz
+
+
+def test_bf16_gated_segments_eight_micro_batches_and_the_fallback_beyond():
+    """Slices of 128 columns (two positions per tile column) over 8 micro-batches, the most the segment form
+    takes; with 9 the same block runs the union of the slices over all rows and zeroes afterwards."""
+    w = di.Workload("mb_seg_128", 12, 50, 256, 12, 64, 1536, 1, "bf16")
+    rng = np.random.default_rng(92)
+    ops8 = [list(rng.choice([FULL, FULL, FWD, SKIP, SKIP], size=w.heads)) for _ in range(8)]
+    for o in ops8:
+        o[0] = FULL
+    n = segment_launches(lambda: run_mb(w, ops8, [2, 1, 2, 1, 2, 1, 2, 1], seed=92, gate=True))
+    assert n == 2
+    ops9 = ops8 + [ops8[0]]
+    n = segment_launches(lambda: run_mb(w, ops9, [2, 1, 2, 1, 2, 1, 1, 1, 1], seed=93, gate=True))
+    assert n == 0
+
+
 def test_bf16_union_of_codes_without_a_full_head():
     w = di.Workload("mb_union_fwd", 4, 100, 256, 4, 64, 512, 1, "bf16")
     g, rg = run_mb(w, [[FWD, SKIP, SKIP, FWD], [SKIP, FWD, SKIP, SKIP]], [1, 3], seed=82)
