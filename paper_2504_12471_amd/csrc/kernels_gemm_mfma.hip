@@ -233,7 +233,7 @@ __device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, i
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool GROUPED = false,
-          bool SEGMENTS = false>
+          bool SEGMENTS = false, bool DGELU = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
@@ -526,6 +526,60 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     float csum[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) csum[i] = 0.f;
+    // DGELU: C = (A B) * Z with nothing else in the epilogue (the backward's dz), as an instantiation of its own.
+    // The saved derivative is fetched a band ahead - each chunk's registers are refilled for the next band as soon
+    // as the chunk is stored - instead of one dependent load per chunk.
+    if constexpr (DGELU) {
+        static_assert(!GROUPED && !A_COL, "a plain product with A row-major");
+        const int mrow = em0 + wm * WTM + lane / CPR;           // the lane's row of chunk 0 in band 0
+        const int n = en0 + wn * WTN + (lane % CPR) * 8;        // its columns in every chunk
+        const bf16* zp = Z + (long)mrow * g.ldz + n;
+        bf16* cp = C + (long)mrow * g.ldc + n;
+        const long zstep = (long)(64 / CPR) * g.ldz, cstep = (long)(64 / CPR) * g.ldc;   // rows between chunks
+        u32x4 zq[CPL];
+        auto fetch = [&](int t, int c) {   // zeros for a row outside the problem or outside its segment's slices
+            const int m = mrow + t * 32 + c * (64 / CPR);
+            const bool live = m < g.M && n < g.N && (!SEGMENTS || ((rows_alive >> (t * CPL + c)) & 1));
+            zq[c] = u32x4{0u, 0u, 0u, 0u};
+            if (live) zq[c] = *reinterpret_cast<const u32x4*>(zp);
+            zp += zstep;   // chunks are fetched in the order they are stored
+        };
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) fetch(0, c);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    stage[(8 * (e >> 2) + row_l + (e & 3)) * SST + u * 32 + col_l] = acc[t][u][e];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int r = lane / CPR + c * (64 / CPR), cc = (lane % CPR) * 8;
+                const int m = mrow + t * 32 + c * (64 / CPR);
+                float v[8];
+                const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
+                const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
+                v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[2 * i] *= __uint_as_float(zq[c][i] << 16);
+                    v[2 * i + 1] *= __uint_as_float(zq[c][i] & 0xffff0000u);
+                }
+                if (t + 1 < MT) fetch(t + 1, c);
+                if (m < g.M && n < g.N) {
+                    store8(cp, v);
+                    if (g.colsum) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) csum[i] += v[i];
+                    }
+                }
+                cp += cstep;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
 #pragma unroll
@@ -664,10 +718,10 @@ constexpr size_t lds_bytes() {
     return slabs > stage ? slabs : stage;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool DGELU = false>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, A_COL, B_COL>();
-    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, KTAIL>;
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, KTAIL, false, false, DGELU>;
     static int resident = 0;   // per instantiation: workgroups the chip holds at once, a multiple of 8
     if (resident == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -736,12 +790,17 @@ hipError_t launch_grouped_cfg(GemmArgs* g, hipStream_t s) {
     return hipGetLastError();
 }
 
+// C = (A B) * Z and nothing else in the epilogue: the instantiations with the band-ahead fetch of Z
+inline bool dgelu_only(const GemmArgs& g) {
+    return g.act == ACT_DGELU && !g.partial && !g.bias && !g.residual && g.a_cs == 1 && g.b_rs != 1;
+}
+
 // row-segment launch: the 256x256 tile, A row-major, K a multiple of 64
 template <bool B_COL, int REMAP>
 hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
     constexpr int BM = 256, BN = 256, BK = 64, WGM = 2, WGN = 4;
     constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, false, B_COL>();
-    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, false, B_COL, REMAP, false, false, true>;
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, false, B_COL, REMAP, false, false, true, B_COL>;
     static int resident = 0;
     if (resident == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -761,14 +820,20 @@ hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
 }
 
 // K a multiple of 64 (every shape of the model): the slab loads carry no per-chunk k check
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool DGELU = false>
 hipError_t launch_tail(const GemmArgs& g, hipStream_t s) {
-    if (g.K % BK) return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, true>(g, s);
-    return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, false>(g, s);
+    if (g.K % BK) return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, true, DGELU>(g, s);
+    return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, false, DGELU>(g, s);
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 hipError_t launch_remap(const GemmArgs& g, hipStream_t s) {
+    if constexpr (!A_COL && B_COL) {   // the backward's dz has an epilogue of its own (the remapped-k form never occurs)
+        if (dgelu_only(g)) {
+            if (g.remap == REMAP_B_N) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N, true>(g, s);
+            if (g.remap == REMAP_NONE) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE, true>(g, s);
+        }
+    }
     switch (g.remap) {
         case REMAP_B_N: return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N>(g, s);
         case REMAP_B_K: return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_K>(g, s);
@@ -849,13 +914,14 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
     const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
     const int tile = pick_tile(g);
     const bool tail = (g.K % 64) != 0;
-    static char names[4][3][3][2][80];
-    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail];
+    const bool dgelu = !a_col && b_col && dgelu_only(g) && g.remap != REMAP_B_K;
+    static char names[4][3][3][2][2][88];
+    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail][dgelu];
     if (!name[0]) {
         const int bm = tile == 0 ? 128 : (tile == 3 ? 192 : 256), bn = tile == 0 ? 128 : 256;
-        snprintf(name, sizeof(names[0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false, false>", bm, bn,
+        snprintf(name, sizeof(names[0][0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false, false, %s>", bm, bn,
                  tile == 0 ? 2 : 4, a_col ? "true" : "false", b_col ? "true" : "false",
-                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false");
+                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false", dgelu ? "true" : "false");
     }
     return name;
 }
@@ -875,6 +941,7 @@ hipError_t gemm_mfma_seg_prepare(GemmArgs* g) {
     GemmRowSegments& S = g->seg;
     if (!gemm_mfma_supported(*g) || g->partial || g->a_cs != 1 || g->K % 64) return hipErrorNotSupported;
     if (g->residual) return hipErrorNotSupported;   // a row that takes no part is written as zero, not as the residual
+    if (g->b_rs != 1 && !dgelu_only(*g)) return hipErrorNotSupported;   // B with k strided: instantiated for dz only
     const int tiles_m = (g->M + 255) / 256, tiles_n = (g->N + 255) / 256;
     if (S.n < 1 || S.n > kMaxGemmSegments || S.slice < 64 || S.slice % 64 || tiles_m > kMaxSegTileRows || tiles_n > 16 ||
         (g->N + S.slice - 1) / S.slice > 64 || S.end[S.n - 1] != g->M)

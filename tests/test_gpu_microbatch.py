@@ -125,7 +125,9 @@ def segment_launches(fn):
         recs = P.d2ft_timing_read(256)
     finally:
         P.d2ft_timing_enable(False)
-    return sum(r["launches"] for r in recs if r["name"].endswith("false, true>"))
+    # the kernel's template arguments end with (grouped, row segments, dz epilogue)
+    return sum(r["launches"] for r in recs
+               if r["name"].startswith("gemm_mfma_kernel<") and r["name"].rstrip(">").split(", ")[-2] == "true")
 
 
 def test_bf16_gated_segments_slices_across_tiles_and_ends_inside_tiles():
