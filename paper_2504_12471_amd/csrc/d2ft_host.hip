@@ -356,8 +356,8 @@ hipError_t run_gemm_segments(GemmArgs g, const d2ft_block_desc* d, const MicroMa
     if (gemm_mfma_seg_prepare(&g) != hipSuccess) return hipErrorNotSupported;
     if (colsum_bands) *colsum_bands = 2 * ((g.M + 255) / 256);
     timing_begin(s, "gemm");
-    g_timing.label = g.b_rs != 1 ? "gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 1, false, false, true, true>"
-                                 : "gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 1, false, false, true, false>";
+    g_timing.label = g.b_rs != 1 ? "gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 1, false, false, true, 1>"
+                                 : "gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 1, false, false, true, 0>";
     g_timing.flops = 2.0 * cols * g.K;
     const hipError_t e = launch_gemm_mfma_seg(g, s);
     timing_end(s);
@@ -505,7 +505,7 @@ d2ft_status weight_grad_flush(WeightGradBatch* b, const d2ft_block_desc* d, cons
     hipError_t e = hipErrorNotSupported;
     if (gemm_grouped_slots(g) * 65536 <= part_floats) {
         timing_begin(st, "gemm");
-        g_timing.label = "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 0, false, true, false, false>";
+        g_timing.label = "gemm_mfma_kernel<256, 256, 64, 2, 4, true, true, 0, false, true, false, 0>";
         for (int i = 0; i < g.n_groups; ++i) g_timing.flops += 2.0 * g.grp[i].M * g.grp[i].N * s.M;
         e = launch_gemm_grouped(&g, st);
         timing_end(st);

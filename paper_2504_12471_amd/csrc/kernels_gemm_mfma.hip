@@ -232,8 +232,12 @@ __device__ __forceinline__ void tile_of_block(int pid, int total, int tiles_m, i
     tn = in_group / gsize;
 }
 
+// epilogues with an instantiation of their own: C = (A B) * Z (the backward's dz) and C = A B + bias + R (the
+// products that close a residual branch); both fetch their operand a band ahead
+enum { EPI_ANY = 0, EPI_DGELU = 1, EPI_RESIDUAL = 2 };
+
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool GROUPED = false,
-          bool SEGMENTS = false, bool DGELU = false>
+          bool SEGMENTS = false, int EPI = EPI_ANY>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
@@ -526,16 +530,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     float csum[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) csum[i] = 0.f;
-    // DGELU: C = (A B) * Z with nothing else in the epilogue (the backward's dz), as an instantiation of its own.
-    // The saved derivative is fetched a band ahead - each chunk's registers are refilled for the next band as soon
-    // as the chunk is stored - instead of one dependent load per chunk.
-    if constexpr (DGELU) {
+    // EPI_DGELU: C = (A B) * Z with nothing else in the epilogue; EPI_RESIDUAL: C = A B + bias + R.  The operand
+    // (Z or R) is fetched a band ahead - each chunk's registers are refilled for the next band as soon as the
+    // chunk is stored - instead of one dependent load per chunk.
+    if constexpr (EPI != EPI_ANY) {
         static_assert(!GROUPED && !A_COL, "a plain product with A row-major");
         const int mrow = em0 + wm * WTM + lane / CPR;           // the lane's row of chunk 0 in band 0
         const int n = en0 + wn * WTN + (lane % CPR) * 8;        // its columns in every chunk
-        const bf16* zp = Z + (long)mrow * g.ldz + n;
+        const long ldop = EPI == EPI_DGELU ? g.ldz : g.ldr;
+        const bf16* zp = (EPI == EPI_DGELU ? Z : static_cast<const bf16*>(g.residual)) + (long)mrow * ldop + n;
         bf16* cp = C + (long)mrow * g.ldc + n;
-        const long zstep = (long)(64 / CPR) * g.ldz, cstep = (long)(64 / CPR) * g.ldc;   // rows between chunks
+        const long zstep = (long)(64 / CPR) * ldop, cstep = (long)(64 / CPR) * g.ldc;   // rows between chunks
         u32x4 zq[CPL];
         auto fetch = [&](int t, int c) {   // zeros for a row outside the problem or outside its segment's slices
             const int m = mrow + t * 32 + c * (64 / CPR);
@@ -564,8 +569,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                 v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    v[2 * i] *= __uint_as_float(zq[c][i] << 16);
-                    v[2 * i + 1] *= __uint_as_float(zq[c][i] & 0xffff0000u);
+                    if constexpr (EPI == EPI_DGELU) {
+                        v[2 * i] *= __uint_as_float(zq[c][i] << 16);
+                        v[2 * i + 1] *= __uint_as_float(zq[c][i] & 0xffff0000u);
+                    } else {   // braw is zero without a bias
+                        v[2 * i] += __uint_as_float(braw[i] << 16);
+                        v[2 * i + 1] += __uint_as_float(braw[i] & 0xffff0000u);
+                        v[2 * i] += __uint_as_float(zq[c][i] << 16);
+                        v[2 * i + 1] += __uint_as_float(zq[c][i] & 0xffff0000u);
+                    }
                 }
                 if (t + 1 < MT) fetch(t + 1, c);
                 if (m < g.M && n < g.N) {
@@ -718,10 +730,10 @@ constexpr size_t lds_bytes() {
     return slabs > stage ? slabs : stage;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, bool DGELU = false>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool KTAIL, int EPI = EPI_ANY>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, A_COL, B_COL>();
-    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, KTAIL, false, false, DGELU>;
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, KTAIL, false, false, EPI>;
     static int resident = 0;   // per instantiation: workgroups the chip holds at once, a multiple of 8
     if (resident == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -795,12 +807,17 @@ inline bool dgelu_only(const GemmArgs& g) {
     return g.act == ACT_DGELU && !g.partial && !g.bias && !g.residual && g.a_cs == 1 && g.b_rs != 1;
 }
 
+// C = A B + bias + R: likewise
+inline bool residual_only(const GemmArgs& g) {
+    return g.act == ACT_NONE && !g.partial && g.residual && g.a_cs == 1 && g.b_rs == 1;
+}
+
 // row-segment launch: the 256x256 tile, A row-major, K a multiple of 64
 template <bool B_COL, int REMAP>
 hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
     constexpr int BM = 256, BN = 256, BK = 64, WGM = 2, WGN = 4;
     constexpr size_t lds = lds_bytes<BM, BN, BK, WGM, WGN, false, B_COL>();
-    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, false, B_COL, REMAP, false, false, true, B_COL>;
+    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, false, B_COL, REMAP, false, false, true, B_COL ? EPI_DGELU : EPI_ANY>;
     static int resident = 0;
     if (resident == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -820,18 +837,24 @@ hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
 }
 
 // K a multiple of 64 (every shape of the model): the slab loads carry no per-chunk k check
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, bool DGELU = false>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int REMAP, int EPI = EPI_ANY>
 hipError_t launch_tail(const GemmArgs& g, hipStream_t s) {
-    if (g.K % BK) return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, true, DGELU>(g, s);
-    return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, false, DGELU>(g, s);
+    if (g.K % BK) return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, true, EPI>(g, s);
+    return launch_cfg<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP, false, EPI>(g, s);
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 hipError_t launch_remap(const GemmArgs& g, hipStream_t s) {
     if constexpr (!A_COL && B_COL) {   // the backward's dz has an epilogue of its own (the remapped-k form never occurs)
         if (dgelu_only(g)) {
-            if (g.remap == REMAP_B_N) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N, true>(g, s);
-            if (g.remap == REMAP_NONE) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE, true>(g, s);
+            if (g.remap == REMAP_B_N) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_N, EPI_DGELU>(g, s);
+            if (g.remap == REMAP_NONE) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE, EPI_DGELU>(g, s);
+        }
+    }
+    if constexpr (!A_COL && !B_COL) {   // the forward products that close a residual branch (never with remapped columns)
+        if (residual_only(g)) {
+            if (g.remap == REMAP_B_K) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_B_K, EPI_RESIDUAL>(g, s);
+            if (g.remap == REMAP_NONE) return launch_tail<BM, BN, BK, WGM, WGN, A_COL, B_COL, REMAP_NONE, EPI_RESIDUAL>(g, s);
         }
     }
     switch (g.remap) {
@@ -914,14 +937,15 @@ const char* gemm_mfma_config_name(const GemmArgs& g) {
     const bool a_col = (g.a_cs != 1), b_col = (g.b_rs != 1);
     const int tile = pick_tile(g);
     const bool tail = (g.K % 64) != 0;
-    const bool dgelu = !a_col && b_col && dgelu_only(g) && g.remap != REMAP_B_K;
-    static char names[4][3][3][2][2][88];
-    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail][dgelu];
+    const int epi = (!a_col && b_col && dgelu_only(g) && g.remap != REMAP_B_K) ? EPI_DGELU
+                    : (!a_col && !b_col && residual_only(g) && g.remap != REMAP_B_N) ? EPI_RESIDUAL : EPI_ANY;
+    static char names[4][3][3][2][3][88];
+    char* name = names[tile][a_col ? 2 : (b_col ? 1 : 0)][g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0)][tail][epi];
     if (!name[0]) {
         const int bm = tile == 0 ? 128 : (tile == 3 ? 192 : 256), bn = tile == 0 ? 128 : 256;
-        snprintf(name, sizeof(names[0][0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false, false, %s>", bm, bn,
+        snprintf(name, sizeof(names[0][0][0][0][0]), "gemm_mfma_kernel<%d, %d, 64, 2, %d, %s, %s, %d, %s, false, false, %d>", bm, bn,
                  tile == 0 ? 2 : 4, a_col ? "true" : "false", b_col ? "true" : "false",
-                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false", dgelu ? "true" : "false");
+                 g.remap == REMAP_B_N ? 1 : (g.remap == REMAP_B_K ? 2 : 0), tail ? "true" : "false", epi);
     }
     return name;
 }
