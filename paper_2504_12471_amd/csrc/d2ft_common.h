@@ -158,15 +158,15 @@ hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
-// Grouped weight-gradient launch (bf16 MFMA only).  The caller fills K, partial, n_groups and grp[].{A, B, lda,
-// ldb, M, N}; the launcher fills the tile bookkeeping and returns it in *g for the reduction.  partial must hold
-// gemm_grouped_slots(g) tiles of 256 x 256 floats.  hipErrorNotSupported if an operand does not fit the kernel.
 // The forms with A row-major (C = A B, no split-K, no residual) over row segments: prepare takes g->seg.n, slice,
 // end and pos and fills the rest of g->seg, or returns hipErrorNotSupported if the shape does not fit (more than
 // 64 tile rows or 16 tile columns of 256, K not a multiple of 64, operands the matrix-core path does not take);
 // the launch takes a prepared g.
 hipError_t gemm_mfma_seg_prepare(GemmArgs* g);
 hipError_t launch_gemm_mfma_seg(const GemmArgs& g, hipStream_t s);
+// Grouped weight-gradient launch (bf16 MFMA only).  The caller fills K, partial, n_groups and grp[].{A, B, lda,
+// ldb, M, N}; the launcher fills the tile bookkeeping and returns it in *g for the reduction.  partial must hold
+// gemm_grouped_slots(g) tiles of 256 x 256 floats.  hipErrorNotSupported if an operand does not fit the kernel.
 size_t gemm_grouped_slots(const GemmArgs& g);
 hipError_t launch_gemm_grouped(GemmArgs* g, hipStream_t s);
 // out_g[r'][c'] (=|+=) sum over the slots of each tile, (r', c') through the group's remap
