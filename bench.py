@@ -143,6 +143,9 @@ def main() -> int:
                     help="split the batch into this many micro-batches, each with its own op codes (0: one code per head)")
     ap.add_argument("--no-sub-records", action="store_true",
                     help="skip the extra workloads timed beside the headline one (skip40 mask, gated FFN, 5 micro-batches)")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="every launch on the caller's stream (D2FT_FLAG_ONE_STREAM): for kernel traces in which each "
+                         "kernel runs alone; the default lets the backward's weight-gradient work run on a second stream")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -172,7 +175,7 @@ def main() -> int:
     full_ops = di.all_full_ops(w)
 
     desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype, w.lora_rank, w.lora_scale,
-                       w.ln_eps, w.head_dim, P.FLAG_GATE_FFN if w.gate_ffn else 0)
+                       w.ln_eps, w.head_dim, (P.FLAG_GATE_FFN if w.gate_ffn else 0) | (P.FLAG_ONE_STREAM if args.one_stream else 0))
     dws = [{k: P.to_device(v, w.dtype) for k, v in bw.items()} for bw in s.weights]
     if w.train_base:
         grad_fields = [k for k in P.WEIGHT_FIELDS if not k.startswith("ln")]   # norm layers frozen (Sec. III-A)
@@ -194,7 +197,7 @@ def main() -> int:
     x, dy = P.to_device(s.x, w.dtype), P.to_device(s.dy, w.dtype)
 
     # step time measured the same with 3 and with 100 warm-up steps; the default of 20 is margin
-    def timed(mask, steps, warmup):
+    def timed(mask, steps, warmup, stack=stack):
         for _ in range(warmup):
             stack.step(x, dy, mask)
         torch.cuda.synchronize()
@@ -212,6 +215,14 @@ def main() -> int:
         del src, dst
     ms = timed(ops, args.steps, args.warmup)
     ms_full = None if args.no_all_full else timed(full_ops, args.steps, min(args.warmup, 20))
+    # the same step with every launch on one stream: the launch order the per-kernel figures below are taken in
+    ms_one = None
+    if not args.no_all_full and not args.one_stream and w.dtype == "bf16":
+        desc_one = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype, w.lora_rank, w.lora_scale,
+                               w.ln_eps, w.head_dim, (P.FLAG_GATE_FFN if w.gate_ffn else 0) | P.FLAG_ONE_STREAM)
+        stack_one = P.BlockStack(desc_one, dws, w.dtype, grad_fields, mb_images)
+        ms_one = timed(ops, max(10, args.steps // 2), min(args.warmup, 10), stack_one)
+        del stack_one
 
     # per-kernel durations, measured with HIP events inside the library on the launch stream
     stack.step(x, dy, ops)
@@ -305,6 +316,7 @@ def main() -> int:
         "all_full": None if ms_full is None else {
             "ms_per_step": round(ms_full, 4), "images_per_s": round(w.batch / (ms_full * 1e-3), 1),
             "masked_over_all_full_time": round(ms / ms_full, 4)},
+        "one_stream_ms_per_step": None if ms_one is None else round(ms_one, 4),
         "kernel_ms_per_step_sum": round(total_kernel_ms, 4),
         "roofline": roofline,
         "subnet_scores": scores,

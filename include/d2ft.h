@@ -65,7 +65,15 @@ enum {
      * subnet's slice is trained.  b2 is then added iff at least one subnet is live, and with no
      * live subnet the block is the identity.  Requires mlp_hidden divisible by heads with a
      * quotient that is a multiple of 64; otherwise D2FT_ESHAPE. */
-    D2FT_FLAG_GATE_FFN = 4u
+    D2FT_FLAG_GATE_FFN = 4u,
+    /* d2ft_block_bwd / d2ft_block_bwd_mb (bf16 matrix-core path): launch everything on the caller's stream.
+     * By default those calls put the weight-gradient products, which nothing else in the call waits for, on a
+     * second stream of the library's own (default priority), ordered behind the caller's earlier work and joined
+     * to the caller's stream before the call returns, so that to the caller the call is work on its stream
+     * either way.  The two modes group the weight gradients into launches differently, so their split-K sums
+     * may differ in rounding order; nothing else differs.  The second stream is not used while per-kernel
+     * timing is on (d2ft_timing_enable) or while the caller's stream is being captured. */
+    D2FT_FLAG_ONE_STREAM = 8u
 };
 
 #define D2FT_MAX_HEADS 64

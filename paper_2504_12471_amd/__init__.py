@@ -6,7 +6,7 @@ caller-side loop over blocks.  Importing the package requires the built
 library; there is no CPU or PyTorch fallback.
 """
 from .binding import (  # noqa: F401
-    BF16, F32, FLAG_ACCUM_GRADS, FLAG_GATE_FFN, FLAG_NO_MFMA, OP_FULL, OP_FWD, OP_SKIP, SCORE_FISHER, SCORE_MAGNITUDE,
+    BF16, F32, FLAG_ACCUM_GRADS, FLAG_GATE_FFN, FLAG_NO_MFMA, FLAG_ONE_STREAM, OP_FULL, OP_FWD, OP_SKIP, SCORE_FISHER, SCORE_MAGNITUDE,
     WEIGHT_FIELDS, BlockDesc, D2ftError, EmbedDesc, HeadDesc,
     d2ft_classifier_fwd_bwd, d2ft_embed_saved_bytes, d2ft_embed_scratch_bytes, d2ft_head_scratch_bytes,
     d2ft_patch_embed_bwd, d2ft_patch_embed_fwd,

@@ -26,7 +26,7 @@ _lib = C.CDLL(LIB_PATH)
 OK, EINVAL, ESHAPE, EDEVICE = 0, 1, 2, 3
 OP_FULL, OP_FWD, OP_SKIP = 1, 2, 3
 F32, BF16 = 0, 1
-FLAG_ACCUM_GRADS, FLAG_NO_MFMA, FLAG_GATE_FFN = 1, 2, 4
+FLAG_ACCUM_GRADS, FLAG_NO_MFMA, FLAG_GATE_FFN, FLAG_ONE_STREAM = 1, 2, 4, 8
 MAX_HEADS = 64
 
 WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",

@@ -495,11 +495,50 @@ d2ft_status weight_grad_queue(WeightGradBatch* b, const d2ft_block_desc* d, cons
     return D2FT_OK;
 }
 
+// A second stream of the library's own, per device, with the two events that order it against the caller's
+// stream.  A backward call puts the weight-gradient launches with their reductions on it - nothing else in the
+// call waits for them - so that they run beside the chain of launches that leads to dx, most of which leave CUs
+// idle (GEMMs of fewer tiles than CUs, partial last rounds, the attention backward).  Default priority; every
+// call ends joined, so that to the caller the whole call is work on its own stream.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool failed = false;
+};
+SideStream* side_stream() {
+    static SideStream per_device[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    SideStream& S = per_device[dev];
+    if (S.failed) return nullptr;
+    if (!S.stream) {
+        if (hipStreamCreateWithFlags(&S.stream, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&S.fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&S.join, hipEventDisableTiming) != hipSuccess) {
+            S.failed = true;
+            S.stream = nullptr;
+            return nullptr;
+        }
+    }
+    return &S;
+}
+// work launched on S->stream from here on starts after what `st` holds now
+bool side_fork(SideStream* S, hipStream_t st) {
+    return hipEventRecord(S->fork, st) == hipSuccess && hipStreamWaitEvent(S->stream, S->fork, 0) == hipSuccess;
+}
+
+// part_used: if given, the floats at the start of `part` that earlier flushes of the same call own (their
+// launches may still be running on the other stream); this flush takes the next ones
 d2ft_status weight_grad_flush(WeightGradBatch* b, const d2ft_block_desc* d, const Dims& s, float* part, size_t part_floats,
-                              hipStream_t st) {
+                              hipStream_t st, size_t* part_used = nullptr) {
     if (b->g.n_groups == 0) return D2FT_OK;
     GemmArgs& g = b->g;
     g.K = (int)s.M;
+    if (part_used) {
+        part += *part_used;
+        part_floats -= *part_used;
+        *part_used += gemm_grouped_slots(g) * 65536;
+    }
     g.partial = part;
     const int accum = (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
     hipError_t e = hipErrorNotSupported;
@@ -819,24 +858,51 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     // are projected from it once the batch has run
     bool lora_queued = false;
     HeadList lora_heads; lora_heads.n = 0;
-    auto flush_wgrads = [&]() -> d2ft_status {
-        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st);
+    // Side stream (see SideStream): for the whole-block matrix-core path, unless the caller asks for one stream,
+    // per-kernel timing is on (its durations are those of kernels running alone) or the stream is being captured.
+    SideStream* side = nullptr;
+    if (half == PART_BOTH && wgrads.enabled && !(desc->flags & D2FT_FLAG_ONE_STREAM) && !g_timing.on) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) side = side_stream();
+    }
+    bool side_used = false;   // a join is due at the call's end
+    hipStream_t const st_main = st;
+    hipStream_t const st_side = side ? side->stream : st;
+    size_t part_used = 0;   // floats of `part` owned by weight-gradient launches that may still be running
+    // the weight gradients collected so far (and what follows from them) on stream `st`
+    auto flush_wgrads = [&](hipStream_t st) -> d2ft_status {
+        float* const mine = part + part_used;
+        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st, &part_used);
         if (rw != D2FT_OK) return rw;
         if (lora_queued) {
             lora_queued = false;
             const long elems = (long)lora_heads.n * 192 * s.D;
-            const float* G = wgrads.f32_splits > 0 ? part : (const float*)(ws + WL.lora_g);
+            const float* G = wgrads.f32_splits > 0 ? mine : (const float*)(ws + WL.lora_g);
             D2FT_TRY(launch_lora_project(s.dtype, G, wgrads.f32_splits > 0 ? wgrads.f32_splits : 1, elems, w->lora_a_q,
                                          w->lora_a_v, w->lora_b_q, w->lora_b_v, grads->lora_a_q, grads->lora_a_v,
                                          grads->lora_b_q, grads->lora_b_v, lora_heads, s.H, s.D, s.r, desc->lora_scale, accum, st));
         }
         return D2FT_OK;
     };
-    // the call's last launches: the collected weight gradients, then the bias reductions
+    // hand the weight gradients collected so far to the side stream, which picks them up behind what the
+    // caller's stream holds now; without a side stream nothing happens here and they wait for the call's end
+    auto hand_over = [&]() -> d2ft_status {
+        if (!side || wgrads.g.n_groups == 0) return D2FT_OK;
+        if (!side_fork(side, st_main)) return D2FT_EDEVICE;
+        side_used = true;
+        return flush_wgrads(st_side);
+    };
+    // the call's last launches: the collected weight gradients, then the bias reductions, then the join
     auto finish = [&](const Remap64& tbl_a, const Remap64& tbl_b) -> d2ft_status {
-        const d2ft_status rw = flush_wgrads();
+        const d2ft_status rw = flush_wgrads(st_main);
         if (rw != D2FT_OK) return rw;
-        return flush_bias_grads(desc, s, &bias_batch, tbl_a, tbl_b, st);
+        if (bias_batch.n > 0) {
+            const d2ft_status rb = flush_bias_grads(desc, s, &bias_batch, tbl_a, tbl_b, st_main);
+            if (rb != D2FT_OK) return rb;
+        }
+        if (side_used && (hipEventRecord(side->join, st_side) != hipSuccess || hipStreamWaitEvent(st_main, side->join, 0) != hipSuccess))
+            return D2FT_EDEVICE;
+        return D2FT_OK;
     };
 
     // ---- feed-forward network: all of it, or (gated) the slices of the p_f heads, a prefix of the compacted layout ----
@@ -902,6 +968,19 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                                    gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, 0, st);
             if (rc != D2FT_OK) return rc;
         }
+        // dW2 and dW1 have their operands (dy, g, dz, v: nothing later in the call writes them).  They go to the
+        // side stream if they are a launch worth its own: measured, from about a quarter of the chip's CUs in
+        // tiles on (the ungated feed-forward widths, or nearly all subnets p_f); below that one launch for all of
+        // the call's weight gradients at its end packs the CUs better than two, and the events cost more than
+        // the overlap brings (gated ViT-B/16 at 7 p_f subnets: +0.09 ms per step with the side stream).
+        if (side) {
+            long tiles = 0;
+            for (int i = 0; i < wgrads.g.n_groups; ++i)
+                tiles += (long)((wgrads.g.grp[i].M + 255) / 256) * ((wgrads.g.grp[i].N + 255) / 256);
+            if (tiles < 64) side = nullptr;   // nothing has been launched on it
+        }
+        rc = hand_over();
+        if (rc != D2FT_OK) return rc;
         if (grads->b1 && b1_bands > 0) {
             queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
         } else if (grads->b1) {
@@ -1021,13 +1100,14 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         for (int j = 0; j < nf; ++j) lora_heads.h[j] = (uint8_t)live[j];
     } else if (want_lora) {   // the same product by a launch of its own
         int splits = 1;
-        rc = weight_grad(desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D, RED_REMAP_ROWS, qkv_tbl,
+        float* const mine = part + part_used;   // behind the partial tiles of launches that may still be running
+        rc = weight_grad(desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, mine, grads->w_qkv, s.D, RED_REMAP_ROWS, qkv_tbl,
                          st, &splits, grads->w_qkv != nullptr);
         if (rc != D2FT_OK) return rc;
         if (want_lora) {
             HeadList fl; fl.n = nf;
             for (int j = 0; j < nf; ++j) fl.h[j] = (uint8_t)live[j];
-            D2FT_TRY(launch_lora_project(s.dtype, part, splits, (long)nf * 192 * s.D, w->lora_a_q, w->lora_a_v, w->lora_b_q,
+            D2FT_TRY(launch_lora_project(s.dtype, mine, splits, (long)nf * 192 * s.D, w->lora_a_q, w->lora_a_v, w->lora_b_q,
                                          w->lora_b_v, grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v,
                                          fl, s.H, s.D, s.r, desc->lora_scale, accum, st));
         }
@@ -1036,6 +1116,14 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         queue_bias_reduce(&bias_batch, bqkv_part, s.B, nf * 192, grads->b_qkv, 1);   // table a
     } else if (grads->b_qkv) {
         rc = bias_grad(s, ws + WL.dqkv, ld_dq, nf * 192, colpart + 3 * WL.colpart_stride, grads->b_qkv, 1, &bias_batch, st);   // table a
+        if (rc != D2FT_OK) return rc;
+    }
+    // dWo and dWqkv have their operands: they run beside du and the LayerNorm backward (dx1 is only read from
+    // here on: with a side stream it is never dx itself).  The bias reductions stay on the caller's stream: with
+    // them the two streams end the call at about the same time, and a join that has to wait costs more than
+    // the reductions.
+    if (dx1 != dx) {
+        rc = hand_over();
         if (rc != D2FT_OK) return rc;
     }
     {   // du = dQKV W_eff (rows of the p_f heads)
@@ -1064,7 +1152,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             D2FT_TRY(launch_reduce_partials(s.dtype, pb, chunks, s.D, 1, s.D, grads->ln1_b, s.D, RED_REMAP_NONE, none, accum, st));
     }
     if (dx1 == dx) {   // the rows of dx1 are about to be rewritten in place: its weight gradients go first
-        rc = flush_wgrads();
+        rc = flush_wgrads(st_main);
         if (rc != D2FT_OK) return rc;
     }
     // dx = dx1 + LN1bwd(du)

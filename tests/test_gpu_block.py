@@ -216,3 +216,24 @@ def test_unsupported_shapes_are_rejected_without_a_launch():
         desc = P.make_desc(base["batch"], base["tokens"], base["width"], base["heads"], base["mlp_hidden"], base["dtype"],
                            0, 1.0, 1e-6, base["head_dim"])
         assert P.d2ft_block_saved_bytes(desc) == 0 and P.d2ft_block_scratch_bytes(desc) == 0, kw
+
+
+def test_one_stream_and_second_stream_agree():
+    """The backward's weight-gradient launches run on a second stream of the library by default and on the
+    caller's with D2FT_FLAG_ONE_STREAM: same y and dx bit for bit, gradients to rounding order (the two modes group
+    the weight gradients into launches differently), both against the oracle; the two-stream call is repeated to
+    show that a call does not disturb the next one."""
+    FLAG_ONE_STREAM = 8
+    ops = [FULL, FWD, SKIP, FULL, FULL, FWD]
+    x, wt, dy = draw_block(MID_BF16, 21)
+    one = gpu_block(MID_BF16, wt, ops, x, dy, di.WEIGHT_FIELDS, FLAG_ONE_STREAM)
+    two = gpu_block(MID_BF16, wt, ops, x, dy, di.WEIGHT_FIELDS, 0)
+    again = gpu_block(MID_BF16, wt, ops, x, dy, di.WEIGHT_FIELDS, 0)
+    ref = oracle_block(MID_BF16, wt, ops, x, dy)
+    for got in (one, two):
+        compare_block(MID_BF16, ops, got, ref, TOL["bf16"], di.WEIGHT_FIELDS)
+    assert np.array_equal(one[0], two[0]) and np.array_equal(one[1], two[1])
+    for k, v in two[2].items():
+        if v is not None:
+            assert np.array_equal(v, again[2][k]), k
+            assert rel_inf(v, np.asarray(one[2][k], np.float64)) <= 2.0 ** -7, k
