@@ -969,18 +969,20 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (rc != D2FT_OK) return rc;
         }
         // dW2 and dW1 have their operands (dy, g, dz, v: nothing later in the call writes them).  They go to the
-        // side stream if they are a launch worth its own: measured, from about a quarter of the chip's CUs in
-        // tiles on (the ungated feed-forward widths, or nearly all subnets p_f); below that one launch for all of
-        // the call's weight gradients at its end packs the CUs better than two, and the events cost more than
-        // the overlap brings (gated ViT-B/16 at 7 p_f subnets: +0.09 ms per step with the side stream).
+        // side stream now if they are a launch worth its own: measured, from about a quarter of the chip's CUs in
+        // tiles on (the ungated feed-forward widths, or nearly all subnets p_f).  Below that they wait for the
+        // attention half's and all go over in one launch, which packs the CUs better than two (gated ViT-B/16 at
+        // 7 p_f subnets: two launches +0.09 ms per step against one stream, one launch behind the attention
+        // backward -0.08 ms).
         if (side) {
             long tiles = 0;
             for (int i = 0; i < wgrads.g.n_groups; ++i)
                 tiles += (long)((wgrads.g.grp[i].M + 255) / 256) * ((wgrads.g.grp[i].N + 255) / 256);
-            if (tiles < 64) side = nullptr;   // nothing has been launched on it
+            if (tiles >= 64) {
+                rc = hand_over();
+                if (rc != D2FT_OK) return rc;
+            }
         }
-        rc = hand_over();
-        if (rc != D2FT_OK) return rc;
         if (grads->b1 && b1_bands > 0) {
             queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
         } else if (grads->b1) {
@@ -1122,7 +1124,9 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     // here on: with a side stream it is never dx itself).  The bias reductions stay on the caller's stream: with
     // them the two streams end the call at about the same time, and a join that has to wait costs more than
     // the reductions.
-    if (dx1 != dx) {
+    // With LoRA the product is followed by the projection onto the adapters, too long a tail for the side stream
+    // beside du alone (+0.06 ms per step): those stay on the caller's stream.
+    if (dx1 != dx && !lora_queued) {
         rc = hand_over();
         if (rc != D2FT_OK) return rc;
     }
