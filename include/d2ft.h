@@ -18,9 +18,14 @@
  *   - Plain C types only.  Every tensor pointer is a DEVICE pointer unless the
  *     parameter comment says HOST.  Tensors are row-major and contiguous.
  *   - The caller owns every buffer.  The library allocates no device memory
- *     and keeps no state between calls.
+ *     and keeps no tensor state between calls (per device it keeps launch
+ *     parameters it has looked up, a HIP stream and two events of its own,
+ *     see D2FT_FLAG_ONE_STREAM, and the timing records of d2ft_timing_enable).
  *   - Block calls are asynchronous on the given HIP stream (a hipStream_t
- *     passed as void*; NULL is the default stream).
+ *     passed as void*; NULL is the default stream): when a call returns, all
+ *     of its work is ordered on that stream.
+ *   - Calls on one device from several host threads must be serialised by the
+ *     caller.
  *   - Errors are return codes.  Arguments are validated before anything is
  *     launched, so a call that returns D2FT_EINVAL or D2FT_ESHAPE has had no
  *     effect.  D2FT_EDEVICE reports a HIP error of a launch or copy.
