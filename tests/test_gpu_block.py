@@ -237,3 +237,49 @@ def test_one_stream_and_second_stream_agree():
         if v is not None:
             assert np.array_equal(v, again[2][k]), k
             assert rel_inf(v, np.asarray(one[2][k], np.float64)) <= 2.0 ** -7, k
+
+
+def test_block_calls_captured_in_a_hip_graph():
+    """Forward + backward captured from a stream: the library then keeps every launch on that stream (no second
+    stream, no event of its own in the graph).  Every replay, with eager work and synchronisations in between,
+    must give what the eager calls gave."""
+    import torch
+    import paper_2504_12471_amd as P
+    w, ops = MID_BF16, [FULL, FWD, SKIP, FULL, FULL, FWD]
+    x, wt, dy = draw_block(w, 22)
+    desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype)
+    dw = {k: P.to_device(v, w.dtype) for k, v in wt.items()}
+    xd, dyd = P.to_device(x, w.dtype), P.to_device(dy, w.dtype)
+    y, dx = torch.empty_like(xd), torch.empty_like(xd)
+    saved = torch.empty(P.d2ft_block_saved_bytes(desc), dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(P.d2ft_block_scratch_bytes(desc), dtype=torch.uint8, device="cuda")
+    grads = {k: (None if v is None else torch.zeros_like(v)) for k, v in dw.items()}
+
+    def calls():
+        P.d2ft_block_fwd(desc, dw, ops, xd, y, saved, scratch)
+        P.d2ft_block_bwd(desc, dw, ops, xd, dyd, dx, grads, saved, scratch)
+
+    def poison():
+        y.fill_(float("nan"))
+        dx.fill_(float("nan"))
+        for v in grads.values():
+            if v is not None:
+                v.fill_(float("nan"))
+
+    calls()
+    torch.cuda.synchronize()
+    eager = (y.clone(), dx.clone(), {k: (None if v is None else v.clone()) for k, v in grads.items()})
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls()
+    for _ in range(3):
+        poison()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager[0]) and torch.equal(dx, eager[1])
+        for k, v in grads.items():
+            if v is not None:
+                assert rel_inf(v.float().cpu().numpy(), eager[2][k].double().cpu().numpy()) <= 2.0 ** -7, k
+        calls()   # eager work between the replays
+        torch.cuda.synchronize()
