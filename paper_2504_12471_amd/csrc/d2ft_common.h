@@ -145,6 +145,7 @@ struct GemmArgs {
     // problem is cut into `splits` runs of units_per_wg K slabs; unit u = split * total_tiles + tile leaves its
     // fp32 sums in slot u of `partial` ([slots][256][256]); reduce_grouped adds a tile's slots in split order.
     int n_groups, units_per_wg, slabs_per_tile, total_tiles;
+    int max_units;        // grouped mode, in: if > 0, no more (tile, split) units than this unless one split exceeds it
     GemmGroup grp[kMaxGemmGroups];
     float* colsum;        // non-null (MFMA path only): column sums of C's values over bands of rows, fp32
                           // [bands][N]; band = colsum_row0 + 2 * (row tile) + (upper / lower half of the tile)

@@ -530,10 +530,11 @@ bool side_fork(SideStream* S, hipStream_t st) {
 // part_used: if given, the floats at the start of `part` that earlier flushes of the same call own (their
 // launches may still be running on the other stream); this flush takes the next ones
 d2ft_status weight_grad_flush(WeightGradBatch* b, const d2ft_block_desc* d, const Dims& s, float* part, size_t part_floats,
-                              hipStream_t st, size_t* part_used = nullptr) {
+                              hipStream_t st, size_t* part_used = nullptr, int max_units = 0) {
     if (b->g.n_groups == 0) return D2FT_OK;
     GemmArgs& g = b->g;
     g.K = (int)s.M;
+    g.max_units = max_units;
     if (part_used) {
         part += *part_used;
         part_floats -= *part_used;
@@ -870,9 +871,9 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     hipStream_t const st_side = side ? side->stream : st;
     size_t part_used = 0;   // floats of `part` owned by weight-gradient launches that may still be running
     // the weight gradients collected so far (and what follows from them) on stream `st`
-    auto flush_wgrads = [&](hipStream_t st) -> d2ft_status {
+    auto flush_wgrads = [&](hipStream_t st, int max_units = 0) -> d2ft_status {
         float* const mine = part + part_used;
-        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st, &part_used);
+        const d2ft_status rw = weight_grad_flush(&wgrads, desc, s, part, WL.part_floats, st, &part_used, max_units);
         if (rw != D2FT_OK) return rw;
         if (lora_queued) {
             lora_queued = false;
@@ -886,11 +887,11 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     };
     // hand the weight gradients collected so far to the side stream, which picks them up behind what the
     // caller's stream holds now; without a side stream nothing happens here and they wait for the call's end
-    auto hand_over = [&]() -> d2ft_status {
+    auto hand_over = [&](int max_units) -> d2ft_status {
         if (!side || wgrads.g.n_groups == 0) return D2FT_OK;
         if (!side_fork(side, st_main)) return D2FT_EDEVICE;
         side_used = true;
-        return flush_wgrads(st_side);
+        return flush_wgrads(st_side, max_units);
     };
     // the call's last launches: the collected weight gradients, then the bias reductions, then the join
     auto finish = [&](const Remap64& tbl_a, const Remap64& tbl_b) -> d2ft_status {
@@ -979,7 +980,10 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             for (int i = 0; i < wgrads.g.n_groups; ++i)
                 tiles += (long)((wgrads.g.grp[i].M + 255) / 256) * ((wgrads.g.grp[i].N + 255) / 256);
             if (tiles >= 64) {
-                rc = hand_over();
+                // It has a long stretch of the caller's stream beside it and should leave that stream CUs: at
+                // most 160 workgroups (vit_b16, 72 tiles: 2 runs of K per tile 8.41 ms per step, the 3 runs the
+                // launch would pick for itself 8.56, 1 run 9.10).
+                rc = hand_over(160);
                 if (rc != D2FT_OK) return rc;
             }
         }
@@ -1127,7 +1131,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     // With LoRA the product is followed by the projection onto the adapters, too long a tail for the side stream
     // beside du alone (+0.06 ms per step): those stay on the caller's stream.
     if (dx1 != dx && !lora_queued) {
-        rc = hand_over();
+        rc = hand_over(0);   // little is left beside it: as fast as it can
         if (rc != D2FT_OK) return rc;
     }
     {   // du = dQKV W_eff (rows of the p_f heads)

@@ -790,6 +790,7 @@ hipError_t launch_grouped_cfg(GemmArgs* g, hipStream_t s) {
     double best_cost = 1e30;
     for (int sp = 1; sp <= kGroupedMaxSplits && sp <= S; ++sp) {
         const long units = (long)tile * sp;
+        if (sp > 1 && g->max_units > 0 && units > g->max_units) break;   // the caller wants CUs left over
         const long rounds = (units + resident - 1) / resident;
         const double cost = rounds * ((S + sp - 1) / sp + 8.0) + 0.04 * units;
         if (cost < best_cost) { best_cost = cost; best = sp; }
