@@ -969,21 +969,18 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                                    gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, 0, st);
             if (rc != D2FT_OK) return rc;
         }
-        // dW2 and dW1 have their operands (dy, g, dz, v: nothing later in the call writes them).  They go to the
-        // side stream now if they are a launch worth its own: measured, from about a quarter of the chip's CUs in
-        // tiles on (the ungated feed-forward widths, or nearly all subnets p_f).  Below that they wait for the
-        // attention half's and all go over in one launch, which packs the CUs better than two (gated ViT-B/16 at
-        // 7 p_f subnets: two launches +0.09 ms per step against one stream, one launch behind the attention
-        // backward -0.08 ms).
+        // dW2 and dW1 have their operands (dy, g, dz, v: nothing later in the call writes them).  From 24 tiles on
+        // they go to the side stream now.  They have a long stretch of the caller's stream beside them and should
+        // leave that stream CUs: the launch is held to 128 workgroups, or to two runs of K per tile if that is
+        // more.  Measured per step: vit_b16 (72 tiles) 2 runs 8.41 ms, the 3 runs the launch would pick alone 8.56,
+        // 1 run 9.10; gated at 7 p_f subnets (42 tiles) 3 runs 7.18 ms, the 6 runs it would pick alone 7.39, 2 runs
+        // 7.26, everything in one launch behind the attention backward 7.30.
         if (side) {
             long tiles = 0;
             for (int i = 0; i < wgrads.g.n_groups; ++i)
                 tiles += (long)((wgrads.g.grp[i].M + 255) / 256) * ((wgrads.g.grp[i].N + 255) / 256);
-            if (tiles >= 64) {
-                // It has a long stretch of the caller's stream beside it and should leave that stream CUs: at
-                // most 160 workgroups (vit_b16, 72 tiles: 2 runs of K per tile 8.41 ms per step, the 3 runs the
-                // launch would pick for itself 8.56, 1 run 9.10).
-                rc = hand_over(160);
+            if (tiles >= 24) {
+                rc = hand_over((int)(2 * tiles > 128 ? 2 * tiles : 128));
                 if (rc != D2FT_OK) return rc;
             }
         }
