@@ -298,7 +298,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     };
     auto setup_tile = [&](int pid) {
         int tile_m, tile_n;
-        if (SEGMENTS && total == tiles_m * tiles_n) {
+        if (SEGMENTS && total == tiles_m * tiles_n) {   // every tile has work: the plain order
             tile_of_block(pid, total, tiles_m, tiles_n, tile_m, tile_n, split);
         } else if constexpr (SEGMENTS) {
             // the pid-th tile with work, counted row by row (ids with equal id mod 8 get a contiguous range)
