@@ -23,7 +23,8 @@
  *     see D2FT_FLAG_ONE_STREAM, and the timing records of d2ft_timing_enable).
  *   - Block calls are asynchronous on the given HIP stream (a hipStream_t
  *     passed as void*; NULL is the default stream): when a call returns, all
- *     of its work is ordered on that stream.
+ *     of its work is ordered on that stream (unless the caller opts out with
+ *     D2FT_FLAG_DEFER_JOIN).
  *   - Calls on one device from several host threads must be serialised by the
  *     caller.
  *   - Errors are return codes.  Arguments are validated before anything is
@@ -78,7 +79,16 @@ enum {
      * either way.  The two modes group the weight gradients into launches differently, so their split-K sums
      * may differ in rounding order; nothing else differs.  The second stream is not used while per-kernel
      * timing is on (d2ft_timing_enable) or while the caller's stream is being captured. */
-    D2FT_FLAG_ONE_STREAM = 8u
+    D2FT_FLAG_ONE_STREAM = 8u,
+    /* d2ft_block_bwd / d2ft_block_bwd_mb, for a caller's loop over blocks: return without making the caller's
+     * stream wait for the work the call left on the library's second stream (weight gradients of this call).
+     * That work is then ordered on the caller's stream by the next call into the library on this device
+     * (any entry point that launches work waits for it first; a following backward call of the same shape with
+     * this flag waits only where it has to, which is what makes the flag worth setting) or by d2ft_join().
+     * Until then the caller must not read this call's weight gradients, and must not write, free or reuse
+     * any buffer passed to this call, from its own code on any stream.  dx is complete on the caller's stream
+     * as always. */
+    D2FT_FLAG_DEFER_JOIN = 16u
 };
 
 #define D2FT_MAX_HEADS 64
@@ -183,6 +193,10 @@ d2ft_status d2ft_block_bwd(const d2ft_block_desc *desc, const d2ft_block_weights
                            const uint8_t *ops, const void *x, const void *dy, void *dx,
                            const d2ft_block_grads *grads, const void *saved, void *scratch,
                            void *hip_stream);
+
+/* Makes hip_stream wait for whatever an earlier call with D2FT_FLAG_DEFER_JOIN left running on the library's
+ * second stream on the current device; a no-op if there is nothing.  D2FT_EDEVICE if the wait cannot be queued. */
+d2ft_status d2ft_join(void *hip_stream);
 
 /* One block over several micro-batches, each with its own op codes: the scheduling table of
  * Alg. 1 holds one code per (subnet, micro-batch), T_opt[k][x_i], and Sec. IV-A splits a batch into

@@ -26,7 +26,7 @@ _lib = C.CDLL(LIB_PATH)
 OK, EINVAL, ESHAPE, EDEVICE = 0, 1, 2, 3
 OP_FULL, OP_FWD, OP_SKIP = 1, 2, 3
 F32, BF16 = 0, 1
-FLAG_ACCUM_GRADS, FLAG_NO_MFMA, FLAG_GATE_FFN, FLAG_ONE_STREAM = 1, 2, 4, 8
+FLAG_ACCUM_GRADS, FLAG_NO_MFMA, FLAG_GATE_FFN, FLAG_ONE_STREAM, FLAG_DEFER_JOIN = 1, 2, 4, 8, 16
 MAX_HEADS = 64
 
 WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",
@@ -109,6 +109,14 @@ _lib.d2ft_timing_enable.restype = C.c_int
 _lib.d2ft_timing_enable.argtypes = [C.c_int32]
 _lib.d2ft_timing_read.restype = C.c_int32
 _lib.d2ft_timing_read.argtypes = [C.POINTER(KernelTime), C.c_int32]
+
+
+_lib.d2ft_join.restype = C.c_int
+_lib.d2ft_join.argtypes = [C.c_void_p]
+
+
+def d2ft_join(stream: Optional["torch.cuda.Stream"] = None) -> None:
+    _check(_lib.d2ft_join(_stream_ptr(stream)), "d2ft_join")
 
 
 def d2ft_timing_enable(on: bool) -> None:
@@ -384,4 +392,4 @@ def exported_symbols():
             "d2ft_select_knapsack_static",
             "d2ft_scores_workspace_bytes", "d2ft_subnet_scores", "d2ft_sgd_step", "d2ft_embed_saved_bytes",
             "d2ft_embed_scratch_bytes", "d2ft_patch_embed_fwd", "d2ft_patch_embed_bwd", "d2ft_head_scratch_bytes",
-            "d2ft_classifier_fwd_bwd", "d2ft_timing_enable", "d2ft_timing_read"]
+            "d2ft_classifier_fwd_bwd", "d2ft_timing_enable", "d2ft_timing_read", "d2ft_join"]

@@ -502,25 +502,41 @@ d2ft_status weight_grad_queue(WeightGradBatch* b, const d2ft_block_desc* d, cons
 // call ends joined, so that to the caller the whole call is work on its own stream.
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, early = nullptr;
     bool failed = false;
+    // D2FT_FLAG_DEFER_JOIN: a call has returned with work still on the stream (`join` marks its end).
+    // pending_early: its feed-forward weight gradients went over on their own and `early` marks their end;
+    // pending_dims: the call's shape, i.e. its scratch layout.
+    bool pending = false, pending_early = false;
+    Dims pending_dims;
 };
-SideStream* side_stream() {
+// the current device's side stream; create = false: only if it exists already
+SideStream* side_stream(bool create = true) {
     static SideStream per_device[16];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
     SideStream& S = per_device[dev];
     if (S.failed) return nullptr;
     if (!S.stream) {
+        if (!create) return nullptr;
         if (hipStreamCreateWithFlags(&S.stream, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&S.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&S.join, hipEventDisableTiming) != hipSuccess) {
+            hipEventCreateWithFlags(&S.join, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&S.early, hipEventDisableTiming) != hipSuccess) {
             S.failed = true;
             S.stream = nullptr;
             return nullptr;
         }
     }
     return &S;
+}
+// Orders st behind whatever an earlier call with D2FT_FLAG_DEFER_JOIN left running on the side stream.  Every
+// entry point that launches work starts with it (the backward takes a cheaper route of its own when it can).
+d2ft_status join_pending(hipStream_t st) {
+    SideStream* S = side_stream(false);
+    if (!S || !S->pending) return D2FT_OK;
+    S->pending = false;
+    return hipStreamWaitEvent(st, S->join, 0) == hipSuccess ? D2FT_OK : D2FT_EDEVICE;
 }
 // work launched on S->stream from here on starts after what `st` holds now
 bool side_fork(SideStream* S, hipStream_t st) {
@@ -654,6 +670,8 @@ int32_t d2ft_timing_read(d2ft_kernel_time* out, int32_t max_entries) {
     return n;
 }
 
+d2ft_status d2ft_join(void* hip_stream) { return join_pending(static_cast<hipStream_t>(hip_stream)); }
+
 const char* d2ft_status_string(d2ft_status status) {
     switch (status) {
         case D2FT_OK: return "ok";
@@ -704,6 +722,8 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                                   const MicroMask* mask = nullptr) {
     int32_t live[D2FT_MAX_HEADS], nf = 0, nl = 0;
     d2ft_status cs = compact(ops, desc->heads, live, &nf, &nl);
+    if (cs != D2FT_OK) return cs;
+    cs = join_pending(st);   // an earlier backward call may still read the buffers this call writes
     if (cs != D2FT_OK) return cs;
 
     const Dims s = dims_of(desc);
@@ -867,6 +887,30 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) side = side_stream();
     }
     bool side_used = false;   // a join is due at the call's end
+    // An earlier call that deferred its join.  If this call has the same shape (hence the same scratch layout),
+    // defers too and the earlier call's feed-forward gradients went over on their own, only two things of that
+    // call can still be running: those gradients, which read dz, and the attention half's, which read dx1 and
+    // dQKV.  This call then waits for the first before it writes dz and for the second before it writes dx1
+    // (join_late), by when both have long ended; otherwise it waits for everything now.
+    bool join_late = false;
+    if (SideStream* P = side_stream(false); P && P->pending) {
+        const Dims& q = P->pending_dims;
+        const bool same = q.B == s.B && q.T == s.T && q.D == s.D && q.H == s.H && q.Dm == s.Dm && q.r == s.r && q.dtype == s.dtype;
+        if (side && same && P->pending_early && (desc->flags & D2FT_FLAG_DEFER_JOIN)) {
+            P->pending = false;
+            if (hipStreamWaitEvent(st, P->early, 0) != hipSuccess) return D2FT_EDEVICE;
+            join_late = true;
+        } else {
+            const d2ft_status rj = join_pending(st);
+            if (rj != D2FT_OK) return rj;
+        }
+    }
+    auto late_join = [&]() -> d2ft_status {   // before the first write to what the earlier call's last launch reads
+        if (!join_late) return D2FT_OK;
+        join_late = false;
+        return hipStreamWaitEvent(st, side->join, 0) == hipSuccess ? D2FT_OK : D2FT_EDEVICE;
+    };
+    bool early_went = false;   // this call's feed-forward gradients went over on their own
     hipStream_t const st_main = st;
     hipStream_t const st_side = side ? side->stream : st;
     size_t part_used = 0;   // floats of `part` owned by weight-gradient launches that may still be running
@@ -901,8 +945,18 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             const d2ft_status rb = flush_bias_grads(desc, s, &bias_batch, tbl_a, tbl_b, st_main);
             if (rb != D2FT_OK) return rb;
         }
-        if (side_used && (hipEventRecord(side->join, st_side) != hipSuccess || hipStreamWaitEvent(st_main, side->join, 0) != hipSuccess))
-            return D2FT_EDEVICE;
+        const d2ft_status rl = late_join();
+        if (rl != D2FT_OK) return rl;
+        if (side_used) {
+            if (hipEventRecord(side->join, st_side) != hipSuccess) return D2FT_EDEVICE;
+            if (desc->flags & D2FT_FLAG_DEFER_JOIN) {   // the next call on this device, or d2ft_join, waits for it
+                side->pending = true;
+                side->pending_early = early_went;
+                side->pending_dims = s;
+            } else if (hipStreamWaitEvent(st_main, side->join, 0) != hipSuccess) {
+                return D2FT_EDEVICE;
+            }
+        }
         return D2FT_OK;
     };
 
@@ -982,6 +1036,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (tiles >= 24) {
                 rc = hand_over((int)(2 * tiles > 128 ? 2 * tiles : 128));
                 if (rc != D2FT_OK) return rc;
+                if (hipEventRecord(side->early, st_side) != hipSuccess) return D2FT_EDEVICE;
+                early_went = true;
             }
         }
         if (grads->b1 && b1_bands > 0) {
@@ -1013,6 +1069,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         }
         // dx1 = dy + LN2bwd(dv); with no p_f head this already is dx (residual route only)
         void* out = (half == PART_BOTH && nf > 0) ? (void*)(ws + WL.dx1) : dx;
+        rc = late_join();
+        if (rc != D2FT_OK) return rc;
         if (ln2_sums && (want_b2 || want_bo)) {
             float* sum_res = want_b2 ? (float*)(ws + WL.colfuse_b2) : nullptr;
             float* sum_out = want_bo ? (float*)(ws + WL.colfuse_bo) : nullptr;
@@ -1031,6 +1089,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
 
     // ---- attention side ----
     sv = sva;
+    rc = late_join();   // if the feed-forward half did not run
+    if (rc != D2FT_OK) return rc;
     if (want_bo && !ln2_sums) {
         rc = bias_grad(s, dx1, s.D, s.D, colpart + 2 * WL.colpart_stride, grads->b_o, 0, &bias_batch, st);
         if (rc != D2FT_OK) return rc;
@@ -1424,6 +1484,10 @@ d2ft_status d2ft_subnet_scores(const d2ft_block_desc* desc, const d2ft_block_wei
     }
     const ScoreArgs a = score_spans(desc, t);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {   // gradients or buffers an earlier backward call may still be working on
+        const d2ft_status rj = join_pending(st);
+        if (rj != D2FT_OK) return rj;
+    }
     double* partial = static_cast<double*>(workspace);
     double* out = partial + (size_t)desc->heads * score_spans(desc, nullptr).total_chunks;
     if (a.n == 0) {
@@ -1500,6 +1564,10 @@ d2ft_status d2ft_sgd_step(const d2ft_block_desc* desc, const d2ft_block_grads* w
 #undef D2FT_M
     if (bad) return D2FT_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {   // gradients or buffers an earlier backward call may still be working on
+        const d2ft_status rj = join_pending(st);
+        if (rj != D2FT_OK) return rj;
+    }
     D2FT_TRY(launch_sgd(s.dtype, per_head, upd, st));
     D2FT_TRY(launch_sgd(s.dtype, shared, one, st));
     return D2FT_OK;
@@ -1568,6 +1636,10 @@ d2ft_status d2ft_patch_embed_fwd(const d2ft_embed_desc* d, const void* images, c
     if (((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
     const EmbedLayout L = embed_layout(d);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {   // gradients or buffers an earlier backward call may still be working on
+        const d2ft_status rj = join_pending(st);
+        if (rj != D2FT_OK) return rj;
+    }
     char* ws = static_cast<char*>(scratch);
     D2FT_TRY(launch_im2col(d->dtype, images, saved, d->batch, d->channels, d->height, d->width_px, d->patch, st));
     const d2ft_block_desc hd = helper_desc(d->dtype, d->flags);
@@ -1593,6 +1665,10 @@ d2ft_status d2ft_patch_embed_bwd(const d2ft_embed_desc* d, const void* dtokens, 
     if (((uintptr_t)saved & 255) || ((uintptr_t)scratch & 255)) return D2FT_EINVAL;
     const EmbedLayout L = embed_layout(d);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {   // gradients or buffers an earlier backward call may still be working on
+        const d2ft_status rj = join_pending(st);
+        if (rj != D2FT_OK) return rj;
+    }
     char* ws = static_cast<char*>(scratch);
     const int accum = (d->flags & D2FT_FLAG_ACCUM_GRADS) ? 1 : 0;
     D2FT_TRY(launch_embed_bwd_gather(d->dtype, dtokens, ws + L.dproj, g_pos, g_cls, d->batch, L.Np, d->width, accum, st));
@@ -1654,6 +1730,10 @@ d2ft_status d2ft_classifier_fwd_bwd(const d2ft_head_desc* d, const void* tokens,
         if (labels[b] < 0 || labels[b] >= d->classes) return D2FT_EINVAL;
     const HeadLayout L = head_layout(d);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {   // gradients or buffers an earlier backward call may still be working on
+        const d2ft_status rj = join_pending(st);
+        if (rj != D2FT_OK) return rj;
+    }
     char* ws = static_cast<char*>(scratch);
     if (hipMemcpyAsync(ws + L.labels, labels, (size_t)d->batch * 4, hipMemcpyHostToDevice, st) != hipSuccess)
         return D2FT_EDEVICE;

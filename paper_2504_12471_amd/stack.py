@@ -38,6 +38,10 @@ class BlockStack:
         """mb_images: images per micro-batch; when given, ops passed to forward/backward are
         [L][n_micro][heads] and every block call goes through the micro-batch entry points."""
         self.desc = desc
+        # the backward calls of a pass follow each other: each leaves its weight-gradient work to be joined by the
+        # next one, and backward() joins the last
+        self.desc_bwd = B.BlockDesc.from_buffer_copy(desc)
+        self.desc_bwd.flags |= B.FLAG_DEFER_JOIN
         self.mb_images = None if mb_images is None else [int(b) for b in mb_images]
         self.dtype = dtype
         self.weights = weights
@@ -75,12 +79,13 @@ class BlockStack:
         for l in range(self.L - 1, -1, -1):
             out = self.dacts[l & 1]
             if self.mb_images is None:
-                B.d2ft_block_bwd(self.desc, self.weights[l], ops[l], self.acts[l], cur, out, self.grads[l],
+                B.d2ft_block_bwd(self.desc_bwd, self.weights[l], ops[l], self.acts[l], cur, out, self.grads[l],
                                  self.saved[l], self.scratch, stream)
             else:
-                B.d2ft_block_bwd_mb(self.desc, self.weights[l], self.mb_images, ops[l], self.acts[l], cur, out,
+                B.d2ft_block_bwd_mb(self.desc_bwd, self.weights[l], self.mb_images, ops[l], self.acts[l], cur, out,
                                     self.grads[l], self.saved[l], self.scratch, stream)
             cur = out
+        B.d2ft_join(stream)   # the gradients are complete on the stream when this returns
         return cur
 
     def step(self, x: torch.Tensor, dy: torch.Tensor, ops: np.ndarray, stream=None):

@@ -283,3 +283,48 @@ def test_block_calls_captured_in_a_hip_graph():
                 assert rel_inf(v.float().cpu().numpy(), eager[2][k].double().cpu().numpy()) <= 2.0 ** -7, k
         calls()   # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_deferred_join_over_consecutive_backward_calls():
+    """Backward calls of two blocks in a row with D2FT_FLAG_DEFER_JOIN: the second call takes over the wait for the
+    first one's weight gradients, d2ft_join (or the next call into the library) orders the rest on the stream.
+    Against the same calls without the flag, bit for bit (the launches are the same); only the caller's stream is
+    synchronised before the results are read."""
+    import torch
+    import paper_2504_12471_amd as P
+    w = MID_BF16   # 24 feed-forward gradient tiles: they go to the second stream on their own
+    ops = [[FULL, FWD, SKIP, FULL, FULL, FWD], [FULL, FULL, FWD, SKIP, FULL, FULL]]
+    rng = np.random.default_rng(23)
+    x, dy = di.draw_hidden(rng, w), di.draw_hidden(rng, w)
+    wts = [di.draw_block_weights(rng, w) for _ in range(2)]
+    dws = [{k: P.to_device(v, w.dtype) for k, v in wt.items()} for wt in wts]
+    xd, dyd = P.to_device(x, w.dtype), P.to_device(dy, w.dtype)
+
+    def run(flags, finish):
+        desc = P.make_desc(w.batch, w.tokens, w.width, w.heads, w.mlp_hidden, w.dtype, 0, 1.0, w.ln_eps, w.head_dim, flags)
+        saved = [torch.empty(P.d2ft_block_saved_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        scratch = torch.empty(P.d2ft_block_scratch_bytes(desc), dtype=torch.uint8, device="cuda")
+        h = [xd, torch.empty_like(xd), torch.empty_like(xd)]
+        d = [torch.empty_like(xd), torch.empty_like(xd), dyd]
+        grads = [{k: (None if v is None else torch.full_like(v, float("nan"))) for k, v in dw.items()} for dw in dws]
+        for l in range(2):
+            P.d2ft_block_fwd(desc, dws[l], ops[l], h[l], h[l + 1], saved[l], scratch)
+        for l in (1, 0):
+            P.d2ft_block_bwd(desc, dws[l], ops[l], h[l], d[l + 1], d[l], grads[l], saved[l], scratch)
+        finish(desc, h, saved, scratch)
+        torch.cuda.current_stream().synchronize()
+        return d[0].clone(), [{k: (None if v is None else v.clone()) for k, v in g.items()} for g in grads]
+
+    plain = run(0, lambda *a: None)
+    joined = run(P.FLAG_DEFER_JOIN, lambda *a: P.d2ft_join())
+    # no explicit join: the next call into the library (a forward call into spare buffers) waits first
+    spare_y = torch.empty_like(xd)
+    by_next_call = run(P.FLAG_DEFER_JOIN,
+                       lambda desc, h, saved, scratch: P.d2ft_block_fwd(desc, dws[0], ops[0], h[0], spare_y,
+                                                                        torch.empty_like(saved[0]), scratch))
+    for got in (joined, by_next_call):
+        assert torch.equal(got[0], plain[0])
+        for l in range(2):
+            for k, v in plain[1][l].items():
+                if v is not None:
+                    assert torch.equal(got[1][l][k], v), (l, k)
