@@ -87,7 +87,7 @@ SavedLayout saved_layout(const Dims& s) {
 
 // ---- layout of the scratch buffer ----
 struct ScratchLayout {
-    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, dz, dv, dx1, d_o, dqkv, du, delta, lora_g, total;
+    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, colfuse_set, dz, dv, dx1, d_o, dqkv, du, delta, lora_g, total;
     size_t part_floats, colpart_stride;
 };
 ScratchLayout scratch_layout(const Dims& s) {
@@ -115,6 +115,10 @@ ScratchLayout scratch_layout(const Dims& s) {
     L.colfuse_b2 = take((size_t)ln_bwd_sums_bands((int)s.M) * s.D * 4);
     L.colfuse_bo = take((size_t)ln_bwd_sums_bands((int)s.M) * s.D * 4);
     L.colfuse_bqkv = take((size_t)s.B * s.H * 192 * 4);   // per image, from the attention backward
+    // and a second set of the four: consecutive backward calls alternate, so that a call may write its sums
+    // while the reduction of the call before, left on the side stream (D2FT_FLAG_DEFER_JOIN), still reads its own
+    L.colfuse_set = take(0) - L.colfuse_b1;
+    take(L.colfuse_set);
     L.dz = take(s.M * s.Dm * s.es);
     L.dv = take(s.M * s.D * s.es);
     L.dx1 = take(s.M * s.D * s.es);
@@ -509,6 +513,7 @@ struct SideStream {
     // pending_dims: the call's shape, i.e. its scratch layout.
     bool pending = false, pending_early = false;
     Dims pending_dims;
+    int parity = 0;   // which set of fused column-sum regions the last backward call used
 };
 // the current device's side stream; create = false: only if it exists already
 SideStream* side_stream(bool create = true) {
@@ -911,6 +916,12 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         return hipStreamWaitEvent(st, side->join, 0) == hipSuccess ? D2FT_OK : D2FT_EDEVICE;
     };
     bool early_went = false;   // this call's feed-forward gradients went over on their own
+    // the set of fused column-sum regions of this call
+    const size_t cf = (side ? (side->parity ^= 1) : 0) * WL.colfuse_set;
+    // Where the join is deferred the bias reductions go to the side stream with the last weight gradients (the
+    // caller's stream then ends the call with LayerNorm 1's backward); where the call ends joined they stay on
+    // the caller's stream, which would otherwise wait for them.
+    const bool bias_on_side = side && (desc->flags & D2FT_FLAG_DEFER_JOIN);
     hipStream_t const st_main = st;
     hipStream_t const st_side = side ? side->stream : st;
     size_t part_used = 0;   // floats of `part` owned by weight-gradient launches that may still be running
@@ -1010,7 +1021,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             g.M = M; g.N = n_hid; g.K = s.D;
             g.C = ws + WL.dz; g.ldc = n_hid;
             g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = ld_hid;
-            if (grads->b1 && on_mfma_path(g, desc)) g.colsum = (float*)(ws + WL.colfuse_b1);   // db1 = column sums of dz
+            if (grads->b1 && on_mfma_path(g, desc)) g.colsum = (float*)(ws + WL.colfuse_b1 + cf);   // db1 = column sums of dz
             // micro-batches with their own codes: the saved GELU' is zero where a slice was not p_f, so those
             // products need not be formed
             hipError_t es = (gate && mask) ? run_gemm_segments(g, desc, *mask, mask->full, s.T, slice, st, &b1_bands) : hipErrorNotSupported;
@@ -1041,7 +1052,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             }
         }
         if (grads->b1 && b1_bands > 0) {
-            queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
+            queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1 + cf), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
         } else if (grads->b1) {
             rc = bias_grad(s, ws + WL.dz, n_hid, n_hid, colpart + 1 * WL.colpart_stride, grads->b1, gate ? 2 : 0,
                            &bias_batch, st);
@@ -1072,8 +1083,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         rc = late_join();
         if (rc != D2FT_OK) return rc;
         if (ln2_sums && (want_b2 || want_bo)) {
-            float* sum_res = want_b2 ? (float*)(ws + WL.colfuse_b2) : nullptr;
-            float* sum_out = want_bo ? (float*)(ws + WL.colfuse_bo) : nullptr;
+            float* sum_res = want_b2 ? (float*)(ws + WL.colfuse_b2 + cf) : nullptr;
+            float* sum_out = want_bo ? (float*)(ws + WL.colfuse_bo + cf) : nullptr;
             D2FT_TRY_BYTES(4.0 * s.M * s.D * s.es + 8.0 * s.M, launch_ln_bwd_sums(s.dtype, ws + WL.dv, x1, (const float*)(sv + SL.mean2),
                                         (const float*)(sv + SL.rstd2), w->ln2_g, dy, out, M, s.D, sum_res, sum_out, st));
             const int bands = ln_bwd_sums_bands(M);
@@ -1144,7 +1155,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     }
     // the matrix-core attention backward also leaves per-image column sums of dQKV: the QKV bias gradient
     const bool fuse_bqkv = grads->b_qkv && (mask || attn_bwd_on_mfma(desc, s.T, ldq, ldo, ld_do, ld_dq));
-    float* bqkv_part = fuse_bqkv ? (float*)(ws + WL.colfuse_bqkv) : nullptr;
+    float* bqkv_part = fuse_bqkv ? (float*)(ws + WL.colfuse_bqkv + cf) : nullptr;
     D2FT_TRY(run_attn_bwd(desc, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o, ld_do,
                           ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), bqkv_part, s.B, s.T, nf, st, mask));
     const void* u = sv + SL.u;
@@ -1188,8 +1199,18 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     // With LoRA the product is followed by the projection onto the adapters, too long a tail for the side stream
     // beside du alone (+0.06 ms per step): those stay on the caller's stream.
     if (dx1 != dx && !lora_queued) {
+        const bool forked = side && wgrads.g.n_groups > 0;   // hand_over orders the side stream behind this point
         rc = hand_over(0);   // little is left beside it: as fast as it can
         if (rc != D2FT_OK) return rc;
+        if (bias_on_side && forked && bias_batch.n > 0) {
+            bool fused_only = true;   // sums a column-sum pass left in the (single) colpart regions stay on the caller's stream
+            for (int i = 0; i < bias_batch.n; ++i)
+                if (bias_batch.job[i].partial >= colpart && bias_batch.job[i].partial < colpart + 6 * WL.colpart_stride) fused_only = false;
+            if (fused_only) {
+                rc = flush_bias_grads(desc, s, &bias_batch, qkv_tbl, ffn_tbl, st_side);
+                if (rc != D2FT_OK) return rc;
+            }
+        }
     }
     {   // du = dQKV W_eff (rows of the p_f heads)
         GemmArgs g = gemm_base();
