@@ -529,20 +529,20 @@ def dp_searching(scores: Sequence[float], weight: int, capacity: int) -> List[in
     sel = [0] * n
     if C < 0:
         return sel
+    # value table, one row per prefix of the items: row i is row i-1, improved from column c on by taking item i-1
     T = np.zeros((n + 1, C + 1), dtype=np.float64)
-    for i in range(1, n + 1):
-        a = float(scores[i - 1])
-        for wcap in range(0, C + 1):
-            if wcap >= c:
-                T[i][wcap] = max(T[i - 1][wcap], T[i - 1][wcap - c] + a)
-            else:
-                T[i][wcap] = T[i - 1][wcap]
-    i, wcap = n, C
-    while i > 0 and wcap > 0:
-        if T[i][wcap] != T[i - 1][wcap]:
+    for i, a in enumerate(np.asarray(scores, dtype=np.float64), start=1):
+        T[i] = T[i - 1]
+        if 0 <= c <= C:
+            T[i, c:] = np.maximum(T[i - 1, c:], T[i - 1, :C + 1 - c] + a)
+    # an item was taken wherever the value changes between consecutive rows at the remaining capacity
+    left = C
+    for i in range(n, 0, -1):
+        if left <= 0:
+            break
+        if T[i, left] != T[i - 1, left]:
             sel[i - 1] = 1
-            wcap -= c
-        i -= 1
+            left -= c
     return sel
 
 
@@ -563,15 +563,8 @@ def knapsack_scheduling(score_full, score_fwd, cost_fwd, cost_bwd, cap_full, cap
         w_f = int(cost_fwd[k])
         t_pf = dp_searching(score_full[k], w_b, int(cap_full[k]))
         t_po = dp_searching(score_fwd[k], w_f, int(cap_fwd[k]))
-        for i in range(n):
-            if t_pf[i] == 1 and t_po[i] == 0:
-                table[k][i] = OP_FULL
-            if t_pf[i] == 0 and t_po[i] == 1:
-                table[k][i] = OP_FWD
-            if t_pf[i] == 1 and t_po[i] == 1:
-                table[k][i] = OP_FULL
-            if t_pf[i] == 0 and t_po[i] == 0:
-                table[k][i] = OP_SKIP
+        pf, po = np.asarray(t_pf, dtype=bool), np.asarray(t_po, dtype=bool)
+        table[k] = np.where(pf, OP_FULL, np.where(po, OP_FWD, OP_SKIP))
     return table
 
 
