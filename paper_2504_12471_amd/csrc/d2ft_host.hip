@@ -510,8 +510,9 @@ struct SideStream {
     bool failed = false;
     // D2FT_FLAG_DEFER_JOIN: a call has returned with work still on the stream (`join` marks its end).
     // pending_early: its feed-forward weight gradients went over on their own and `early` marks their end;
+    // pending_late_dz: they went over with the attention half's instead, so the last launch reads dz;
     // pending_dims: the call's shape, i.e. its scratch layout.
-    bool pending = false, pending_early = false;
+    bool pending = false, pending_early = false, pending_late_dz = false;
     Dims pending_dims;
     int parity = 0;   // which set of fused column-sum regions the last backward call used
 };
@@ -892,18 +893,19 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) side = side_stream();
     }
     bool side_used = false;   // a join is due at the call's end
-    // An earlier call that deferred its join.  If this call has the same shape (hence the same scratch layout),
-    // defers too and the earlier call's feed-forward gradients went over on their own, only two things of that
-    // call can still be running: those gradients, which read dz, and the attention half's, which read dx1 and
-    // dQKV.  This call then waits for the first before it writes dz and for the second before it writes dx1
-    // (join_late), by when both have long ended; otherwise it waits for everything now.
+    // An earlier call that deferred its join.  If this call has the same shape (hence the same scratch layout)
+    // and defers too, only two things of that call can still be running: its feed-forward gradients, which read
+    // dz, and the attention half's (or the LoRA product), which read dx1 and dQKV.  This call then waits for the
+    // first (if there were any) before it writes dz and for the second before it writes dx1 (join_late), by when
+    // both have long ended.  Otherwise - or if the feed-forward gradients were part of that call's last launch -
+    // it waits for everything now.
     bool join_late = false;
     if (SideStream* P = side_stream(false); P && P->pending) {
         const Dims& q = P->pending_dims;
         const bool same = q.B == s.B && q.T == s.T && q.D == s.D && q.H == s.H && q.Dm == s.Dm && q.r == s.r && q.dtype == s.dtype;
-        if (side && same && P->pending_early && (desc->flags & D2FT_FLAG_DEFER_JOIN)) {
+        if (side && same && !P->pending_late_dz && (desc->flags & D2FT_FLAG_DEFER_JOIN)) {
             P->pending = false;
-            if (hipStreamWaitEvent(st, P->early, 0) != hipSuccess) return D2FT_EDEVICE;
+            if (P->pending_early && hipStreamWaitEvent(st, P->early, 0) != hipSuccess) return D2FT_EDEVICE;
             join_late = true;
         } else {
             const d2ft_status rj = join_pending(st);
@@ -916,6 +918,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         return hipStreamWaitEvent(st, side->join, 0) == hipSuccess ? D2FT_OK : D2FT_EDEVICE;
     };
     bool early_went = false;   // this call's feed-forward gradients went over on their own
+    bool late_dz = false;      // ... or wait in the batch for the call's last launch
     // the set of fused column-sum regions of this call
     const size_t cf = (side ? (side->parity ^= 1) : 0) * WL.colfuse_set;
     // Where the join is deferred the bias reductions go to the side stream with the last weight gradients (the
@@ -963,6 +966,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (desc->flags & D2FT_FLAG_DEFER_JOIN) {   // the next call on this device, or d2ft_join, waits for it
                 side->pending = true;
                 side->pending_early = early_went;
+                side->pending_late_dz = late_dz;
                 side->pending_dims = s;
             } else if (hipStreamWaitEvent(st_main, side->join, 0) != hipSuccess) {
                 return D2FT_EDEVICE;
@@ -1049,6 +1053,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                 if (rc != D2FT_OK) return rc;
                 if (hipEventRecord(side->early, st_side) != hipSuccess) return D2FT_EDEVICE;
                 early_went = true;
+            } else if (tiles > 0) {
+                late_dz = true;
             }
         }
         if (grads->b1 && b1_bands > 0) {
@@ -1197,8 +1203,8 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     // them the two streams end the call at about the same time, and a join that has to wait costs more than
     // the reductions.
     // With LoRA the product is followed by the projection onto the adapters, too long a tail for the side stream
-    // beside du alone (+0.06 ms per step): those stay on the caller's stream.
-    if (dx1 != dx && !lora_queued) {
+    // beside du alone if the call ends joined (+0.06 ms per step): those then stay on the caller's stream.
+    if (dx1 != dx && (!lora_queued || bias_on_side)) {
         const bool forked = side && wgrads.g.n_groups > 0;   // hand_over orders the side stream behind this point
         rc = hand_over(0);   // little is left beside it: as fast as it can
         if (rc != D2FT_OK) return rc;
