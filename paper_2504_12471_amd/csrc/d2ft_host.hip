@@ -945,16 +945,37 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     };
     // hand the weight gradients collected so far to the side stream, which picks them up behind what the
     // caller's stream holds now; without a side stream nothing happens here and they wait for the call's end
+    // Zero fills of the gradient slices of subnets that are not p_f: nothing in the call reads them and the
+    // reductions write other slices, so with the join deferred they wait for the next hand-over and ride on the
+    // side stream behind it instead of taking a turn on the caller's.
+    HeadList zero_list; zero_list.n = 0;
+    bool zero_heads_due = false, zero_ffn_due = false;
+    int zero_slice = 0;
+    auto launch_zeros = [&](hipStream_t st) -> d2ft_status {
+        if (zero_ffn_due) {
+            zero_ffn_due = false;
+            D2FT_TRY(launch_zero_ffn_slices(s.dtype, zero_list, zero_slice, s.D, s.Dm, grads->w1, grads->b1, grads->w2, st));
+        }
+        if (zero_heads_due) {
+            zero_heads_due = false;
+            D2FT_TRY(launch_zero_head_slices(s.dtype, zero_list, s.H, s.D, s.r, grads->w_qkv, grads->b_qkv, grads->w_o,
+                                             grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v, st));
+        }
+        return D2FT_OK;
+    };
     auto hand_over = [&](int max_units) -> d2ft_status {
         if (!side || wgrads.g.n_groups == 0) return D2FT_OK;
         if (!side_fork(side, st_main)) return D2FT_EDEVICE;
         side_used = true;
-        return flush_wgrads(st_side, max_units);
+        const d2ft_status rw = flush_wgrads(st_side, max_units);
+        return rw != D2FT_OK ? rw : launch_zeros(st_side);
     };
     // the call's last launches: the collected weight gradients, then the bias reductions, then the join
     auto finish = [&](const Remap64& tbl_a, const Remap64& tbl_b) -> d2ft_status {
         const d2ft_status rw = flush_wgrads(st_main);
         if (rw != D2FT_OK) return rw;
+        const d2ft_status rz = launch_zeros(st_main);   // no hand-over took them along
+        if (rz != D2FT_OK) return rz;
         if (bias_batch.n > 0) {
             const d2ft_status rb = flush_bias_grads(desc, s, &bias_batch, tbl_a, tbl_b, st_main);
             if (rb != D2FT_OK) return rb;
@@ -988,7 +1009,13 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         HeadList nonfull; nonfull.n = 0;
         for (int h = 0; h < s.H; ++h)
             if (ops[h] != D2FT_OP_FULL) nonfull.h[nonfull.n++] = (uint8_t)h;
-        D2FT_TRY(launch_zero_ffn_slices(s.dtype, nonfull, slice, s.D, s.Dm, grads->w1, grads->b1, grads->w2, st));
+        if (bias_on_side) {
+            zero_list = nonfull;
+            zero_slice = slice;
+            zero_ffn_due = true;
+        } else {
+            D2FT_TRY(launch_zero_ffn_slices(s.dtype, nonfull, slice, s.D, s.Dm, grads->w1, grads->b1, grads->w2, st));
+        }
         if (nl == 0 && grads->b2 && w->b2)   // bias was not applied: its gradient is zero
             D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->b2, s.D, RED_REMAP_NONE, none, 0, st));
         if (nf == 0) {
@@ -1117,8 +1144,13 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         HeadList nonfull; nonfull.n = 0;
         for (int h = 0; h < s.H; ++h)
             if (ops[h] != D2FT_OP_FULL) nonfull.h[nonfull.n++] = (uint8_t)h;
-        D2FT_TRY(launch_zero_head_slices(s.dtype, nonfull, s.H, s.D, s.r, grads->w_qkv, grads->b_qkv, grads->w_o,
-                                         grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v, st));
+        if (bias_on_side) {
+            zero_list = nonfull;
+            zero_heads_due = true;
+        } else {
+            D2FT_TRY(launch_zero_head_slices(s.dtype, nonfull, s.H, s.D, s.r, grads->w_qkv, grads->b_qkv, grads->w_o,
+                                             grads->lora_a_q, grads->lora_a_v, grads->lora_b_q, grads->lora_b_v, st));
+        }
         if (nl == 0 && grads->b_o && w->b_o) {   // bias was not applied: its gradient is zero
             // a [1][D] "partial" of zero splits writes +0.0
             D2FT_TRY(launch_reduce_partials(s.dtype, colpart, 0, 0, 1, s.D, grads->b_o, s.D, RED_REMAP_NONE, none, 0, st));
