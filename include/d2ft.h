@@ -81,13 +81,14 @@ enum {
      * timing is on (d2ft_timing_enable) or while the caller's stream is being captured. */
     D2FT_FLAG_ONE_STREAM = 8u,
     /* d2ft_block_bwd / d2ft_block_bwd_mb, for a caller's loop over blocks: return without making the caller's
-     * stream wait for the work the call left on the library's second stream (weight gradients of this call).
-     * That work is then ordered on the caller's stream by the next call into the library on this device
-     * (any entry point that launches work waits for it first; a following backward call of the same shape with
+     * stream wait for the work the call left on the library's second stream (this call's weight gradients, and
+     * with them its bias gradients and the zero fills of the slices that are not p_f).  That work is then
+     * ordered on the caller's stream by the next call on this device into a block, optimizer, score, embedding
+     * or classifier entry point (each waits for it first; a following backward call of the same shape with
      * this flag waits only where it has to, which is what makes the flag worth setting) or by d2ft_join().
-     * Until then the caller must not read this call's weight gradients, and must not write, free or reuse
-     * any buffer passed to this call, from its own code on any stream.  dx is complete on the caller's stream
-     * as always. */
+     * Until then the caller must not read any gradient of this call, and must not write, free or reuse any
+     * buffer passed to this call, from its own code on any stream.  dx is complete on the caller's stream as
+     * always. */
     D2FT_FLAG_DEFER_JOIN = 16u
 };
 
