@@ -87,7 +87,7 @@ SavedLayout saved_layout(const Dims& s) {
 
 // ---- layout of the scratch buffer ----
 struct ScratchLayout {
-    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, colfuse_set, dz, dv, dx1, d_o, dqkv, du, delta, lora_g, total;
+    size_t part, colpart, colfuse_b1, colfuse_b2, colfuse_bo, colfuse_bqkv, colfuse_set, dz, dz_alt, dv, dx1, d_o, dqkv, du, delta, lora_g, total;
     size_t part_floats, colpart_stride;
 };
 ScratchLayout scratch_layout(const Dims& s) {
@@ -120,6 +120,7 @@ ScratchLayout scratch_layout(const Dims& s) {
     L.colfuse_set = take(0) - L.colfuse_b1;
     take(L.colfuse_set);
     L.dz = take(s.M * s.Dm * s.es);
+    L.dz_alt = take(s.M * s.Dm * s.es) - L.dz;   // consecutive backward calls alternate (as for the column sums above)
     L.dv = take(s.M * s.D * s.es);
     L.dx1 = take(s.M * s.D * s.es);
     L.d_o = take(s.M * s.H * 64 * s.es);
@@ -506,13 +507,11 @@ d2ft_status weight_grad_queue(WeightGradBatch* b, const d2ft_block_desc* d, cons
 // call ends joined, so that to the caller the whole call is work on its own stream.
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr, early = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
     bool failed = false;
     // D2FT_FLAG_DEFER_JOIN: a call has returned with work still on the stream (`join` marks its end).
-    // pending_early: its feed-forward weight gradients went over on their own and `early` marks their end;
-    // pending_late_dz: they went over with the attention half's instead, so the last launch reads dz;
     // pending_dims: the call's shape, i.e. its scratch layout.
-    bool pending = false, pending_early = false, pending_late_dz = false;
+    bool pending = false;
     Dims pending_dims;
     int parity = 0;   // which set of fused column-sum regions the last backward call used
 };
@@ -527,8 +526,7 @@ SideStream* side_stream(bool create = true) {
         if (!create) return nullptr;
         if (hipStreamCreateWithFlags(&S.stream, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&S.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&S.join, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&S.early, hipEventDisableTiming) != hipSuccess) {
+            hipEventCreateWithFlags(&S.join, hipEventDisableTiming) != hipSuccess) {
             S.failed = true;
             S.stream = nullptr;
             return nullptr;
@@ -894,18 +892,17 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     }
     bool side_used = false;   // a join is due at the call's end
     // An earlier call that deferred its join.  If this call has the same shape (hence the same scratch layout)
-    // and defers too, only two things of that call can still be running: its feed-forward gradients, which read
-    // dz, and the attention half's (or the LoRA product), which read dx1 and dQKV.  This call then waits for the
-    // first (if there were any) before it writes dz and for the second before it writes dx1 (join_late), by when
-    // both have long ended.  Otherwise - or if the feed-forward gradients were part of that call's last launch -
-    // it waits for everything now.
+    // and defers too, what may still be running of that call are its weight-gradient launches: they read its dz
+    // and its fused column sums, of which consecutive calls use alternating copies, and dx1 and dQKV.  This call
+    // then waits only before it writes dx1 (join_late), by when they have long ended - and since that wait
+    // covers the whole earlier call, the copies this call writes now were last read two calls ago, behind the
+    // wait of the call before.  Otherwise it waits for everything now.
     bool join_late = false;
     if (SideStream* P = side_stream(false); P && P->pending) {
         const Dims& q = P->pending_dims;
         const bool same = q.B == s.B && q.T == s.T && q.D == s.D && q.H == s.H && q.Dm == s.Dm && q.r == s.r && q.dtype == s.dtype;
-        if (side && same && !P->pending_late_dz && (desc->flags & D2FT_FLAG_DEFER_JOIN)) {
+        if (side && same && (desc->flags & D2FT_FLAG_DEFER_JOIN)) {
             P->pending = false;
-            if (P->pending_early && hipStreamWaitEvent(st, P->early, 0) != hipSuccess) return D2FT_EDEVICE;
             join_late = true;
         } else {
             const d2ft_status rj = join_pending(st);
@@ -917,10 +914,10 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         join_late = false;
         return hipStreamWaitEvent(st, side->join, 0) == hipSuccess ? D2FT_OK : D2FT_EDEVICE;
     };
-    bool early_went = false;   // this call's feed-forward gradients went over on their own
-    bool late_dz = false;      // ... or wait in the batch for the call's last launch
     // the set of fused column-sum regions of this call
-    const size_t cf = (side ? (side->parity ^= 1) : 0) * WL.colfuse_set;
+    const int parity = side ? (side->parity ^= 1) : 0;
+    const size_t cf = parity * WL.colfuse_set;
+    char* const dz_buf = ws + WL.dz + parity * WL.dz_alt;   // dz of this call
     // Where the join is deferred the bias reductions go to the side stream with the last weight gradients (the
     // caller's stream then ends the call with LayerNorm 1's backward); where the call ends joined they stay on
     // the caller's stream, which would otherwise wait for them.
@@ -986,8 +983,6 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (hipEventRecord(side->join, st_side) != hipSuccess) return D2FT_EDEVICE;
             if (desc->flags & D2FT_FLAG_DEFER_JOIN) {   // the next call on this device, or d2ft_join, waits for it
                 side->pending = true;
-                side->pending_early = early_went;
-                side->pending_late_dz = late_dz;
                 side->pending_dims = s;
             } else if (hipStreamWaitEvent(st_main, side->join, 0) != hipSuccess) {
                 return D2FT_EDEVICE;
@@ -1050,7 +1045,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             g.B = w->w2; g.b_rs = s.Dm; g.b_cs = 1;   // B(k = width index, n = hidden index) = W2[k][n]
             g.remap = gate ? REMAP_B_N : REMAP_NONE;
             g.M = M; g.N = n_hid; g.K = s.D;
-            g.C = ws + WL.dz; g.ldc = n_hid;
+            g.C = dz_buf; g.ldc = n_hid;
             g.act = ACT_DGELU; g.Z = const_cast<char*>(sv + SL.z); g.ldz = ld_hid;
             if (grads->b1 && on_mfma_path(g, desc)) g.colsum = (float*)(ws + WL.colfuse_b1 + cf);   // db1 = column sums of dz
             // micro-batches with their own codes: the saved GELU' is zero where a slice was not p_f, so those
@@ -1061,7 +1056,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (!g.colsum) b1_bands = 0;
         }
         if (grads->w1) {   // dW1[hidden] = dz^T v
-            rc = weight_grad_queue(&wgrads, desc, s, ws + WL.dz, n_hid, sv + SL.v, s.D, n_hid, s.D, part, grads->w1, s.D,
+            rc = weight_grad_queue(&wgrads, desc, s, dz_buf, n_hid, sv + SL.v, s.D, n_hid, s.D, part, grads->w1, s.D,
                                    gate ? RED_REMAP_ROWS : RED_REMAP_NONE, ffn_tbl, 0, st);
             if (rc != D2FT_OK) return rc;
         }
@@ -1078,23 +1073,19 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (tiles >= 24) {
                 rc = hand_over((int)(2 * tiles > 128 ? 2 * tiles : 128));
                 if (rc != D2FT_OK) return rc;
-                if (hipEventRecord(side->early, st_side) != hipSuccess) return D2FT_EDEVICE;
-                early_went = true;
-            } else if (tiles > 0) {
-                late_dz = true;
             }
         }
         if (grads->b1 && b1_bands > 0) {
             queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1 + cf), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
         } else if (grads->b1) {
-            rc = bias_grad(s, ws + WL.dz, n_hid, n_hid, colpart + 1 * WL.colpart_stride, grads->b1, gate ? 2 : 0,
+            rc = bias_grad(s, dz_buf, n_hid, n_hid, colpart + 1 * WL.colpart_stride, grads->b1, gate ? 2 : 0,
                            &bias_batch, st);
             if (rc != D2FT_OK) return rc;
         }
         {   // dv = dz W1[hidden]
             GemmArgs g = gemm_base();
             g.tbl = ffn_tbl;
-            g.A = ws + WL.dz; g.a_rs = n_hid; g.a_cs = 1;
+            g.A = dz_buf; g.a_rs = n_hid; g.a_cs = 1;
             g.B = w->w1; g.b_rs = s.D; g.b_cs = 1; g.remap = gate ? REMAP_B_K : REMAP_NONE;
             g.M = M; g.N = s.D; g.K = n_hid;
             g.C = ws + WL.dv; g.ldc = s.D;
