@@ -155,6 +155,12 @@ struct GemmArgs {
 };
 
 // launchers (defined in the kernel sources); each returns hipGetLastError()
+// The next matrix-core launch (a GEMM of any form, or the attention backward) completes ev, as an event record behind
+// it would, at less cost to its stream: the launch sites call take().  pending() tells whether a launch has taken
+// it yet; next(nullptr) withdraws it.  One host thread per device at a time, like the calls themselves.
+void launch_signal_next(hipEvent_t ev);
+bool launch_signal_pending();
+hipEvent_t launch_signal_take();
 hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);

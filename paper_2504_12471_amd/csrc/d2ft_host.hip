@@ -258,8 +258,12 @@ void timing_end(hipStream_t st) {
         if (e__ != hipSuccess) return D2FT_EDEVICE; \
     } while (0)
 
+// the event that the next matrix-core launch is to complete (launch_signal_next)
+hipEvent_t g_launch_signal = nullptr;
+
 // one timed GEMM launch (the launch sites use D2FT_TRY_UNTIMED around run_gemm)
-hipError_t timed_mfma(const GemmArgs& g, hipStream_t st) {
+hipError_t timed_mfma(const GemmArgs& g, hipStream_t st, hipEvent_t done = nullptr) {
+    if (done) launch_signal_next(done);
     timing_begin(st, "gemm");
     g_timing.label = gemm_mfma_config_name(g);
     g_timing.flops = 2.0 * g.M * g.N * g.K;
@@ -274,7 +278,10 @@ bool on_mfma_path(const GemmArgs& g, const d2ft_block_desc* d) {
 }
 
 // colsum_bands: if non-null, receives the number of rows of g.colsum the launches fill
-hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, int* colsum_bands = nullptr) {
+// done: if non-null, the call's last matrix-core launch completes it (gemm_mfma_signal_next); the caller checks
+// launch_signal_pending() for the paths that have no such launch
+hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, int* colsum_bands = nullptr,
+                    hipEvent_t done = nullptr) {
     if (colsum_bands) *colsum_bands = 0;
     if (on_mfma_path(g, d)) {
         // Tile plan for shapes of more than one round of the chip's 256 CUs.  The one-per-CU tiles take whole
@@ -315,14 +322,14 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, 
                         if (colsum_bands) *colsum_bands = 2 * (int)tm_big + 2 * ((rest.M + 127) / 128);
                         hipError_t e = timed_mfma(big, s);
                         if (e != hipSuccess) return e;
-                        return timed_mfma(rest, s);
+                        return timed_mfma(rest, s, done);
                     }
                 } else if (c_all192 < c_all256) {
                     GemmArgs t = g;
                     t.tile_hint = 3;
                     if (gemm_mfma_supported(t)) {
                         if (colsum_bands) *colsum_bands = 2 * ((g.M + 191) / 192);
-                        return timed_mfma(t, s);
+                        return timed_mfma(t, s, done);
                     }
                 }
             }
@@ -331,7 +338,7 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, 
             const int bm = gemm_mfma_tile_rows(g);
             *colsum_bands = 2 * ((g.M + bm - 1) / bm);
         }
-        return timed_mfma(g, s);
+        return timed_mfma(g, s, done);
     }
     if (g.colsum) return hipErrorNotSupported;   // callers ask on_mfma_path() first
     timing_begin(s, "gemm");
@@ -347,7 +354,7 @@ hipError_t run_gemm(const GemmArgs& g, const d2ft_block_desc* d, hipStream_t s, 
 // that no micro-batch needs are not multiplied.  hipErrorNotSupported (nothing launched) if the shape does not
 // fit: the caller then multiplies the union of the slices over all rows and zeroes afterwards.
 hipError_t run_gemm_segments(GemmArgs g, const d2ft_block_desc* d, const MicroMask& mask, const uint64_t* pos_of, int tokens,
-                             int slice, hipStream_t s, int* colsum_bands = nullptr) {
+                             int slice, hipStream_t s, int* colsum_bands = nullptr, hipEvent_t done = nullptr) {
     if (colsum_bands) *colsum_bands = 0;
     if (!on_mfma_path(g, d) || mask.n > kMaxGemmSegments) return hipErrorNotSupported;
     g.seg.n = mask.n;
@@ -360,6 +367,7 @@ hipError_t run_gemm_segments(GemmArgs g, const d2ft_block_desc* d, const MicroMa
     }
     if (gemm_mfma_seg_prepare(&g) != hipSuccess) return hipErrorNotSupported;
     if (colsum_bands) *colsum_bands = 2 * ((g.M + 255) / 256);
+    if (done) launch_signal_next(done);
     timing_begin(s, "gemm");
     g_timing.label = g.b_rs != 1 ? "gemm_mfma_kernel<256, 256, 64, 2, 4, false, true, 1, false, false, true, 1>"
                                  : "gemm_mfma_kernel<256, 256, 64, 2, 4, false, false, 1, false, false, true, 0>";
@@ -395,9 +403,12 @@ static bool attn_bwd_on_mfma(const d2ft_block_desc* d, int tokens, long ldq, lon
            (ld_do % 8) == 0 && (ld_dqkv % 8) == 0;
 }
 
+// done: if non-null, the matrix-core launch completes it (the caller checks launch_signal_pending() for the path
+// that has none)
 hipError_t run_attn_bwd(const d2ft_block_desc* d, const void* qkv, long ldq, const void* o, long ldo, const float* lse,
                         const void* d_o, long ld_do, void* dqkv, long ld_dqkv, float* delta, float* bsum, int batch,
-                        int tokens, int n_full, hipStream_t s, const MicroMask* mask = nullptr) {
+                        int tokens, int n_full, hipStream_t s, const MicroMask* mask = nullptr, hipEvent_t done = nullptr) {
+    if (done) launch_signal_next(done);
     g_timing.flops = 8.0 * batch * n_full * (double)tokens * tokens * 64;
     if (mask) {
         g_timing.label = "attn_bwd_mfma";
@@ -631,6 +642,14 @@ d2ft_status flush_bias_grads(const d2ft_block_desc* d, const Dims& s, ColReduceB
 }
 
 }  // namespace
+
+void launch_signal_next(hipEvent_t ev) { g_launch_signal = ev; }
+bool launch_signal_pending() { return g_launch_signal != nullptr; }
+hipEvent_t launch_signal_take() {
+    hipEvent_t ev = g_launch_signal;
+    g_launch_signal = nullptr;
+    return ev;
+}
 }  // namespace d2ft
 
 using namespace d2ft;
@@ -960,9 +979,15 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         }
         return D2FT_OK;
     };
+    bool fork_recorded = false;   // the last launch on the caller's stream completes side->fork itself
     auto hand_over = [&](int max_units) -> d2ft_status {
         if (!side || wgrads.g.n_groups == 0) return D2FT_OK;
-        if (!side_fork(side, st_main)) return D2FT_EDEVICE;
+        if (fork_recorded) {
+            fork_recorded = false;
+            if (hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) return D2FT_EDEVICE;
+        } else if (!side_fork(side, st_main)) {
+            return D2FT_EDEVICE;
+        }
         side_used = true;
         const d2ft_status rw = flush_wgrads(st_side, max_units);
         return rw != D2FT_OK ? rw : launch_zeros(st_side);
@@ -1050,9 +1075,17 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             if (grads->b1 && on_mfma_path(g, desc)) g.colsum = (float*)(ws + WL.colfuse_b1 + cf);   // db1 = column sums of dz
             // micro-batches with their own codes: the saved GELU' is zero where a slice was not p_f, so those
             // products need not be formed
-            hipError_t es = (gate && mask) ? run_gemm_segments(g, desc, *mask, mask->full, s.T, slice, st, &b1_bands) : hipErrorNotSupported;
-            if (es == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(g, desc, st, &b1_bands));
+            // if the feed-forward weight gradients go to the side stream behind dz, the dz launch itself completes
+            // the event that stream waits for
+            long ffn_tiles = 0;
+            if (grads->w2) ffn_tiles += (long)((s.D + 255) / 256) * ((n_hid + 255) / 256);
+            if (grads->w1) ffn_tiles += (long)((n_hid + 255) / 256) * ((s.D + 255) / 256);
+            hipEvent_t dz_done = (side && ffn_tiles >= 24) ? side->fork : nullptr;
+            hipError_t es = (gate && mask) ? run_gemm_segments(g, desc, *mask, mask->full, s.T, slice, st, &b1_bands, dz_done) : hipErrorNotSupported;
+            if (es == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(g, desc, st, &b1_bands, dz_done));
             else if (es != hipSuccess) return D2FT_EDEVICE;
+            if (dz_done && launch_signal_pending()) launch_signal_next(nullptr);   // no launch took it: record it below
+            else if (dz_done) fork_recorded = true;
             if (!g.colsum) b1_bands = 0;
         }
         if (grads->w1) {   // dW1[hidden] = dz^T v
@@ -1075,6 +1108,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
                 if (rc != D2FT_OK) return rc;
             }
         }
+        fork_recorded = false;   // it stood for this point of the stream only
         if (grads->b1 && b1_bands > 0) {
             queue_bias_reduce(&bias_batch, (const float*)(ws + WL.colfuse_b1 + cf), b1_bands, n_hid, grads->b1, gate ? 2 : 0);
         } else if (grads->b1) {
@@ -1185,10 +1219,18 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
     // the matrix-core attention backward also leaves per-image column sums of dQKV: the QKV bias gradient
     const bool fuse_bqkv = grads->b_qkv && (mask || attn_bwd_on_mfma(desc, s.T, ldq, ldo, ld_do, ld_dq));
     float* bqkv_part = fuse_bqkv ? (float*)(ws + WL.colfuse_bqkv + cf) : nullptr;
-    D2FT_TRY(run_attn_bwd(desc, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o, ld_do,
-                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), bqkv_part, s.B, s.T, nf, st, mask));
-    const void* u = sv + SL.u;
     const bool want_lora = s.r > 0 && (grads->lora_a_q || grads->lora_a_v || grads->lora_b_q || grads->lora_b_v);
+    // If the side stream takes over right behind the attention backward (nothing else is launched on the caller's
+    // stream between the two), that launch itself completes the event the side stream waits for.
+    const bool room = wgrads.g.n_groups < kMaxGemmGroups;   // dWqkv (or the LoRA product) joins the batch
+    const bool lora_batched = want_lora && !grads->w_qkv && room;
+    const bool quiet = room && (fuse_bqkv || !grads->b_qkv) && (!want_lora || lora_batched);
+    hipEvent_t attn_done = (side && dx1 != dx && quiet && (!lora_batched || bias_on_side)) ? side->fork : nullptr;
+    D2FT_TRY(run_attn_bwd(desc, sv + SL.qkv, ldq, sv + SL.o, ldo, (const float*)(sv + SL.lse), ws + WL.d_o, ld_do,
+                          ws + WL.dqkv, ld_dq, (float*)(ws + WL.delta), bqkv_part, s.B, s.T, nf, st, mask, attn_done));
+    if (attn_done && launch_signal_pending()) launch_signal_next(nullptr);   // no launch took it: recorded below
+    else if (attn_done) fork_recorded = true;
+    const void* u = sv + SL.u;
     if (grads->w_qkv && !want_lora) {   // dWqkv = dQKV^T u, rows scattered to the p_f heads' planes
         rc = weight_grad_queue(&wgrads, desc, s, ws + WL.dqkv, ld_dq, u, s.D, nf * 192, s.D, part, grads->w_qkv, s.D,
                                RED_REMAP_ROWS, qkv_tbl, 2, st);
@@ -1241,6 +1283,7 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             }
         }
     }
+    fork_recorded = false;   // it stood for this point of the stream only
     {   // du = dQKV W_eff (rows of the p_f heads)
         GemmArgs g = gemm_base();
         g.tbl = qkv_tbl;

@@ -13,6 +13,7 @@
 // MFMA 32x32x16 bf16 layouts used throughout (h = lane / 32, c = lane % 32):
 //   operand:  row-or-column c, k-slots 8h .. 8h+7
 //   result :  column c, element e <-> row 8*(e/4) + 4h + e%4
+#include <hip/hip_ext.h>
 #include <type_traits>
 #include <utility>
 
@@ -1004,8 +1005,13 @@ hipError_t launch_bwd_kt(const bf16* qkv, long ldq, const bf16* o, long ldo, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * (KT + 1)), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv,
-                       ld_dqkv, bsum, ld_bsum, tokens, n_full, (long)batch * tokens, mask);
+    if (hipEvent_t ev = launch_signal_take()) {   // the launch completes the event itself
+        hipExtLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * (KT + 1)), lds, s, nullptr, ev, 0, qkv, ldq, o, ldo, lse,
+                              d_o, ld_do, dqkv, ld_dqkv, bsum, ld_bsum, tokens, n_full, (long)batch * tokens, mask);
+    } else {
+        hipLaunchKernelGGL(kern, dim3(batch * n_full), dim3(64 * (KT + 1)), lds, s, qkv, ldq, o, ldo, lse, d_o, ld_do, dqkv,
+                           ld_dqkv, bsum, ld_bsum, tokens, n_full, (long)batch * tokens, mask);
+    }
     return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@
 // B's n or k index may go through a 64-granular remap table: that is how the compacted
 // live-head list selects rows / columns of the full weight tensors without copying them.
 #include <cstdio>
+#include <hip/hip_ext.h>
 #include <type_traits>
 
 #include "d2ft_common.h"
@@ -723,6 +724,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     }
 }
 
+// A launch that an event waits for (launch_signal_next) carries the event as its own completion signal.
+template <typename Kernel>
+void launch_kernel(Kernel kern, dim3 grid, dim3 block, size_t lds, hipStream_t s, const GemmArgs& g) {
+    if (hipEvent_t ev = launch_signal_take()) {
+        hipExtLaunchKernelGGL(kern, grid, block, lds, s, nullptr, ev, 0, g);
+    } else {
+        hipLaunchKernelGGL(kern, grid, block, lds, s, g);
+    }
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL>
 constexpr size_t lds_bytes() {
     constexpr size_t slabs = 2 * (slab_elems<BM, BK, A_COL>() + slab_elems<BN, BK, B_COL>()) * sizeof(bf16);
@@ -750,7 +761,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * splits;
     // persistent: no more workgroups than are resident together; each walks tiles b, b + grid, ...
     const dim3 grid((unsigned)(tiles < resident ? tiles : resident)), block(64 * WGM * WGN);
-    hipLaunchKernelGGL(kern, grid, block, lds, s, g);
+    launch_kernel(kern, grid, block, lds, s, g);
     return hipGetLastError();
 }
 
@@ -799,7 +810,7 @@ hipError_t launch_grouped_cfg(GemmArgs* g, hipStream_t s) {
     g->units_per_wg = (S + best - 1) / best;
     const long units = (long)tile * best;
     long grid = units < resident ? (units + 7) / 8 * 8 : resident;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, *g);
+    launch_kernel(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, *g);
     return hipGetLastError();
 }
 
@@ -833,7 +844,7 @@ hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
     }
     const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
     const long grid = tiles < resident ? (tiles + 7) / 8 * 8 : resident;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, g);
+    launch_kernel(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, g);
     return hipGetLastError();
 }
 
