@@ -258,8 +258,8 @@ void timing_end(hipStream_t st) {
         if (e__ != hipSuccess) return D2FT_EDEVICE; \
     } while (0)
 
-// the event that the next matrix-core launch is to complete (launch_signal_next)
-hipEvent_t g_launch_signal = nullptr;
+// the event that this thread's next matrix-core launch is to complete (launch_signal_next)
+thread_local hipEvent_t g_launch_signal = nullptr;
 
 // one timed GEMM launch (the launch sites use D2FT_TRY_UNTIMED around run_gemm)
 hipError_t timed_mfma(const GemmArgs& g, hipStream_t st, hipEvent_t done = nullptr) {
