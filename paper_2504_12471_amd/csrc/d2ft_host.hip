@@ -514,8 +514,10 @@ d2ft_status weight_grad_queue(WeightGradBatch* b, const d2ft_block_desc* d, cons
 // A second stream of the library's own, per device, with the two events that order it against the caller's
 // stream.  A backward call puts the weight-gradient launches with their reductions on it - nothing else in the
 // call waits for them - so that they run beside the chain of launches that leads to dx, most of which leave CUs
-// idle (GEMMs of fewer tiles than CUs, partial last rounds, the attention backward).  Default priority; every
-// call ends joined, so that to the caller the whole call is work on its own stream.
+// idle (GEMMs of fewer tiles than CUs, partial last rounds, the attention backward).  Default priority; a call
+// ends joined, so that to the caller the whole call is work on its own stream, unless the caller hands the join
+// on with D2FT_FLAG_DEFER_JOIN.  `fork` is recorded on the caller's stream, or completed by the launch the side
+// stream has to wait for (launch_signal_next), and waited for by the side stream; `join` the other way round.
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
