@@ -92,6 +92,9 @@ struct Remap64 {
 //   A(m,k) = A[m*a_rs + k*a_cs],  B(k,n) = B[k*b_rs + n*b_cs]   (element strides)
 // ---------------------------------------------------------------------------
 enum { REMAP_NONE = 0, REMAP_B_N = 1, REMAP_B_K = 2 };
+// kernel instantiations only: REMAP_B_K whose K walk is cut down per tile row to the 64-wide blocks of the
+// positions that take part in a row segment the tile overlaps (launch_gemm_mfma_kseg)
+constexpr int REMAP_B_KSEG = 3;
 enum { ACT_NONE = 0, ACT_GELU = 1, ACT_DGELU = 2 };
 
 // One problem of a grouped weight-gradient launch: C_g[m][n] = sum_k A_g[k][m] * B_g[k][n], k over the token
@@ -110,6 +113,10 @@ constexpr int kMaxGemmGroups = 4;
 // output element of a row in segment i and a column of position p is computed if bit p of pos[i] is set and
 // written as zero otherwise.  launch_gemm_mfma_seg skips the 256x256 tiles no row of which takes part (they are
 // only zero-filled) and deals the tiles with work evenly over the workgroups.
+// The same description serves a GEMM whose *K* index comes in positions (launch_gemm_mfma_kseg): the columns of A
+// at position p are zero in the rows of a segment in which p does not take part; every segment gets tile rows of
+// its own (row_before[i]: the first tile row of segment i, live_tiles: their number) and a tile walks only the
+// positions of its segment.
 constexpr int kMaxGemmSegments = 8;
 constexpr int kMaxSegTileRows = 64;
 struct GemmRowSegments {
@@ -165,6 +172,11 @@ hipError_t launch_gemm_simple(const GemmArgs& g, int dtype, hipStream_t s);
 // bf16 MFMA path; returns hipErrorNotSupported if the shape/strides do not fit it
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs& g);
+// C = A B (+ bias + residual) with A row-major, B's k through the remap table (REMAP_B_K) and K = positions of
+// g.seg.slice columns of A: the tiles of a segment's rows walk only the positions set in its g.seg.pos (the
+// caller guarantees that A is zero elsewhere, so the result is that of the full walk).  Takes g.seg.n, slice, end
+// and pos; hipErrorNotSupported (nothing launched) if the shape does not fit.
+hipError_t launch_gemm_mfma_kseg(const GemmArgs& g, hipStream_t s);
 // The forms with A row-major (C = A B, no split-K, no residual) over row segments: prepare takes g->seg.n, slice,
 // end and pos and fills the rest of g->seg, or returns hipErrorNotSupported if the shape does not fit (more than
 // 64 tile rows or 16 tile columns of 256, K not a multiple of 64, operands the matrix-core path does not take);

@@ -377,6 +377,33 @@ hipError_t run_gemm_segments(GemmArgs g, const d2ft_block_desc* d, const MicroMa
     return e;
 }
 
+// A product whose K index runs over the gated slices (FC2 forward, the backward's dv) while the micro-batches have
+// their own codes: A's columns of a slice are zero in the rows of a micro-batch in which the slice does not take
+// part (pos_of[i]: the slices of micro-batch i), so every tile walks only the slices of the micro-batches its rows
+// belong to.  The sums are those of the full walk.  hipErrorNotSupported (nothing launched) if the shape does not fit.
+hipError_t run_gemm_kseg(GemmArgs g, const d2ft_block_desc* d, const MicroMask& mask, const uint64_t* pos_of, int tokens,
+                         int slice, hipStream_t s) {
+    if (!on_mfma_path(g, d) || mask.n > kMaxGemmSegments) return hipErrorNotSupported;
+    g.seg.n = mask.n;
+    g.seg.slice = slice;
+    double ks = 0.0;   // row x k pairs that are walked if no tile straddles two micro-batches
+    for (int i = 0; i < kMaxGemmSegments; ++i) {
+        g.seg.end[i] = i < mask.n ? mask.img_end[i] * tokens : g.M;
+        g.seg.pos[i] = i < mask.n ? pos_of[i] : 0;
+        if (i < mask.n) ks += (double)(mask.img_end[i] - (i ? mask.img_end[i - 1] : 0)) * tokens * __builtin_popcountll(pos_of[i]) * slice;
+    }
+    timing_begin(s, "gemm");
+    if (g_timing.on) {
+        static char label[160];
+        snprintf(label, sizeof(label), "%s k-segments", gemm_mfma_config_name(g));
+        g_timing.label = label;
+        g_timing.flops = 2.0 * ks * g.N;
+    }
+    const hipError_t e = launch_gemm_mfma_kseg(g, s);
+    timing_end(s);
+    return e;
+}
+
 // bf16, head dimension 64, up to 224 tokens: the matrix-core attention kernels, forward and backward
 static bool attn_on_mfma(const d2ft_block_desc* d) {
     return d->dtype == D2FT_BF16 && !(d->flags & D2FT_FLAG_NO_MFMA) && d->tokens <= 224;
@@ -853,7 +880,10 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         g.C = y; g.ldc = s.D;
         g.bias = w->b2;
         g.residual = x1; g.ldr = s.D;
-        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        // micro-batches with their own codes: g is zero where a slice was skipped, so a tile need not walk it
+        hipError_t ek = (gate && mask) ? run_gemm_kseg(g, desc, *mask, mask->live, s.T, slice, st) : hipErrorNotSupported;
+        if (ek == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        else if (ek != hipSuccess) return D2FT_EDEVICE;
         // the backward multiplies the saved g and GELU' of the p_f slices over the whole batch: zero what
         // was forward-only in its micro-batch (dz = (dy W2) * GELU' is then zero there too)
         if (gate && mask) D2FT_TRY(launch_zero_pairs(s.dtype, sv + SL.g, sv + SL.z, n_hid, s.B, s.T, nf, slice, PAIRS_FORWARD_ONLY, *mask, st));
@@ -1125,7 +1155,10 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
             g.B = w->w1; g.b_rs = s.D; g.b_cs = 1; g.remap = gate ? REMAP_B_K : REMAP_NONE;
             g.M = M; g.N = s.D; g.K = n_hid;
             g.C = ws + WL.dv; g.ldc = s.D;
-            D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+            // micro-batches with their own codes: dz is zero where a slice was not p_f
+            hipError_t ek = (gate && mask) ? run_gemm_kseg(g, desc, *mask, mask->full, s.T, slice, st) : hipErrorNotSupported;
+            if (ek == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+            else if (ek != hipSuccess) return D2FT_EDEVICE;
         }
         if (grads->ln2_g || grads->ln2_b) {
             const int chunks = pick_chunks(s.M);

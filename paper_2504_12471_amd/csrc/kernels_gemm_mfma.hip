@@ -241,6 +241,9 @@ template <int BM, int BN, int BK, int WGM, int WGN, bool A_COL, bool B_COL, int 
           bool SEGMENTS = false, int EPI = EPI_ANY>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int kThreads = 64 * WGM * WGN;    // WGM x WGN wavefronts
+    constexpr bool KSEG = REMAP == REMAP_B_KSEG;    // K walk over the positions of the tile's row segments
+    constexpr bool REMAP_BK = REMAP == REMAP_B_K || KSEG;
+    static_assert(!KSEG || (!KTAIL && !GROUPED && !SEGMENTS && !A_COL), "the K-segment form: A row-major, K a multiple of 64");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
     constexpr int MT = WTM / 32, NT = WTN / 32; // MFMA tiles per wavefront
     constexpr int A_ELEMS = slab_elems<BM, BK, A_COL>();
@@ -253,7 +256,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     const bf16* __restrict__ B = static_cast<const bf16*>(g.B);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    // K-segment form: every segment has tile rows of its own (g.seg.live_tiles of them in all), so that no tile
+    // has rows of two segments
+    const int tiles_m = REMAP == REMAP_B_KSEG ? g.seg.live_tiles : (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int total = SEGMENTS ? g.seg.live_tiles : tiles_m * tiles_n * (g.partial ? g.splits : 1);
 
     f32x16 acc[MT][NT];
@@ -266,6 +271,19 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     // the next tile ahead of the current tile's epilogue, and the epilogue's global stores drain while
     // the next tile is being multiplied.
     int m0 = 0, n0 = 0, split = 0, kb = 0, ke = 0, nslabs = 0;
+    // K-segment form: the positions still to walk (the lowest set bit is the current one), the 64-wide block
+    // within the current position, and k of the next slab to fetch
+    uint64_t kseg_left = 0;
+    int kseg_sub = 0, kseg_k = 0, mlim = 0;   // mlim: the end of the tile's segment
+    auto kseg_advance = [&]() {
+        if (++kseg_sub * BK >= g.seg.slice) {
+            kseg_sub = 0;
+            kseg_left &= kseg_left - 1;
+            kseg_k = kseg_left ? __builtin_ctzll(kseg_left) * g.seg.slice : 0;
+        } else {
+            kseg_k += BK;
+        }
+    };
     // Grouped mode (weight gradients of several layers in one launch, all reducing over the same K): the work
     // is the list of units (tile, split) = unit % total_tiles, unit / total_tiles; every tile's K is cut into
     // g.splits equal runs of slabs.  Workgroup ids are renumbered so that the units of one XCD's workgroups are
@@ -328,13 +346,41 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
             kb = split * per;
             ke = min(g.K, kb + per);
         }
+        if constexpr (KSEG) {
+            // the tile row's segment (row_before[i]: the first tile row of segment i), its rows and its positions
+            // (constant indices into the kernel arguments: the segment is picked by comparisons)
+            int lo = 0;
+#pragma unroll
+            for (int i = 0; i < kMaxGemmSegments; ++i) {
+                const int first = (int)g.seg.row_before[i], hi = g.seg.end[i];
+                const bool mine = i < g.seg.n && tile_m >= first && (i + 1 >= g.seg.n || tile_m < (int)g.seg.row_before[i + 1]);
+                if (mine) {
+                    m0 = lo + (tile_m - first) * BM;
+                    mlim = hi;
+                    kseg_left = g.seg.pos[i];
+                }
+                lo = hi;
+            }
+        }
         // strides as (index stride, k stride)
-        la.template init<false>(A, g.a_rs, g.a_cs, m0, g.M, g.tbl);
+        int a_rows = g.M;
+        if constexpr (KSEG) a_rows = mlim;
+        la.template init<false>(A, g.a_rs, g.a_cs, m0, a_rows, g.tbl);
         lb.template init<REMAP == REMAP_B_N>(B, g.b_cs, g.b_rs, n0, g.N, g.tbl);
         nslabs = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
-        if (nslabs > 0) {
+        if constexpr (KSEG) {
+            const uint64_t take = kseg_left;
+            kseg_sub = 0;
+            kseg_k = take ? __builtin_ctzll(take) * g.seg.slice : 0;
+            nslabs = __builtin_popcountll(take) * (g.seg.slice / BK);
+            if (nslabs > 0) {
+                la.template load<false, false>(kseg_k, ke, g.tbl);
+                lb.template load<true, false>(kseg_k, ke, g.tbl);
+                kseg_advance();
+            }
+        } else if (nslabs > 0) {
             la.template load<false, KTAIL>(kb, ke, g.tbl);
-            lb.template load<REMAP == REMAP_B_K, KTAIL>(kb, ke, g.tbl);
+            lb.template load<REMAP_BK, KTAIL>(kb, ke, g.tbl);
         }
     };
 
@@ -393,8 +439,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         la.store(smem);
         lb.store(smem + A_ELEMS);
         if (nslabs > 1) {
-            la.template load<false, KTAIL>(kb + BK, ke, g.tbl);
-            lb.template load<REMAP == REMAP_B_K, KTAIL>(kb + BK, ke, g.tbl);
+            int k1 = kb + BK;
+            if constexpr (KSEG) k1 = kseg_k;
+            la.template load<false, KTAIL>(k1, ke, g.tbl);
+            lb.template load<REMAP_BK, KTAIL>(k1, ke, g.tbl);
+            if constexpr (KSEG) kseg_advance();
         }
     }
     __syncthreads();
@@ -407,7 +456,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         const int CUR = s & 1;
         lds_bf16* as_next = smem + (1 - CUR) * STAGE_ELEMS;
         lds_bf16* bs_next = as_next + A_ELEMS;
-        const int k_next = kb + (s + 2) * BK;
+        int k_next = kb + (s + 2) * BK;
+        if constexpr (KSEG) k_next = kseg_k;
         auto move_third = [&](auto third_tag) {   // a third of the slab's chunks: store, then reload
             constexpr int P = decltype(third_tag)::value;
 #pragma unroll
@@ -417,7 +467,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                     if (LOAD) la.template load_one<false, KTAIL>(c, k_next, ke, g.tbl);
                 } else {
                     if (STORE) lb.store_one(c - KA, bs_next);
-                    if (LOAD) lb.template load_one<REMAP == REMAP_B_K, KTAIL>(c - KA, k_next, ke, g.tbl);
+                    if (LOAD) lb.template load_one<REMAP_BK, KTAIL>(c - KA, k_next, ke, g.tbl);
                 }
             }
         };
@@ -433,6 +483,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         __builtin_amdgcn_sched_barrier(0);
         read_frags(1, CUR, 48);
         move_third(std::integral_constant<int, 2>{});
+        if constexpr (KSEG && LOAD) kseg_advance();
         mfma_group(0);
         pace_group<NM, NR, STORE ? NW - 2 * NW / 3 : 0>();
         __builtin_amdgcn_sched_barrier(0);
@@ -455,6 +506,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
     }
     __syncthreads();   // the epilogue reuses the operand buffers
     const int em0 = m0, en0 = n0, esplit = split, eslot = piece_slot;
+    int m_lim = g.M;   // rows of the tile below it are written
+    if constexpr (KSEG) m_lim = mlim;
     // the next tile's first slab arrives under the epilogue
     if constexpr (grouped) {
         have_work = setup_piece();
@@ -545,7 +598,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
         u32x4 zq[CPL];
         auto fetch = [&](int t, int c) {   // zeros for a row outside the problem or outside its segment's slices
             const int m = mrow + t * 32 + c * (64 / CPR);
-            const bool live = m < g.M && n < g.N && (!SEGMENTS || ((rows_alive >> (t * CPL + c)) & 1));
+            const bool live = m < m_lim && n < g.N && (!SEGMENTS || ((rows_alive >> (t * CPL + c)) & 1));
             zq[c] = u32x4{0u, 0u, 0u, 0u};
             if (live) zq[c] = *reinterpret_cast<const u32x4*>(zp);
             zp += zstep;   // chunks are fetched in the order they are stored
@@ -581,7 +634,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                     }
                 }
                 if (t + 1 < MT) fetch(t + 1, c);
-                if (m < g.M && n < g.N) {
+                if (m < m_lim && n < g.N) {
                     store8(cp, v);
                     if (g.colsum) {
 #pragma unroll
@@ -613,7 +666,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_mfma_kernel(GemmArgs g
                 const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
                 v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
                 store8(Pslot + (wm * WTM + t * 32 + r) * BN + wn * WTN + cc, v);
-            } else if (m < g.M && n < g.N) {
+            } else if (m < m_lim && n < g.N) {
                 float v[8];
                 const float4 lo = *reinterpret_cast<const float4*>(stage + r * SST + cc);
                 const float4 hi = *reinterpret_cast<const float4*>(stage + r * SST + cc + 4);
@@ -758,7 +811,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
         if (resident < 8) resident = 8;
     }
     const int splits = g.partial ? g.splits : 1;
-    const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM) * splits;
+    const long tiles = (long)((g.N + BN - 1) / BN) * (REMAP == REMAP_B_KSEG ? g.seg.live_tiles : (g.M + BM - 1) / BM) * splits;
     // persistent: no more workgroups than are resident together; each walks tiles b, b + grid, ...
     const dim3 grid((unsigned)(tiles < resident ? tiles : resident)), block(64 * WGM * WGN);
     launch_kernel(kern, grid, block, lds, s, g);
@@ -846,6 +899,13 @@ hipError_t launch_seg_cfg(const GemmArgs& g, hipStream_t s) {
     const long grid = tiles < resident ? (tiles + 7) / 8 * 8 : resident;
     launch_kernel(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, s, g);
     return hipGetLastError();
+}
+
+// K-segment launch: A row-major, B's k through the remap table; the epilogue is the residual form (FC2 forward) or
+// the generic one (the backward's dv)
+template <int BM, bool B_COL, int EPI>
+hipError_t launch_kseg_cfg(const GemmArgs& g, hipStream_t s) {
+    return launch_cfg<BM, 256, 64, 2, 4, false, B_COL, REMAP_B_KSEG, false, EPI>(g, s);
 }
 
 // K a multiple of 64 (every shape of the model): the slab loads carry no per-chunk k check
@@ -1012,6 +1072,43 @@ hipError_t gemm_mfma_seg_prepare(GemmArgs* g) {
     }
     S.live_tiles = before;
     return g->remap == REMAP_B_N ? hipSuccess : hipErrorNotSupported;   // the gated feed-forward forms
+}
+
+hipError_t launch_gemm_mfma_kseg(const GemmArgs& g, hipStream_t s) {
+    const GemmRowSegments& S = g.seg;
+    if (!gemm_mfma_supported(g) || g.remap != REMAP_B_K || g.a_cs != 1 || g.partial || g.colsum || g.act != ACT_NONE) return hipErrorNotSupported;
+    if (S.n < 1 || S.n > kMaxGemmSegments || S.slice < 64 || S.slice % 64 || g.K % S.slice || g.K / S.slice > 64) return hipErrorNotSupported;
+    const uint64_t all = g.K / S.slice >= 64 ? ~0ull : ((1ull << (g.K / S.slice)) - 1ull);
+    int lo = 0;
+    for (int i = 0; i < S.n; ++i) {
+        if (S.end[i] <= lo || (S.pos[i] & ~all)) return hipErrorNotSupported;
+        lo = S.end[i];
+    }
+    if (lo != g.M) return hipErrorNotSupported;
+    const bool b_col = (g.b_rs != 1);
+    if (!b_col && !residual_only(g)) return hipErrorNotSupported;   // instantiated for FC2 forward ...
+    if (b_col && (g.residual || g.bias)) return hipErrorNotSupported;   // ... and the backward's dv
+    // every segment gets tile rows of its own; the 192-row tile when it fills more of one round of the chip than
+    // the 256-row tile (as pick_tile has it)
+    auto tile_rows = [&](int bm) {
+        long t = 0;
+        for (int i = 0; i < S.n; ++i) t += (S.end[i] - (i ? S.end[i - 1] : 0) + bm - 1) / bm;
+        return t;
+    };
+    const long tn = (g.N + 255) / 256;
+    const long big = tile_rows(256) * tn, mid = tile_rows(192) * tn;
+    const bool t192 = big < 256 && mid <= 256 && mid > big;
+    const int bm = t192 ? 192 : 256;
+    GemmArgs k = g;
+    int t = 0;
+    for (int i = 0; i < kMaxGemmSegments; ++i) {
+        k.seg.row_before[i] = (uint16_t)t;
+        if (i < S.n) t += (S.end[i] - (i ? S.end[i - 1] : 0) + bm - 1) / bm;
+    }
+    if (t > 0xffff) return hipErrorNotSupported;
+    k.seg.live_tiles = t;
+    if (!b_col) return t192 ? launch_kseg_cfg<192, false, EPI_RESIDUAL>(k, s) : launch_kseg_cfg<256, false, EPI_RESIDUAL>(k, s);
+    return t192 ? launch_kseg_cfg<192, true, EPI_ANY>(k, s) : launch_kseg_cfg<256, true, EPI_ANY>(k, s);
 }
 
 hipError_t launch_gemm_mfma_seg(const GemmArgs& g, hipStream_t s) {

@@ -158,6 +158,36 @@ def test_bf16_gated_segments_eight_micro_batches_and_the_fallback_beyond():
     assert n == 0
 
 
+def k_segment_launches(fn):
+    """Runs fn with the library's per-kernel timing on; returns the launches of the GEMMs whose K walk follows the
+    micro-batches' own slices (FC2 forward and the backward's dv)."""
+    import paper_2504_12471_amd as P
+    P.d2ft_timing_enable(True)
+    try:
+        fn()
+        recs = P.d2ft_timing_read(256)
+    finally:
+        P.d2ft_timing_enable(False)
+    return sum(r["launches"] for r in recs if r["name"].endswith("k-segments"))
+
+
+def test_bf16_gated_k_walk_per_micro_batch():
+    """FC2 forward and dv walk, per tile, only the slices of the tile's own micro-batch: micro-batches that start at
+    odd rows, a micro-batch smaller than a tile, one in which nothing is p_f (dv's tiles there walk nothing) and
+    one with a single live subnet; then nine micro-batches, one more than the form takes (the full walk runs)."""
+    w = di.Workload("mb_kseg", 9, 197, 384, 6, 64, 1536, 1, "bf16")
+    ops_mb = [[FULL, FWD, SKIP, FULL, FWD, SKIP],
+              [FWD, SKIP, FWD, SKIP, SKIP, FWD],
+              [SKIP, FULL, FULL, FWD, SKIP, SKIP],
+              [SKIP, SKIP, SKIP, SKIP, SKIP, FULL],
+              [FULL, FULL, FULL, FULL, FULL, FULL]]
+    n = k_segment_launches(lambda: run_mb(w, ops_mb, [3, 1, 2, 1, 2], seed=94, gate=True))
+    assert n == 2
+    ops9 = ops_mb + [ops_mb[0], ops_mb[2], ops_mb[4], ops_mb[1]]
+    n = k_segment_launches(lambda: run_mb(w, ops9, [1, 1, 1, 1, 1, 1, 1, 1, 1], seed=95, gate=True))
+    assert n == 0
+
+
 def test_bf16_union_of_codes_without_a_full_head():
     w = di.Workload("mb_union_fwd", 4, 100, 256, 4, 64, 512, 1, "bf16")
     g, rg = run_mb(w, [[FWD, SKIP, SKIP, FWD], [SKIP, FWD, SKIP, SKIP]], [1, 3], seed=82)
