@@ -377,10 +377,10 @@ hipError_t run_gemm_segments(GemmArgs g, const d2ft_block_desc* d, const MicroMa
     return e;
 }
 
-// A product whose K index runs over the gated slices (FC2 forward, the backward's dv) while the micro-batches have
-// their own codes: A's columns of a slice are zero in the rows of a micro-batch in which the slice does not take
-// part (pos_of[i]: the slices of micro-batch i), so every tile walks only the slices of the micro-batches its rows
-// belong to.  The sums are those of the full walk.  hipErrorNotSupported (nothing launched) if the shape does not fit.
+// A product whose K index runs over the gated slices (FC2 forward, the backward's dv) or over the heads (output
+// projection forward, the backward's du) while the micro-batches have their own codes: A's columns of a slice are
+// zero in the rows of a micro-batch in which the slice does not take part (pos_of[i]: the slices of micro-batch
+// i), so every tile walks only the slices of its own micro-batch.  The sums are those of the full walk.  hipErrorNotSupported (nothing launched) if the shape does not fit.
 hipError_t run_gemm_kseg(GemmArgs g, const d2ft_block_desc* d, const MicroMask& mask, const uint64_t* pos_of, int tokens,
                          int slice, hipStream_t s) {
     if (!on_mfma_path(g, d) || mask.n > kMaxGemmSegments) return hipErrorNotSupported;
@@ -821,7 +821,10 @@ static d2ft_status block_fwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         p.C = (part == PART_ATTN) ? y : (void*)(sv + SL.x1); p.ldc = s.D;
         p.bias = w->b_o;
         p.residual = x; p.ldr = s.D;
-        D2FT_TRY_UNTIMED(run_gemm(p, desc, st));
+        // micro-batches with their own codes: the O block of a skipped pair is zero, so a tile need not walk it
+        hipError_t ek = mask ? run_gemm_kseg(p, desc, *mask, mask->live, s.T, 64, st) : hipErrorNotSupported;
+        if (ek == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(p, desc, st));
+        else if (ek != hipSuccess) return D2FT_EDEVICE;
         x1 = p.C;
         // the backward multiplies the saved O of the p_f positions over the whole batch: a pair that
         // was forward-only in its micro-batch must not reach the gradient of W_o
@@ -1331,7 +1334,10 @@ static d2ft_status block_bwd_impl(const d2ft_block_desc* desc, const d2ft_block_
         g.b_rs = s.D; g.b_cs = 1;
         g.M = M; g.N = s.D; g.K = nf * 192;
         g.C = ws + WL.du; g.ldc = s.D;
-        D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        // micro-batches with their own codes: the dQKV block of a pair that is not p_f is zero
+        hipError_t ek = (mask && s.r == 0) ? run_gemm_kseg(g, desc, *mask, mask->full, s.T, 192, st) : hipErrorNotSupported;
+        if (ek == hipErrorNotSupported) D2FT_TRY_UNTIMED(run_gemm(g, desc, st));
+        else if (ek != hipSuccess) return D2FT_EDEVICE;
     }
     if (grads->ln1_g || grads->ln1_b) {
         const int chunks = pick_chunks(s.M);

@@ -172,7 +172,8 @@ def k_segment_launches(fn):
 
 
 def test_bf16_gated_k_walk_per_micro_batch():
-    """FC2 forward and dv walk, per tile, only the slices of the tile's own micro-batch: micro-batches that start at
+    """FC2 forward and dv (and the output projection and du over the heads) walk, per tile, only the slices of the
+    tile's own micro-batch: micro-batches that start at
     odd rows, a micro-batch smaller than a tile, one in which nothing is p_f (dv's tiles there walk nothing) and
     one with a single live subnet; then nine micro-batches, one more than the form takes (the full walk runs)."""
     w = di.Workload("mb_kseg", 9, 197, 384, 6, 64, 1536, 1, "bf16")
@@ -182,7 +183,9 @@ def test_bf16_gated_k_walk_per_micro_batch():
               [SKIP, SKIP, SKIP, SKIP, SKIP, FULL],
               [FULL, FULL, FULL, FULL, FULL, FULL]]
     n = k_segment_launches(lambda: run_mb(w, ops_mb, [3, 1, 2, 1, 2], seed=94, gate=True))
-    assert n == 2
+    assert n == 4   # with the output projection and du, whose K index runs over the heads
+    n = k_segment_launches(lambda: run_mb(w, ops_mb, [3, 1, 2, 1, 2], seed=96))
+    assert n == 2   # no gated slices: those two alone
     ops9 = ops_mb + [ops_mb[0], ops_mb[2], ops_mb[4], ops_mb[1]]
     n = k_segment_launches(lambda: run_mb(w, ops9, [1, 1, 1, 1, 1, 1, 1, 1, 1], seed=95, gate=True))
     assert n == 0
